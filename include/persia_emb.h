@@ -1,0 +1,169 @@
+/* persia_emb.h -- C ABI of the MI355X embedding hot path.
+ *
+ * The library keeps the embedding parameter w^emb of a deep recommender resident in HBM
+ * and implements the two operations the paper's training loop performs on it
+ * (section 2.1: y = NN_{w_nn}(lookup_{w_emb}(x^ID), x^NID); section 3.1 / Algorithm 1:
+ * get(x^ID) in the forward task, put(x^ID, F'^emb) plus the optimizer Omega^emb in the
+ * backward task):
+ *
+ *   emb_lookup_pool      get + the embedding worker's aggregation (section 4.1, step 4):
+ *                        hash every ID to a row, gather the rows, sum them per slot.
+ *   emb_backward_update  put + update (section 4.1, step 7; Algorithm 1 backward task;
+ *                        equation (2)): turn the gradient of the pooled activations into
+ *                        one gradient per touched row, via the unique-key index form of
+ *                        the batch (section 4.2.3, "Lossless compression"), and apply the
+ *                        row's optimizer, whose state is stored beside the row
+ *                        (section 4.2.2).
+ *
+ * Conventions
+ *   - Every function returns an emb_status (0 = ok, negative = error) and never throws or
+ *     aborts; on error outputs are untouched and emb_last_error() describes the failure.
+ *   - "device" pointers are HIP device memory on the context's GPU, owned by the caller
+ *     (e.g. torch tensors); "host" pointers are ordinary memory.  The library owns the
+ *     tables, the optimizer state and its workspace, all sized in emb_create, so the hot
+ *     calls allocate nothing.
+ *   - Hot calls (emb_lookup_pool, emb_hash_rows, emb_backward_update) only enqueue work on
+ *     the given hipStream_t (passed as void*, NULL = the null stream) and return; caller
+ *     buffers must stay valid until the stream has passed the call.  The functions marked
+ *     "synchronous" wait for the device.
+ *   - A batch is CSR over bags: bag index = b * num_slots + s for sample b and slot s;
+ *     ids[offsets[bag] .. offsets[bag+1]) are the bag's 64-bit IDs.  offsets must be
+ *     non-decreasing with offsets[0] = 0 and offsets[B*S] = num_ids; this is a caller
+ *     contract and is not validated on the hot path.
+ *   - Pooled activations and their gradient are fp32, row-major [B, W] with
+ *     W = sum over slots of the slot's table dim; slot s occupies columns
+ *     [col(s), col(s) + dim) where col(s) is the sum of the dims of slots before it.
+ *   - A context is not thread-safe; calls on one context must be issued from one thread
+ *     (or externally serialised).  Two hot calls on different streams may overlap on the
+ *     device only if the caller orders them as it needs (bounded-staleness training,
+ *     section 5: a lookup may read rows an earlier update is still writing).
+ */
+#ifndef PERSIA_EMB_H
+#define PERSIA_EMB_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct emb_ctx emb_ctx; /* opaque */
+
+typedef enum { EMB_OK = 0, EMB_EINVAL = -1, EMB_ENOMEM = -2, EMB_EDEVICE = -3, EMB_ESTATE = -4 } emb_status;
+typedef enum { EMB_F32 = 0, EMB_BF16 = 1 } emb_dtype;          /* table storage type */
+typedef enum { EMB_OPT_SGD = 0, EMB_OPT_ROWWISE_ADAGRAD = 1 } emb_opt_kind;
+typedef enum { EMB_HASH_IDENTITY_MOD = 0, EMB_HASH_MIX_MOD = 1 } emb_hash_kind;
+
+/* One embedding table: `rows` x `dim`, row-major, rows contiguous.
+ * dim must be one of 8, 16, 32, 64, 128; sum of rows over all tables must be < 2^31. */
+typedef struct {
+  uint64_t rows;
+  uint32_t dim;
+  int32_t dtype; /* emb_dtype */
+} emb_table_desc;
+
+/* One ID-type feature group (section 2.1): which table it reads and the salt that makes
+ * its IDs a key space of their own. */
+typedef struct {
+  uint32_t table;
+  uint32_t reserved; /* must be 0 */
+  uint64_t salt;
+} emb_slot_desc;
+
+/* hash:  EMB_HASH_IDENTITY_MOD: row = id mod rows.
+ *        EMB_HASH_MIX_MOD:      row = mix64(id + salt) mod rows, with
+ *          mix64(z): z ^= z>>31; z *= 0x9FB21C651E98DF25; z ^= z>>29;
+ *                    z *= 0xC2B2AE3D27D4EB4F; z ^= z>>32   (arithmetic mod 2^64).
+ *        Distinct IDs that hash to one row share it.
+ * opt:   EMB_OPT_SGD:             w <- w - lr * G
+ *        EMB_OPT_ROWWISE_ADAGRAD: a <- a + mean_d(G_d^2);  w_d <- w_d - lr * G_d / (sqrt(a) + eps)
+ *        with G the sum of the upstream gradients of all occurrences of the row in the
+ *        batch, a one fp32 accumulator per row (initially acc_init); one application per
+ *        unique row per batch.  bf16 tables round the new row to nearest-even.
+ * init:  element d of row r of table t starts at lo + (hi-lo) * k / 2^24, k = the top 24 bits of
+ *        mix64(mix64(init_seed + (t+1)*0x9E3779B97F4A7C15) + r*dim + d), evaluated as
+ *        float(k - 2^23) * ((hi-lo) * 2^-24) + (hi+lo)/2 with separate fp32 multiply and add.
+ * max_batch / max_ids bound batch_size and num_ids of every later call (workspace sizing). */
+typedef struct {
+  uint32_t num_tables;
+  uint32_t num_slots;
+  const emb_table_desc* tables; /* host, [num_tables] */
+  const emb_slot_desc* slots;   /* host, [num_slots]  */
+  int32_t hash;                 /* emb_hash_kind */
+  int32_t opt;                  /* emb_opt_kind  */
+  float lr, eps, acc_init;
+  float init_lo, init_hi;
+  int32_t device;               /* HIP device ordinal */
+  uint64_t init_seed;
+  uint64_t max_ids;
+  uint32_t max_batch;
+  uint32_t reserved;            /* must be 0 */
+} emb_config;
+
+typedef struct {
+  uint32_t batch_size;     /* B */
+  uint32_t reserved;       /* must be 0 */
+  uint64_t num_ids;        /* N = offsets[B * num_slots] */
+  const uint64_t* ids;     /* device, [N] */
+  const int32_t* offsets;  /* device, [B * num_slots + 1] */
+} emb_batch;
+
+/* Allocates and initialises tables, optimizer state and workspace on cfg->device
+ * (synchronous).  On failure *out is untouched and emb_last_error(NULL) has the reason. */
+int emb_create(const emb_config* cfg, emb_ctx** out);
+int emb_destroy(emb_ctx* ctx); /* synchronous; frees everything the context owns */
+
+/* Forward (section 2.1 lookup; Algorithm 1 forward task; section 4.1 step 4):
+ * pooled[b, col(s) + d] = sum over ids i of bag (b, s) of W_table(s)[row(i), d], duplicates
+ * counted with multiplicity, empty bags give zeros.  pooled: device, fp32 [B, W], written whole. */
+int emb_lookup_pool(emb_ctx* ctx, const emb_batch* batch, float* pooled, void* hip_stream);
+
+/* The hash step alone (section 4.2.2: the global hashing function that locates a parameter):
+ * rows_out[i] = row of ids[i] in the table of its slot.  rows_out: device, uint32 [N]. */
+int emb_hash_rows(emb_ctx* ctx, const emb_batch* batch, uint32_t* rows_out, void* hip_stream);
+
+/* Backward + update (section 4.1 step 7; Algorithm 1 backward task; equation (2)) for the same
+ * batch the forward saw.  d_pooled: device, fp32 [B, W], gradient of the loss w.r.t. pooled.
+ * Builds the index form of the batch -- unique (table,row) keys ascending, and for each key
+ * the bag indices holding it in batch order -- sums d_pooled over each key's bags, and applies
+ * the optimizer once per unique row.  Rows not in the batch are not touched.  The index form
+ * stays in the context's workspace until the next call on the context. */
+int emb_backward_update(emb_ctx* ctx, const emb_batch* batch, const float* d_pooled, void* hip_stream);
+
+/* Inspection of the index form left by the last emb_backward_update (synchronous; for tests
+ * and benchmarks).  keys[u] = (table << 32) | row, strictly ascending; seg_off[U+1] with
+ * seg_off[0] = 0, seg_off[U] = N; seg_bags[N]: bag indices, non-decreasing inside a segment.
+ * Host buffers; any of the three may be NULL. */
+int emb_dedup_sizes(emb_ctx* ctx, uint64_t* num_unique, uint64_t* num_ids);
+int emb_read_dedup(emb_ctx* ctx, uint64_t* keys, uint32_t* seg_off, uint32_t* seg_bags);
+
+/* Copy rows of a table, widened to fp32, and their optimizer accumulators to the host /
+ * overwrite them from the host (values rounded to the table's storage type).  Synchronous.
+ * rows: host [n]; w: host fp32 [n, dim] or NULL; acc: host fp32 [n] or NULL. */
+int emb_read_rows(emb_ctx* ctx, uint32_t table, const uint64_t* rows, uint64_t n, float* w, float* acc);
+int emb_write_rows(emb_ctx* ctx, uint32_t table, const uint64_t* rows, uint64_t n, const float* w, const float* acc);
+
+/* Device pointers to a table's storage and accumulators (library-owned; for checksums). */
+int emb_table_ptr(emb_ctx* ctx, uint32_t table, void** w_dev, float** acc_dev);
+
+/* Per-stage device timing.  While enabled, every hot call brackets each kernel stage with HIP
+ * events on the call's stream; emb_read_stage_ms waits for the device and returns, per stage,
+ * the accumulated milliseconds and number of launches since the last emb_reset_stage_ms.
+ * Stage names: emb_stage_name(i) for 0 <= i < emb_stage_count(). */
+int emb_set_profiling(emb_ctx* ctx, int enabled);
+int emb_stage_count(void);
+const char* emb_stage_name(int stage);
+int emb_read_stage_ms(emb_ctx* ctx, float* ms, uint32_t* launches); /* host arrays [emb_stage_count()] */
+int emb_reset_stage_ms(emb_ctx* ctx);
+
+/* Bytes of device memory the context holds (tables, state, workspace). */
+uint64_t emb_device_bytes(emb_ctx* ctx);
+
+/* Message of the last failed call on ctx (or of the last failed emb_create if ctx is NULL).
+ * The pointer stays valid until the next failing call. */
+const char* emb_last_error(emb_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PERSIA_EMB_H */

@@ -1,0 +1,225 @@
+"""Thin ctypes binding over the C-ABI library (include/persia_emb.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels.  torch is used for
+device memory and streams; tensors are passed to the library as raw device pointers.  There is no
+CPU fallback: if the built library is missing, importing a symbol from it raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+import torch  # imported before the library so that both use the HIP runtime torch ships
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpersia_emb.so")
+
+EMB_OK, EMB_EINVAL, EMB_ENOMEM, EMB_EDEVICE, EMB_ESTATE = 0, -1, -2, -3, -4
+_STATUS = {EMB_EINVAL: "EMB_EINVAL", EMB_ENOMEM: "EMB_ENOMEM", EMB_EDEVICE: "EMB_EDEVICE", EMB_ESTATE: "EMB_ESTATE"}
+
+
+class emb_table_desc(C.Structure):
+    _fields_ = [("rows", C.c_uint64), ("dim", C.c_uint32), ("dtype", C.c_int32)]
+
+
+class emb_slot_desc(C.Structure):
+    _fields_ = [("table", C.c_uint32), ("reserved", C.c_uint32), ("salt", C.c_uint64)]
+
+
+class emb_config(C.Structure):
+    _fields_ = [("num_tables", C.c_uint32), ("num_slots", C.c_uint32),
+                ("tables", C.POINTER(emb_table_desc)), ("slots", C.POINTER(emb_slot_desc)),
+                ("hash", C.c_int32), ("opt", C.c_int32),
+                ("lr", C.c_float), ("eps", C.c_float), ("acc_init", C.c_float),
+                ("init_lo", C.c_float), ("init_hi", C.c_float), ("device", C.c_int32),
+                ("init_seed", C.c_uint64), ("max_ids", C.c_uint64),
+                ("max_batch", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+class emb_batch(C.Structure):
+    _fields_ = [("batch_size", C.c_uint32), ("reserved", C.c_uint32), ("num_ids", C.c_uint64),
+                ("ids", C.c_void_p), ("offsets", C.c_void_p)]
+
+
+class EmbError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"{_STATUS.get(code, code)}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Loads the in-tree library; raises if it has not been built (python -m paper_2111_05897_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} is missing: build it with `python paper_2111_05897_amd/build.py`")
+    L = C.CDLL(LIB_PATH)
+    vp, u32, u64, i32 = C.c_void_p, C.c_uint32, C.c_uint64, C.c_int
+    L.emb_create.argtypes = [C.POINTER(emb_config), C.POINTER(vp)]
+    L.emb_destroy.argtypes = [vp]
+    L.emb_lookup_pool.argtypes = [vp, C.POINTER(emb_batch), vp, vp]
+    L.emb_hash_rows.argtypes = [vp, C.POINTER(emb_batch), vp, vp]
+    L.emb_backward_update.argtypes = [vp, C.POINTER(emb_batch), vp, vp]
+    L.emb_dedup_sizes.argtypes = [vp, C.POINTER(u64), C.POINTER(u64)]
+    L.emb_read_dedup.argtypes = [vp, vp, vp, vp]
+    L.emb_read_rows.argtypes = [vp, u32, vp, u64, vp, vp]
+    L.emb_write_rows.argtypes = [vp, u32, vp, u64, vp, vp]
+    L.emb_table_ptr.argtypes = [vp, u32, C.POINTER(vp), C.POINTER(vp)]
+    L.emb_set_profiling.argtypes = [vp, i32]
+    L.emb_stage_count.argtypes = []
+    L.emb_stage_name.argtypes = [i32]
+    L.emb_stage_name.restype = C.c_char_p
+    L.emb_read_stage_ms.argtypes = [vp, vp, vp]
+    L.emb_reset_stage_ms.argtypes = [vp]
+    L.emb_device_bytes.argtypes = [vp]
+    L.emb_device_bytes.restype = u64
+    L.emb_last_error.argtypes = [vp]
+    L.emb_last_error.restype = C.c_char_p
+    for name in ("emb_create", "emb_destroy", "emb_lookup_pool", "emb_hash_rows", "emb_backward_update",
+                 "emb_dedup_sizes", "emb_read_dedup", "emb_read_rows", "emb_write_rows", "emb_table_ptr",
+                 "emb_set_profiling", "emb_stage_count", "emb_read_stage_ms", "emb_reset_stage_ms"):
+        getattr(L, name).restype = C.c_int
+    _lib = L
+    return L
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+class DeviceBatch:
+    """A CSR batch resident on the GPU: ids uint64 [N] (held as int64 bits), offsets int32 [B*S+1]."""
+
+    def __init__(self, batch_size: int, ids: np.ndarray, offsets: np.ndarray, device="cuda:0"):
+        ids = np.ascontiguousarray(ids, dtype=np.uint64)
+        offsets = np.ascontiguousarray(offsets, dtype=np.int32)
+        self.batch_size = int(batch_size)
+        self.num_ids = int(offsets[-1]) if len(offsets) else 0
+        assert self.num_ids == len(ids)
+        self.ids = torch.from_numpy(ids.view(np.int64)).to(device)
+        self.offsets = torch.from_numpy(offsets).to(device)
+        self.c = emb_batch(self.batch_size, 0, self.num_ids, self.ids.data_ptr() if self.num_ids else None,
+                           self.offsets.data_ptr())
+
+
+class EmbContext:
+    """Owns one emb_ctx.  Method names mirror the C entry points."""
+
+    def __init__(self, tables: Sequence[Tuple[int, int, int]], slots: Sequence[Tuple[int, int]], hash_kind: int,
+                 opt: int, lr: float, eps: float, acc_init: float, init_seed: int, init_lo: float, init_hi: float,
+                 max_batch: int, max_ids: int, device: int = 0):
+        self.L = load_library()
+        self.tables = [tuple(t) for t in tables]
+        self.slots = [tuple(s) for s in slots]
+        self.device = device
+        self._t = (emb_table_desc * len(tables))(*[emb_table_desc(r, d, dt) for r, d, dt in tables])
+        self._s = (emb_slot_desc * len(slots))(*[emb_slot_desc(t, 0, salt) for t, salt in slots])
+        cfg = emb_config(len(tables), len(slots), self._t, self._s, hash_kind, opt, lr, eps, acc_init, init_lo, init_hi,
+                         device, init_seed, max_ids, max_batch, 0)
+        h = C.c_void_p()
+        rc = self.L.emb_create(C.byref(cfg), C.byref(h))
+        if rc:
+            raise EmbError(rc, self.L.emb_last_error(None).decode())
+        self.h = h
+        self.S = len(slots)
+        self.width = sum(self.tables[t][1] for t, _ in slots)
+
+    @classmethod
+    def from_config(cls, cfg, max_batch: int, max_ids: int, device: int = 0):
+        """cfg: workload.EmbConfig (duck-typed)."""
+        return cls([(t.rows, t.dim, t.dtype) for t in cfg.tables], [(s.table, s.salt) for s in cfg.slots],
+                   cfg.hash_kind, cfg.opt, cfg.lr, cfg.eps, cfg.acc_init, cfg.init_seed, cfg.init_lo, cfg.init_hi,
+                   max_batch, max_ids, device)
+
+    def _ck(self, rc: int):
+        if rc:
+            raise EmbError(rc, self.L.emb_last_error(self.h).decode())
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.L.emb_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- hot calls (enqueue only) ----
+    def emb_lookup_pool(self, batch: DeviceBatch, pooled: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+        if pooled is None:
+            pooled = torch.empty((batch.batch_size, self.width), dtype=torch.float32, device=batch.offsets.device)
+        assert pooled.is_contiguous() and pooled.dtype == torch.float32
+        assert pooled.shape == (batch.batch_size, self.width)
+        self._ck(self.L.emb_lookup_pool(self.h, C.byref(batch.c), pooled.data_ptr(), _stream_ptr(stream)))
+        return pooled
+
+    def emb_hash_rows(self, batch: DeviceBatch, stream=None) -> torch.Tensor:
+        rows = torch.empty(max(batch.num_ids, 1), dtype=torch.int32, device=batch.offsets.device)
+        self._ck(self.L.emb_hash_rows(self.h, C.byref(batch.c), rows.data_ptr(), _stream_ptr(stream)))
+        return rows[: batch.num_ids]
+
+    def emb_backward_update(self, batch: DeviceBatch, d_pooled: torch.Tensor, stream=None) -> None:
+        assert d_pooled.is_contiguous() and d_pooled.dtype == torch.float32
+        assert d_pooled.shape == (batch.batch_size, self.width)
+        self._ck(self.L.emb_backward_update(self.h, C.byref(batch.c), d_pooled.data_ptr(), _stream_ptr(stream)))
+
+    # ---- inspection (synchronous) ----
+    def emb_dedup_sizes(self) -> Tuple[int, int]:
+        U, N = C.c_uint64(), C.c_uint64()
+        self._ck(self.L.emb_dedup_sizes(self.h, C.byref(U), C.byref(N)))
+        return U.value, N.value
+
+    def emb_read_dedup(self):
+        U, N = self.emb_dedup_sizes()
+        keys = np.empty(U, dtype=np.uint64)
+        seg_off = np.empty(U + 1, dtype=np.uint32)
+        seg_bags = np.empty(N, dtype=np.uint32)
+        self._ck(self.L.emb_read_dedup(self.h, keys.ctypes.data, seg_off.ctypes.data, seg_bags.ctypes.data))
+        return keys, seg_off, seg_bags
+
+    def emb_read_rows(self, table: int, rows) -> Tuple[np.ndarray, np.ndarray]:
+        rows = np.ascontiguousarray(rows, dtype=np.uint64)
+        w = np.empty((len(rows), self.tables[table][1]), dtype=np.float32)
+        acc = np.empty(len(rows), dtype=np.float32)
+        self._ck(self.L.emb_read_rows(self.h, table, rows.ctypes.data, len(rows), w.ctypes.data, acc.ctypes.data))
+        return w, acc
+
+    def emb_write_rows(self, table: int, rows, w, acc=None) -> None:
+        rows = np.ascontiguousarray(rows, dtype=np.uint64)
+        w = np.ascontiguousarray(w, dtype=np.float32)
+        assert w.shape == (len(rows), self.tables[table][1])
+        ap = None
+        if acc is not None:
+            acc = np.ascontiguousarray(acc, dtype=np.float32)
+            ap = acc.ctypes.data
+        self._ck(self.L.emb_write_rows(self.h, table, rows.ctypes.data, len(rows), w.ctypes.data, ap))
+
+    def emb_table_ptr(self, table: int) -> Tuple[int, int]:
+        w, a = C.c_void_p(), C.c_void_p()
+        self._ck(self.L.emb_table_ptr(self.h, table, C.byref(w), C.byref(a)))
+        return w.value, a.value
+
+    def emb_set_profiling(self, enabled: bool) -> None:
+        self._ck(self.L.emb_set_profiling(self.h, 1 if enabled else 0))
+
+    def emb_reset_stage_ms(self) -> None:
+        self._ck(self.L.emb_reset_stage_ms(self.h))
+
+    def emb_read_stage_ms(self) -> dict:
+        n = self.L.emb_stage_count()
+        ms = (C.c_float * n)()
+        cnt = (C.c_uint32 * n)()
+        self._ck(self.L.emb_read_stage_ms(self.h, ms, cnt))
+        return {self.L.emb_stage_name(i).decode(): (float(ms[i]), int(cnt[i])) for i in range(n)}
+
+    def emb_device_bytes(self) -> int:
+        return int(self.L.emb_device_bytes(self.h))

@@ -1,0 +1,316 @@
+// Backward after the dedup: segmented reduction of the upstream gradient over the sorted
+// occurrences, fused with the row-wise optimizer update.
+//
+// The sorted occurrence list is cut into fixed tiles of kTile entries, one lane-group per tile
+// (each lane owns 4 of the row's D elements), so work per group is constant however skewed the
+// key frequencies are.  A group walks its tile in order, summing d_pooled rows of the bags it
+// meets; when the key changes, the finished run is a whole segment unless it touches a tile edge:
+//   - a run that began before the tile is stored as a partial in slot first[tile];
+//   - otherwise a run that continues past the tile is stored in slot last[tile];
+//   - every other run is a complete segment and the optimizer is applied to its row at once.
+// Segments that span tiles are listed by find_multi and finished by the fix-up kernel, which adds
+// last[t0], first[t0+1], ..., first[t1] in a fixed order and then applies the optimizer.  No float
+// atomics: the summation order is a function of the batch alone, so results are reproducible.
+#include "device_utils.h"
+#include "launch.h"
+
+namespace pemb {
+namespace {
+
+__device__ __forceinline__ float4 add4(float4 a, float4 b) {
+  return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w);
+}
+
+// Row update by a group of LG lanes; lane owns elements [4*lane, 4*lane+4) and G holds its part of
+// the row's gradient.  OPT 0: SGD.  OPT 1: row-wise Adagrad (mean of G^2 over the row feeds one
+// accumulator; eps outside the square root).
+template <typename T, int D, int OPT>
+__device__ __forceinline__ void apply_update(T* __restrict__ w, float* __restrict__ accs, uint32_t row, float4 G,
+                                             int lane, float lr, float eps) {
+  constexpr int LG = D / 4;
+  T* p = w + (size_t)row * D + lane * 4;
+  float4 v = load_frag4(p);
+  if constexpr (OPT == 0) {
+    v.x = fmaf(-lr, G.x, v.x);
+    v.y = fmaf(-lr, G.y, v.y);
+    v.z = fmaf(-lr, G.z, v.z);
+    v.w = fmaf(-lr, G.w, v.w);
+  } else {
+    float sq = G.x * G.x + G.y * G.y + G.z * G.z + G.w * G.w;
+#pragma unroll
+    for (int m = LG / 2; m >= 1; m >>= 1) sq += __shfl_xor(sq, m);
+    const float a = accs[row] + sq * (1.0f / D);
+    const float step = lr / (sqrtf(a) + eps);
+    v.x = fmaf(-step, G.x, v.x);
+    v.y = fmaf(-step, G.y, v.y);
+    v.z = fmaf(-step, G.z, v.z);
+    v.w = fmaf(-step, G.w, v.w);
+    if (lane == 0) accs[row] = a;
+  }
+  store_frag4(p, v);
+}
+
+struct TileArgs {
+  const uint32_t* keys;
+  const uint32_t* bags;
+  uint32_t n;
+  const float* d_pooled;
+  uint32_t S, width;
+  const uint32_t* slot_col;
+  int uniform;
+  float* partials;
+  uint32_t pstride;
+  const uint32_t* range;
+  void* w;
+  float* accs;
+  uint32_t key_base;
+  float lr, eps;
+};
+
+template <int D>
+__device__ __forceinline__ const float* grad_ptr(const TileArgs& a, uint32_t bag, int lane) {
+  if (a.uniform) return a.d_pooled + (size_t)bag * D + lane * 4;
+  const uint32_t b = bag / a.S;
+  const uint32_t s = bag - b * a.S;
+  return a.d_pooled + (size_t)b * a.width + a.slot_col[s] + lane * 4;
+}
+
+template <typename T, int D, int OPT>
+__global__ __launch_bounds__(kBlock) void k_tile_reduce_update(TileArgs a) {
+  constexpr int LG = D / 4;
+  constexpr int GPB = kBlock / LG;
+  const uint32_t tile = blockIdx.x * GPB + threadIdx.x / LG;
+  const int lane = threadIdx.x % LG;
+  const uint64_t p0_64 = (uint64_t)tile * kTile;
+  if (p0_64 >= a.n) return;
+  const uint32_t p0 = (uint32_t)p0_64;
+  const uint32_t p1 = (a.n - p0 < kTile) ? a.n : p0 + kTile;
+  uint32_t q0 = p0, q1 = p1;
+  if (a.range) {  // several tables: only this table's stretch of the sorted list
+    const uint32_t rb = a.range[0], re = a.range[1];
+    q0 = q0 > rb ? q0 : rb;
+    q1 = q1 < re ? q1 : re;
+    if (q0 >= q1) return;
+  }
+  const uint32_t* __restrict__ keys = a.keys;
+  const uint32_t* __restrict__ bags = a.bags;
+  T* w = reinterpret_cast<T*>(a.w);
+
+  const bool cont_in = (q0 == p0) && p0 > 0 && keys[p0 - 1] == keys[p0];
+  const bool cont_out = (q1 == p1) && p1 < a.n && keys[p1] == keys[p1 - 1];
+
+  uint32_t cur = keys[q0];
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  bool first = true;
+
+  for (uint32_t i = q0; i < q1; i += 4) {
+    uint32_t k[4];
+    float4 g[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const bool ok = i + j < q1;
+      k[j] = ok ? keys[i + j] : cur;
+      const uint32_t bag = ok ? bags[i + j] : 0u;
+      g[j] = ok ? load_frag4(grad_ptr<D>(a, bag, lane)) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (i + j < q1) {
+        if (k[j] != cur) {  // the run of `cur` ended inside the tile
+          if (first && cont_in)
+            store_frag4(a.partials + (size_t)(2 * tile) * a.pstride + lane * 4, acc);
+          else
+            apply_update<T, D, OPT>(w, a.accs, cur - a.key_base, acc, lane, a.lr, a.eps);
+          first = false;
+          cur = k[j];
+          acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        acc = add4(acc, g[j]);
+      }
+    }
+  }
+  if (first && cont_in)
+    store_frag4(a.partials + (size_t)(2 * tile) * a.pstride + lane * 4, acc);
+  else if (cont_out)
+    store_frag4(a.partials + (size_t)(2 * tile + 1) * a.pstride + lane * 4, acc);
+  else
+    apply_update<T, D, OPT>(w, a.accs, cur - a.key_base, acc, lane, a.lr, a.eps);
+}
+
+// Thread per unique key: list the segments that cross a tile edge.
+__global__ __launch_bounds__(kBlock) void k_find_multi(const uint32_t* __restrict__ seg_off,
+                                                       uint32_t* __restrict__ counters,
+                                                       uint32_t* __restrict__ multi_list) {
+  const uint32_t u = blockIdx.x * kBlock + threadIdx.x;
+  if (u >= counters[0]) return;
+  const uint32_t s = seg_off[u], e = seg_off[u + 1];
+  if (s / kTile != (e - 1) / kTile) multi_list[atomicAdd(&counters[1], 1u)] = u;
+}
+
+struct FixupArgs {
+  const uint32_t* unique_keys;
+  const uint32_t* seg_off;
+  const uint32_t* counters;
+  const uint32_t* multi_list;
+  const float* partials;
+  uint32_t pstride;
+  void* w;
+  float* accs;
+  uint32_t key_base;
+  uint64_t rows;
+  float lr, eps;
+};
+
+// Block per listed segment (grid-stride).  Group g adds partials g, g+NG, ... of the segment in
+// order; the NG group sums are then added in group order and the row is updated.
+template <typename T, int D, int OPT>
+__global__ __launch_bounds__(kBlock) void k_fixup(FixupArgs a) {
+  constexpr int LG = D / 4;
+  constexpr int NG = kBlock / LG;
+  __shared__ float s_part[NG][D];
+  const int g = threadIdx.x / LG, lane = threadIdx.x % LG;
+  const uint32_t count = a.counters[1];
+  T* w = reinterpret_cast<T*>(a.w);
+  for (uint32_t e = blockIdx.x; e < count; e += gridDim.x) {
+    const uint32_t u = a.multi_list[e];
+    const uint32_t key = a.unique_keys[u];
+    if (key < a.key_base || (uint64_t)(key - a.key_base) >= a.rows) continue;  // another table's row
+    const uint32_t s = a.seg_off[u], end = a.seg_off[u + 1];
+    const uint32_t t0 = s / kTile, t1 = (end - 1) / kTile;
+    const uint32_t np = t1 - t0 + 1;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (uint32_t k = g; k < np; k += NG) {
+      const size_t slot = (k == 0) ? (size_t)2 * t0 + 1 : (size_t)2 * (t0 + k);
+      acc = add4(acc, load_frag4(a.partials + slot * a.pstride + lane * 4));
+    }
+    store_frag4(&s_part[g][lane * 4], acc);
+    __syncthreads();
+    if (g == 0) {
+      float4 tot = make_float4(0.f, 0.f, 0.f, 0.f);
+      const int ng = np < (uint32_t)NG ? (int)np : NG;
+      for (int gg = 0; gg < ng; ++gg) tot = add4(tot, load_frag4(&s_part[gg][lane * 4]));
+      apply_update<T, D, OPT>(w, a.accs, key - a.key_base, tot, lane, a.lr, a.eps);
+    }
+    __syncthreads();
+  }
+}
+
+// Thread t <= num_tables: ranges[t] = first position whose key >= key_base[t] (ranges[num_tables] = n).
+__global__ void k_table_ranges(const uint32_t* __restrict__ keys, uint32_t n, const uint32_t* __restrict__ key_base,
+                               uint32_t num_tables, uint32_t* __restrict__ ranges) {
+  const uint32_t t = threadIdx.x;
+  if (t > num_tables) return;
+  if (t == num_tables) {
+    ranges[t] = n;
+    return;
+  }
+  const uint32_t kb = key_base[t];
+  uint32_t lo = 0, hi = n;
+  while (lo < hi) {
+    const uint32_t mid = lo + (hi - lo) / 2;
+    if (keys[mid] < kb) lo = mid + 1;
+    else hi = mid;
+  }
+  ranges[t] = lo;
+}
+
+template <typename T, int D>
+hipError_t launch_tile_td(const TileArgs& a, int opt, hipStream_t stream) {
+  constexpr int GPB = kBlock / (D / 4);
+  const uint32_t tiles = (a.n + kTile - 1) / kTile;
+  const uint32_t grid = (tiles + GPB - 1) / GPB;
+  if (opt == 0)
+    hipLaunchKernelGGL((k_tile_reduce_update<T, D, 0>), dim3(grid), dim3(kBlock), 0, stream, a);
+  else
+    hipLaunchKernelGGL((k_tile_reduce_update<T, D, 1>), dim3(grid), dim3(kBlock), 0, stream, a);
+  return hipGetLastError();
+}
+
+template <typename T, int D>
+hipError_t launch_fixup_td(const FixupArgs& a, int opt, uint32_t grid, hipStream_t stream) {
+  if (opt == 0)
+    hipLaunchKernelGGL((k_fixup<T, D, 0>), dim3(grid), dim3(kBlock), 0, stream, a);
+  else
+    hipLaunchKernelGGL((k_fixup<T, D, 1>), dim3(grid), dim3(kBlock), 0, stream, a);
+  return hipGetLastError();
+}
+
+#define PEMB_DIM_SWITCH(T, dim, FN, ...)             \
+  switch (dim) {                                     \
+    case 8: return FN<T, 8>(__VA_ARGS__);            \
+    case 16: return FN<T, 16>(__VA_ARGS__);          \
+    case 32: return FN<T, 32>(__VA_ARGS__);          \
+    case 64: return FN<T, 64>(__VA_ARGS__);          \
+    case 128: return FN<T, 128>(__VA_ARGS__);        \
+    default: return hipErrorInvalidValue;            \
+  }
+
+}  // namespace
+
+hipError_t launch_table_ranges(const uint32_t* keys, uint32_t n, const uint32_t* key_base_dev, uint32_t num_tables,
+                               uint32_t* ranges, hipStream_t stream) {
+  if (num_tables + 1 > 1024) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_table_ranges, dim3(1), dim3(num_tables + 1), 0, stream, keys, n, key_base_dev, num_tables,
+                     ranges);
+  return hipGetLastError();
+}
+
+hipError_t launch_tile_reduce_update(const TableView& t, const BackwardArgs& b, hipStream_t stream) {
+  if (b.n == 0) return hipSuccess;
+  TileArgs a;
+  a.keys = b.keys;
+  a.bags = b.bags;
+  a.n = b.n;
+  a.d_pooled = b.d_pooled;
+  a.S = b.S;
+  a.width = b.width;
+  a.slot_col = b.slot_col;
+  a.uniform = b.uniform;
+  a.partials = b.partials;
+  a.pstride = b.pstride;
+  a.range = b.range;
+  a.w = t.w;
+  a.accs = t.acc;
+  a.key_base = t.key_base;
+  a.lr = b.lr;
+  a.eps = b.eps;
+  if (t.dtype == 1) {
+    PEMB_DIM_SWITCH(bf16_t, t.dim, launch_tile_td, a, b.opt, stream)
+  } else {
+    PEMB_DIM_SWITCH(float, t.dim, launch_tile_td, a, b.opt, stream)
+  }
+}
+
+hipError_t launch_find_multi(const BackwardArgs& b, hipStream_t stream) {
+  if (b.n == 0) return hipSuccess;
+  const uint32_t grid = (b.n + kBlock - 1) / kBlock;  // U <= n; threads past U exit
+  hipLaunchKernelGGL(k_find_multi, dim3(grid), dim3(kBlock), 0, stream, b.seg_off, const_cast<uint32_t*>(b.counters),
+                     b.multi_list);
+  return hipGetLastError();
+}
+
+hipError_t launch_fixup(const TableView& t, const BackwardArgs& b, hipStream_t stream) {
+  if (b.n == 0) return hipSuccess;
+  FixupArgs a;
+  a.unique_keys = b.unique_keys;
+  a.seg_off = b.seg_off;
+  a.counters = b.counters;
+  a.multi_list = b.multi_list;
+  a.partials = b.partials;
+  a.pstride = b.pstride;
+  a.w = t.w;
+  a.accs = t.acc;
+  a.key_base = t.key_base;
+  a.rows = t.rows;
+  a.lr = b.lr;
+  a.eps = b.eps;
+  const uint32_t tiles = (b.n + kTile - 1) / kTile;
+  const uint32_t grid = tiles < 4096u ? tiles : 4096u;  // multi-tile segments <= tiles
+  if (t.dtype == 1) {
+    PEMB_DIM_SWITCH(bf16_t, t.dim, launch_fixup_td, a, b.opt, grid, stream)
+  } else {
+    PEMB_DIM_SWITCH(float, t.dim, launch_fixup_td, a, b.opt, grid, stream)
+  }
+}
+
+}  // namespace pemb

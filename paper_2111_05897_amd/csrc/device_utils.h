@@ -1,0 +1,85 @@
+// Device-side helpers shared by the kernels of the embedding library (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pemb {
+
+constexpr int kWave = 64;
+constexpr int kBlock = 256;                 // every kernel here runs 256-thread workgroups (4 waves)
+constexpr int kWavesPerBlock = kBlock / kWave;
+
+typedef uint16_t bf16_t;                    // raw bf16 storage
+
+// 64-bit bijective mixer of the hash (definition in include/persia_emb.h).
+__host__ __device__ __forceinline__ uint64_t mix64(uint64_t z) {
+  z ^= z >> 31;
+  z *= 0x9FB21C651E98DF25ull;
+  z ^= z >> 29;
+  z *= 0xC2B2AE3D27D4EB4Full;
+  z ^= z >> 32;
+  return z;
+}
+
+// ID -> row.  mask = rows-1 when rows is a power of two (then mod is an AND), else 0.
+__device__ __forceinline__ uint32_t hash_row(uint64_t id, uint64_t salt, uint64_t rows, uint64_t mask, int mix) {
+  uint64_t z = mix ? mix64(id + salt) : id;
+  return (uint32_t)(mask ? (z & mask) : (z % rows));
+}
+
+__device__ __forceinline__ float bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+// fp32 -> bf16, round to nearest even; NaN stays a quiet NaN.
+__device__ __forceinline__ uint32_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x0040u;
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+// Initial value of one table element (definition in include/persia_emb.h): separate multiply and add.
+__device__ __forceinline__ float init_value(uint64_t table_key, uint64_t elem, float scale, float mid) {
+  uint64_t h = mix64(table_key + elem);
+  int k = (int)(h >> 40) - (1 << 23);
+  return __fadd_rn(__fmul_rn((float)k, scale), mid);
+}
+
+// ---- 4-element row fragments (what one lane owns of a row in the backward kernels) ----
+__device__ __forceinline__ float4 load_frag4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ float4 load_frag4(const bf16_t* p) {
+  uint2 v = *reinterpret_cast<const uint2*>(p);
+  return make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xFFFF0000u), __uint_as_float(v.y << 16),
+                     __uint_as_float(v.y & 0xFFFF0000u));
+}
+__device__ __forceinline__ void store_frag4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
+__device__ __forceinline__ void store_frag4(bf16_t* p, float4 v) {
+  uint2 o;
+  o.x = f32_to_bf16(v.x) | (f32_to_bf16(v.y) << 16);
+  o.y = f32_to_bf16(v.z) | (f32_to_bf16(v.w) << 16);
+  *reinterpret_cast<uint2*>(p) = o;
+}
+
+// ---- block-wide exclusive scan over kBlock threads; s_w: shared uint32_t[kWavesPerBlock] ----
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* s_w, uint32_t* total) {
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+  uint32_t incl = v;
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    uint32_t t = __shfl_up(incl, off);
+    if (lane >= off) incl += t;
+  }
+  if (lane == kWave - 1) s_w[wave] = incl;
+  __syncthreads();
+  uint32_t woff = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < kWavesPerBlock; ++w) {
+    uint32_t x = s_w[w];
+    if (w < wave) woff += x;
+    tot += x;
+  }
+  __syncthreads();  // s_w may be reused by the caller right away
+  if (total) *total = tot;
+  return woff + incl - v;
+}
+
+}  // namespace pemb

@@ -1,0 +1,613 @@
+// C ABI of the embedding library (declared in include/persia_emb.h): context, validation,
+// workspace, and the sequence of kernel launches of each hot call.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/persia_emb.h"
+#include "device_utils.h"
+#include "launch.h"
+
+using namespace pemb;
+
+namespace {
+
+enum Stage {
+  ST_GATHER_POOL = 0,
+  ST_BUILD_KEYS,
+  ST_SORT_HIST,
+  ST_SORT_SCAN,
+  ST_SORT_SCATTER,
+  ST_UNIQUE,
+  ST_REDUCE_UPDATE,
+  ST_FIND_MULTI,
+  ST_FIXUP,
+  ST_COUNT
+};
+const char* const kStageNames[ST_COUNT] = {"gather_pool", "build_keys",    "sort_hist",  "sort_scan", "sort_scatter",
+                                           "unique",      "reduce_update", "find_multi", "fixup"};
+
+struct EventRec {
+  int stage;
+  hipEvent_t e0, e1;
+};
+
+thread_local std::string g_create_error;
+
+}  // namespace
+
+struct emb_ctx {
+  int device = 0;
+  uint32_t S = 0, width = 0, max_batch = 0;
+  uint64_t max_ids = 0;
+  int mix = 0, opt = 0;
+  float lr = 0, eps = 0;
+  int key_bits = 1;
+  int uniform = 0;
+  uint32_t pstride = 0;
+  std::vector<TableView> tables;
+  std::vector<uint32_t> key_base_host;
+  SlotArrays slots{};
+  uint32_t* key_base_dev = nullptr;  // [T]
+  // workspace
+  uint32_t *keys[2] = {nullptr, nullptr}, *bags[2] = {nullptr, nullptr};
+  uint32_t *hist = nullptr, *total = nullptr, *blk_heads = nullptr;
+  uint32_t *unique_keys = nullptr, *seg_off = nullptr, *multi_list = nullptr, *counters = nullptr, *ranges = nullptr;
+  float* partials = nullptr;
+  // last backward
+  int sorted_buf = 0;
+  uint64_t last_n = 0;
+  bool have_dedup = false;
+  // bookkeeping
+  std::vector<void*> allocs;
+  uint64_t device_bytes = 0;
+  bool profiling = false;
+  std::vector<EventRec> recs;
+  std::vector<hipEvent_t> free_events;
+  float stage_ms[ST_COUNT] = {0};
+  uint32_t stage_launches[ST_COUNT] = {0};
+  std::string err;
+};
+
+namespace {
+
+int fail(emb_ctx* ctx, int code, const std::string& msg) {
+  if (ctx) ctx->err = msg;
+  else g_create_error = msg;
+  return code;
+}
+
+int fail_hip(emb_ctx* ctx, const char* what, hipError_t e) {
+  return fail(ctx, e == hipErrorOutOfMemory ? EMB_ENOMEM : EMB_EDEVICE,
+              std::string(what) + ": " + hipGetErrorString(e));
+}
+
+template <typename T>
+hipError_t dev_alloc(emb_ctx* ctx, T** p, uint64_t count) {
+  void* q = nullptr;
+  uint64_t bytes = count * sizeof(T);
+  if (bytes == 0) bytes = sizeof(T);
+  hipError_t e = hipMalloc(&q, bytes);
+  if (e != hipSuccess) return e;
+  ctx->allocs.push_back(q);
+  ctx->device_bytes += bytes;
+  *p = reinterpret_cast<T*>(q);
+  return hipSuccess;
+}
+
+template <typename T>
+hipError_t dev_upload(emb_ctx* ctx, T** p, const std::vector<T>& v) {
+  hipError_t e = dev_alloc(ctx, p, v.size());
+  if (e != hipSuccess) return e;
+  if (!v.empty()) e = hipMemcpy(*p, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice);
+  return e;
+}
+
+void free_all(emb_ctx* ctx) {
+  for (void* p : ctx->allocs) (void)hipFree(p);
+  ctx->allocs.clear();
+  for (auto& r : ctx->recs) {
+    (void)hipEventDestroy(r.e0);
+    (void)hipEventDestroy(r.e1);
+  }
+  ctx->recs.clear();
+  for (auto& e : ctx->free_events) (void)hipEventDestroy(e);
+  ctx->free_events.clear();
+}
+
+// Brackets one kernel stage with events when profiling is on.
+struct StageTimer {
+  emb_ctx* ctx;
+  hipStream_t stream;
+  EventRec rec{};
+  bool on = false;
+  StageTimer(emb_ctx* c, int stage, hipStream_t s) : ctx(c), stream(s) {
+    if (!ctx->profiling) return;
+    hipEvent_t ev[2];
+    for (int i = 0; i < 2; ++i) {
+      if (!ctx->free_events.empty()) {
+        ev[i] = ctx->free_events.back();
+        ctx->free_events.pop_back();
+      } else if (hipEventCreate(&ev[i]) != hipSuccess) {
+        if (i == 1) ctx->free_events.push_back(ev[0]);
+        return;
+      }
+    }
+    rec.stage = stage;
+    rec.e0 = ev[0];
+    rec.e1 = ev[1];
+    on = true;
+    (void)hipEventRecord(rec.e0, stream);
+  }
+  ~StageTimer() {
+    if (!on) return;
+    (void)hipEventRecord(rec.e1, stream);
+    ctx->recs.push_back(rec);
+  }
+};
+
+int check_batch(emb_ctx* ctx, const emb_batch* b) {
+  if (!ctx) return fail(nullptr, EMB_EINVAL, "null context");
+  if (!b) return fail(ctx, EMB_EINVAL, "null batch");
+  if (b->reserved != 0) return fail(ctx, EMB_EINVAL, "batch.reserved must be 0");
+  if (b->batch_size > ctx->max_batch) return fail(ctx, EMB_EINVAL, "batch_size exceeds max_batch given to emb_create");
+  if (b->num_ids > ctx->max_ids) return fail(ctx, EMB_EINVAL, "num_ids exceeds max_ids given to emb_create");
+  if (b->batch_size && !b->offsets) return fail(ctx, EMB_EINVAL, "null offsets");
+  if (b->num_ids && !b->ids) return fail(ctx, EMB_EINVAL, "null ids");
+  if (b->batch_size == 0 && b->num_ids != 0) return fail(ctx, EMB_EINVAL, "ids without samples");
+  return EMB_OK;
+}
+
+int bit_length(uint64_t v) {
+  int b = 0;
+  while (v) {
+    ++b;
+    v >>= 1;
+  }
+  return b;
+}
+
+}  // namespace
+
+extern "C" {
+
+int emb_create(const emb_config* cfg, emb_ctx** out) {
+  if (!cfg || !out) return fail(nullptr, EMB_EINVAL, "null argument");
+  if (cfg->num_tables == 0 || cfg->num_tables > 1023 || !cfg->tables)
+    return fail(nullptr, EMB_EINVAL, "num_tables must be in 1..1023");
+  if (cfg->num_slots == 0 || !cfg->slots) return fail(nullptr, EMB_EINVAL, "num_slots must be >= 1");
+  if (cfg->reserved != 0) return fail(nullptr, EMB_EINVAL, "config.reserved must be 0");
+  if (cfg->hash != EMB_HASH_IDENTITY_MOD && cfg->hash != EMB_HASH_MIX_MOD)
+    return fail(nullptr, EMB_EINVAL, "unknown hash kind");
+  if (cfg->opt != EMB_OPT_SGD && cfg->opt != EMB_OPT_ROWWISE_ADAGRAD)
+    return fail(nullptr, EMB_EINVAL, "unknown optimizer kind");
+  if (!std::isfinite(cfg->lr) || !std::isfinite(cfg->eps) || !std::isfinite(cfg->acc_init) || cfg->eps < 0 ||
+      cfg->acc_init < 0)
+    return fail(nullptr, EMB_EINVAL, "lr, eps, acc_init must be finite, eps and acc_init non-negative");
+  if (!std::isfinite(cfg->init_lo) || !std::isfinite(cfg->init_hi) || cfg->init_lo > cfg->init_hi)
+    return fail(nullptr, EMB_EINVAL, "init range must be finite with lo <= hi");
+  if (cfg->max_batch == 0) return fail(nullptr, EMB_EINVAL, "max_batch must be >= 1");
+  if ((uint64_t)cfg->max_batch * cfg->num_slots >= (1ull << 31))
+    return fail(nullptr, EMB_EINVAL, "max_batch * num_slots must be < 2^31");
+  if (cfg->max_ids >= (1ull << 31)) return fail(nullptr, EMB_EINVAL, "max_ids must be < 2^31");
+  uint64_t total_rows = 0;
+  uint32_t max_dim = 0;
+  for (uint32_t t = 0; t < cfg->num_tables; ++t) {
+    const emb_table_desc& d = cfg->tables[t];
+    if (d.rows == 0) return fail(nullptr, EMB_EINVAL, "table with 0 rows");
+    if (d.dim != 8 && d.dim != 16 && d.dim != 32 && d.dim != 64 && d.dim != 128)
+      return fail(nullptr, EMB_EINVAL, "table dim must be one of 8, 16, 32, 64, 128");
+    if (d.dtype != EMB_F32 && d.dtype != EMB_BF16) return fail(nullptr, EMB_EINVAL, "unknown table dtype");
+    total_rows += d.rows;
+    if (total_rows >= (1ull << 31)) return fail(nullptr, EMB_EINVAL, "sum of table rows must be < 2^31");
+    if (d.dim > max_dim) max_dim = d.dim;
+  }
+  for (uint32_t s = 0; s < cfg->num_slots; ++s) {
+    if (cfg->slots[s].table >= cfg->num_tables) return fail(nullptr, EMB_EINVAL, "slot refers to a missing table");
+    if (cfg->slots[s].reserved != 0) return fail(nullptr, EMB_EINVAL, "slot.reserved must be 0");
+  }
+  int ndev = 0;
+  hipError_t e = hipGetDeviceCount(&ndev);
+  if (e != hipSuccess) return fail_hip(nullptr, "hipGetDeviceCount", e);
+  if (cfg->device < 0 || cfg->device >= ndev) return fail(nullptr, EMB_EINVAL, "no such HIP device");
+  if ((e = hipSetDevice(cfg->device)) != hipSuccess) return fail_hip(nullptr, "hipSetDevice", e);
+
+  emb_ctx* ctx = new (std::nothrow) emb_ctx();
+  if (!ctx) return fail(nullptr, EMB_ENOMEM, "out of host memory");
+  ctx->device = cfg->device;
+  ctx->S = cfg->num_slots;
+  ctx->max_batch = cfg->max_batch;
+  ctx->max_ids = cfg->max_ids;
+  ctx->mix = cfg->hash == EMB_HASH_MIX_MOD;
+  ctx->opt = cfg->opt;
+  ctx->lr = cfg->lr;
+  ctx->eps = cfg->eps;
+  ctx->key_bits = bit_length(total_rows - 1);
+  if (ctx->key_bits < 1) ctx->key_bits = 1;
+  ctx->uniform = cfg->num_tables == 1;
+  ctx->pstride = max_dim;
+
+#define CK(call, what)                                  \
+  do {                                                  \
+    hipError_t _e = (call);                             \
+    if (_e != hipSuccess) {                             \
+      int _rc = fail_hip(nullptr, what, _e);            \
+      free_all(ctx);                                    \
+      delete ctx;                                       \
+      return _rc;                                       \
+    }                                                   \
+  } while (0)
+
+  // tables + state
+  std::vector<uint64_t> s_salt(ctx->S), s_rows(ctx->S), s_mask(ctx->S);
+  std::vector<uint32_t> s_kb(ctx->S), s_col(ctx->S);
+  ctx->tables.resize(cfg->num_tables);
+  ctx->key_base_host.resize(cfg->num_tables);
+  uint32_t kb = 0;
+  for (uint32_t t = 0; t < cfg->num_tables; ++t) {
+    const emb_table_desc& d = cfg->tables[t];
+    TableView& tv = ctx->tables[t];
+    tv.rows = d.rows;
+    tv.mask = (d.rows & (d.rows - 1)) == 0 ? d.rows - 1 : 0;
+    if (d.rows == 1) tv.mask = 0;  // rows == 1: "mod 1" path (mask 0 means "not a power of two" to the kernels)
+    tv.dim = d.dim;
+    tv.dtype = d.dtype;
+    tv.key_base = kb;
+    ctx->key_base_host[t] = kb;
+    kb += (uint32_t)d.rows;
+    const uint64_t elems = d.rows * d.dim;
+    if (d.dtype == EMB_BF16) {
+      bf16_t* p = nullptr;
+      CK(dev_alloc(ctx, &p, elems), "hipMalloc(table)");
+      tv.w = p;
+    } else {
+      float* p = nullptr;
+      CK(dev_alloc(ctx, &p, elems), "hipMalloc(table)");
+      tv.w = p;
+    }
+    CK(dev_alloc(ctx, &tv.acc, d.rows), "hipMalloc(optimizer state)");
+    std::vector<uint32_t> list;
+    for (uint32_t s = 0; s < ctx->S; ++s)
+      if (cfg->slots[s].table == t) list.push_back(s);
+    tv.n_slots = (uint32_t)list.size();
+    uint32_t* lp = nullptr;
+    CK(dev_upload(ctx, &lp, list), "upload(slot list)");
+    tv.slot_list = lp;
+    const uint64_t table_key = mix64(cfg->init_seed + (uint64_t)(t + 1) * 0x9E3779B97F4A7C15ull);
+    const float scale = (cfg->init_hi - cfg->init_lo) * 5.9604644775390625e-08f;
+    const float mid = (cfg->init_hi + cfg->init_lo) * 0.5f;
+    CK(launch_init_table(tv, table_key, scale, mid, cfg->acc_init, nullptr), "init_table");
+  }
+  uint32_t col = 0;
+  for (uint32_t s = 0; s < ctx->S; ++s) {
+    const TableView& tv = ctx->tables[cfg->slots[s].table];
+    s_salt[s] = cfg->slots[s].salt;
+    s_rows[s] = tv.rows;
+    s_mask[s] = tv.mask;
+    s_kb[s] = tv.key_base;
+    s_col[s] = col;
+    col += tv.dim;
+  }
+  ctx->width = col;
+  {
+    uint64_t *p_salt = nullptr, *p_rows = nullptr, *p_mask = nullptr;
+    uint32_t *p_kb = nullptr, *p_col = nullptr;
+    CK(dev_upload(ctx, &p_salt, s_salt), "upload(slot salt)");
+    CK(dev_upload(ctx, &p_rows, s_rows), "upload(slot rows)");
+    CK(dev_upload(ctx, &p_mask, s_mask), "upload(slot mask)");
+    CK(dev_upload(ctx, &p_kb, s_kb), "upload(slot key base)");
+    CK(dev_upload(ctx, &p_col, s_col), "upload(slot col)");
+    ctx->slots.salt = p_salt;
+    ctx->slots.rows = p_rows;
+    ctx->slots.mask = p_mask;
+    ctx->slots.key_base = p_kb;
+    ctx->slots.col = p_col;
+    CK(dev_upload(ctx, &ctx->key_base_dev, ctx->key_base_host), "upload(table key base)");
+  }
+  // workspace
+  const uint64_t cap = ctx->max_ids ? ctx->max_ids : 1;
+  const uint64_t ntiles = (cap + kTile - 1) / kTile;
+  for (int i = 0; i < 2; ++i) {
+    CK(dev_alloc(ctx, &ctx->keys[i], cap), "hipMalloc(sort keys)");
+    CK(dev_alloc(ctx, &ctx->bags[i], cap), "hipMalloc(sort payload)");
+  }
+  CK(dev_alloc(ctx, &ctx->hist, (uint64_t)256 * kSortMaxBlocks), "hipMalloc(histograms)");
+  CK(dev_alloc(ctx, &ctx->total, 256), "hipMalloc(digit totals)");
+  CK(dev_alloc(ctx, &ctx->blk_heads, (cap + kUniqueTile - 1) / kUniqueTile + 1), "hipMalloc(block heads)");
+  CK(dev_alloc(ctx, &ctx->unique_keys, cap), "hipMalloc(unique keys)");
+  CK(dev_alloc(ctx, &ctx->seg_off, cap + 1), "hipMalloc(segment offsets)");
+  CK(dev_alloc(ctx, &ctx->multi_list, ntiles), "hipMalloc(multi-tile list)");
+  CK(dev_alloc(ctx, &ctx->counters, 8), "hipMalloc(counters)");
+  CK(dev_alloc(ctx, &ctx->ranges, cfg->num_tables + 1), "hipMalloc(table ranges)");
+  CK(dev_alloc(ctx, &ctx->partials, 2 * ntiles * ctx->pstride), "hipMalloc(partials)");
+  CK(hipDeviceSynchronize(), "table initialisation");
+#undef CK
+  *out = ctx;
+  return EMB_OK;
+}
+
+int emb_destroy(emb_ctx* ctx) {
+  if (!ctx) return EMB_OK;
+  (void)hipSetDevice(ctx->device);
+  (void)hipDeviceSynchronize();
+  free_all(ctx);
+  delete ctx;
+  return EMB_OK;
+}
+
+#define CKH(call, what)                                      \
+  do {                                                       \
+    hipError_t _e = (call);                                  \
+    if (_e != hipSuccess) return fail_hip(ctx, what, _e);    \
+  } while (0)
+
+int emb_lookup_pool(emb_ctx* ctx, const emb_batch* batch, float* pooled, void* hip_stream) {
+  int rc = check_batch(ctx, batch);
+  if (rc) return rc;
+  if (batch->batch_size == 0) return EMB_OK;
+  if (!pooled) return fail(ctx, EMB_EINVAL, "null pooled output");
+  hipStream_t stream = (hipStream_t)hip_stream;
+  CKH(hipSetDevice(ctx->device), "hipSetDevice");
+  for (const TableView& tv : ctx->tables) {
+    StageTimer tm(ctx, ST_GATHER_POOL, stream);
+    CKH(launch_gather_pool(tv, ctx->slots, batch->ids, batch->offsets, batch->batch_size, ctx->S, ctx->width,
+                           ctx->mix, pooled, stream),
+        "gather_pool");
+  }
+  return EMB_OK;
+}
+
+int emb_hash_rows(emb_ctx* ctx, const emb_batch* batch, uint32_t* rows_out, void* hip_stream) {
+  int rc = check_batch(ctx, batch);
+  if (rc) return rc;
+  if (batch->num_ids == 0) return EMB_OK;
+  if (!rows_out) return fail(ctx, EMB_EINVAL, "null rows output");
+  hipStream_t stream = (hipStream_t)hip_stream;
+  CKH(hipSetDevice(ctx->device), "hipSetDevice");
+  CKH(launch_build_keys(ctx->slots, batch->ids, batch->offsets, batch->batch_size, ctx->S, ctx->mix, 1, rows_out,
+                        nullptr, stream),
+      "hash_rows");
+  return EMB_OK;
+}
+
+int emb_backward_update(emb_ctx* ctx, const emb_batch* batch, const float* d_pooled, void* hip_stream) {
+  int rc = check_batch(ctx, batch);
+  if (rc) return rc;
+  if (batch->batch_size && !d_pooled) return fail(ctx, EMB_EINVAL, "null d_pooled");
+  hipStream_t stream = (hipStream_t)hip_stream;
+  CKH(hipSetDevice(ctx->device), "hipSetDevice");
+  const uint32_t n = (uint32_t)batch->num_ids;
+  ctx->last_n = n;
+  ctx->have_dedup = true;
+  ctx->sorted_buf = 0;
+  if (n == 0) {  // nothing to update; leave an empty index form behind
+    CKH(launch_unique(ctx->keys[0], 0, ctx->blk_heads, ctx->unique_keys, ctx->seg_off, ctx->counters, stream),
+        "unique");
+    return EMB_OK;
+  }
+  {
+    StageTimer tm(ctx, ST_BUILD_KEYS, stream);
+    CKH(launch_build_keys(ctx->slots, batch->ids, batch->offsets, batch->batch_size, ctx->S, ctx->mix, 0,
+                          ctx->keys[0], ctx->bags[0], stream),
+        "build_keys");
+  }
+  const SortPlan plan = make_sort_plan(n, ctx->key_bits);
+  int src = 0;
+  for (int pass = 0; pass < plan.passes; ++pass) {
+    const int shift = pass * plan.bits;
+    {
+      StageTimer tm(ctx, ST_SORT_HIST, stream);
+      CKH(launch_radix_hist(plan, shift, ctx->keys[src], ctx->hist, stream), "radix_hist");
+    }
+    {
+      StageTimer tm(ctx, ST_SORT_SCAN, stream);
+      CKH(launch_radix_scan(plan, ctx->hist, ctx->total, stream), "radix_scan");
+    }
+    {
+      StageTimer tm(ctx, ST_SORT_SCATTER, stream);
+      CKH(launch_radix_scatter(plan, shift, ctx->keys[src], ctx->bags[src], ctx->keys[src ^ 1], ctx->bags[src ^ 1],
+                               ctx->hist, ctx->total, stream),
+          "radix_scatter");
+    }
+    src ^= 1;
+  }
+  ctx->sorted_buf = src;
+  {
+    StageTimer tm(ctx, ST_UNIQUE, stream);
+    CKH(launch_unique(ctx->keys[src], n, ctx->blk_heads, ctx->unique_keys, ctx->seg_off, ctx->counters, stream),
+        "unique");
+  }
+  BackwardArgs a{};
+  a.keys = ctx->keys[src];
+  a.bags = ctx->bags[src];
+  a.n = n;
+  a.d_pooled = d_pooled;
+  a.S = ctx->S;
+  a.width = ctx->width;
+  a.slot_col = ctx->slots.col;
+  a.uniform = ctx->uniform;
+  a.partials = ctx->partials;
+  a.pstride = ctx->pstride;
+  a.range = nullptr;
+  a.opt = ctx->opt;
+  a.lr = ctx->lr;
+  a.eps = ctx->eps;
+  a.unique_keys = ctx->unique_keys;
+  a.seg_off = ctx->seg_off;
+  a.counters = ctx->counters;
+  a.multi_list = ctx->multi_list;
+  const bool multi_table = ctx->tables.size() > 1;
+  if (multi_table)
+    CKH(launch_table_ranges(a.keys, n, ctx->key_base_dev, (uint32_t)ctx->tables.size(), ctx->ranges, stream),
+        "table_ranges");
+  for (size_t t = 0; t < ctx->tables.size(); ++t) {
+    StageTimer tm(ctx, ST_REDUCE_UPDATE, stream);
+    a.range = multi_table ? ctx->ranges + t : nullptr;
+    CKH(launch_tile_reduce_update(ctx->tables[t], a, stream), "tile_reduce_update");
+  }
+  {
+    StageTimer tm(ctx, ST_FIND_MULTI, stream);
+    CKH(launch_find_multi(a, stream), "find_multi");
+  }
+  for (size_t t = 0; t < ctx->tables.size(); ++t) {
+    StageTimer tm(ctx, ST_FIXUP, stream);
+    CKH(launch_fixup(ctx->tables[t], a, stream), "fixup");
+  }
+  return EMB_OK;
+}
+
+int emb_dedup_sizes(emb_ctx* ctx, uint64_t* num_unique, uint64_t* num_ids) {
+  if (!ctx) return fail(nullptr, EMB_EINVAL, "null context");
+  if (!ctx->have_dedup) return fail(ctx, EMB_ESTATE, "no emb_backward_update has run on this context");
+  CKH(hipSetDevice(ctx->device), "hipSetDevice");
+  CKH(hipDeviceSynchronize(), "hipDeviceSynchronize");
+  uint32_t c[2] = {0, 0};
+  CKH(hipMemcpy(c, ctx->counters, sizeof(c), hipMemcpyDeviceToHost), "hipMemcpy(counters)");
+  if (num_unique) *num_unique = c[0];
+  if (num_ids) *num_ids = ctx->last_n;
+  return EMB_OK;
+}
+
+int emb_read_dedup(emb_ctx* ctx, uint64_t* keys, uint32_t* seg_off, uint32_t* seg_bags) {
+  uint64_t U = 0, N = 0;
+  int rc = emb_dedup_sizes(ctx, &U, &N);
+  if (rc) return rc;
+  if (keys && U) {
+    std::vector<uint32_t> tmp(U);
+    CKH(hipMemcpy(tmp.data(), ctx->unique_keys, U * sizeof(uint32_t), hipMemcpyDeviceToHost), "hipMemcpy(keys)");
+    size_t t = 0;
+    const size_t T = ctx->key_base_host.size();
+    for (uint64_t u = 0; u < U; ++u) {  // keys ascend, so the table index only moves forward
+      while (t + 1 < T && tmp[u] >= ctx->key_base_host[t + 1]) ++t;
+      keys[u] = ((uint64_t)t << 32) | (uint64_t)(tmp[u] - ctx->key_base_host[t]);
+    }
+  }
+  if (seg_off) CKH(hipMemcpy(seg_off, ctx->seg_off, (U + 1) * sizeof(uint32_t), hipMemcpyDeviceToHost), "hipMemcpy(seg_off)");
+  if (seg_bags && N)
+    CKH(hipMemcpy(seg_bags, ctx->bags[ctx->sorted_buf], N * sizeof(uint32_t), hipMemcpyDeviceToHost),
+        "hipMemcpy(seg_bags)");
+  return EMB_OK;
+}
+
+static int rows_io(emb_ctx* ctx, uint32_t table, const uint64_t* rows, uint64_t n, float* w_out, float* acc_out,
+                   const float* w_in, const float* acc_in, bool write) {
+  if (!ctx) return fail(nullptr, EMB_EINVAL, "null context");
+  if (table >= ctx->tables.size()) return fail(ctx, EMB_EINVAL, "no such table");
+  if (n == 0) return EMB_OK;
+  if (!rows) return fail(ctx, EMB_EINVAL, "null rows");
+  const TableView& tv = ctx->tables[table];
+  for (uint64_t i = 0; i < n; ++i)
+    if (rows[i] >= tv.rows) return fail(ctx, EMB_EINVAL, "row index out of range");
+  CKH(hipSetDevice(ctx->device), "hipSetDevice");
+  const uint64_t chunk = 1u << 20;
+  uint64_t* d_rows = nullptr;
+  float *d_w = nullptr, *d_a = nullptr;
+  const uint64_t m = n < chunk ? n : chunk;
+  hipError_t e = hipMalloc((void**)&d_rows, m * sizeof(uint64_t));
+  if (e == hipSuccess) e = hipMalloc((void**)&d_w, m * tv.dim * sizeof(float));
+  if (e == hipSuccess) e = hipMalloc((void**)&d_a, m * sizeof(float));
+  for (uint64_t i0 = 0; e == hipSuccess && i0 < n; i0 += chunk) {
+    const uint64_t c = n - i0 < chunk ? n - i0 : chunk;
+    e = hipMemcpy(d_rows, rows + i0, c * sizeof(uint64_t), hipMemcpyHostToDevice);
+    if (e != hipSuccess) break;
+    if (write) {
+      if (w_in) e = hipMemcpy(d_w, w_in + i0 * tv.dim, c * tv.dim * sizeof(float), hipMemcpyHostToDevice);
+      if (e == hipSuccess && acc_in) e = hipMemcpy(d_a, acc_in + i0, c * sizeof(float), hipMemcpyHostToDevice);
+      if (e == hipSuccess) e = launch_write_rows(tv, d_rows, c, w_in ? d_w : nullptr, acc_in ? d_a : nullptr, nullptr);
+      if (e == hipSuccess) e = hipDeviceSynchronize();
+    } else {
+      e = launch_read_rows(tv, d_rows, c, w_out ? d_w : nullptr, acc_out ? d_a : nullptr, nullptr);
+      if (e == hipSuccess) e = hipDeviceSynchronize();
+      if (e == hipSuccess && w_out) e = hipMemcpy(w_out + i0 * tv.dim, d_w, c * tv.dim * sizeof(float), hipMemcpyDeviceToHost);
+      if (e == hipSuccess && acc_out) e = hipMemcpy(acc_out + i0, d_a, c * sizeof(float), hipMemcpyDeviceToHost);
+    }
+  }
+  (void)hipFree(d_rows);
+  (void)hipFree(d_w);
+  (void)hipFree(d_a);
+  if (e != hipSuccess) return fail_hip(ctx, write ? "emb_write_rows" : "emb_read_rows", e);
+  return EMB_OK;
+}
+
+int emb_read_rows(emb_ctx* ctx, uint32_t table, const uint64_t* rows, uint64_t n, float* w, float* acc) {
+  if (ctx) {
+    (void)hipSetDevice(ctx->device);
+    (void)hipDeviceSynchronize();
+  }
+  return rows_io(ctx, table, rows, n, w, acc, nullptr, nullptr, false);
+}
+
+int emb_write_rows(emb_ctx* ctx, uint32_t table, const uint64_t* rows, uint64_t n, const float* w, const float* acc) {
+  if (ctx) {
+    (void)hipSetDevice(ctx->device);
+    (void)hipDeviceSynchronize();
+  }
+  return rows_io(ctx, table, rows, n, nullptr, nullptr, w, acc, true);
+}
+
+int emb_table_ptr(emb_ctx* ctx, uint32_t table, void** w_dev, float** acc_dev) {
+  if (!ctx) return fail(nullptr, EMB_EINVAL, "null context");
+  if (table >= ctx->tables.size()) return fail(ctx, EMB_EINVAL, "no such table");
+  if (w_dev) *w_dev = ctx->tables[table].w;
+  if (acc_dev) *acc_dev = ctx->tables[table].acc;
+  return EMB_OK;
+}
+
+int emb_set_profiling(emb_ctx* ctx, int enabled) {
+  if (!ctx) return fail(nullptr, EMB_EINVAL, "null context");
+  ctx->profiling = enabled != 0;
+  return EMB_OK;
+}
+
+int emb_stage_count(void) { return ST_COUNT; }
+
+const char* emb_stage_name(int stage) { return (stage >= 0 && stage < ST_COUNT) ? kStageNames[stage] : ""; }
+
+static int drain_events(emb_ctx* ctx) {
+  CKH(hipSetDevice(ctx->device), "hipSetDevice");
+  CKH(hipDeviceSynchronize(), "hipDeviceSynchronize");
+  for (auto& r : ctx->recs) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, r.e0, r.e1) == hipSuccess) {
+      ctx->stage_ms[r.stage] += ms;
+      ctx->stage_launches[r.stage] += 1;
+    }
+    ctx->free_events.push_back(r.e0);
+    ctx->free_events.push_back(r.e1);
+  }
+  ctx->recs.clear();
+  return EMB_OK;
+}
+
+int emb_read_stage_ms(emb_ctx* ctx, float* ms, uint32_t* launches) {
+  if (!ctx) return fail(nullptr, EMB_EINVAL, "null context");
+  int rc = drain_events(ctx);
+  if (rc) return rc;
+  for (int i = 0; i < ST_COUNT; ++i) {
+    if (ms) ms[i] = ctx->stage_ms[i];
+    if (launches) launches[i] = ctx->stage_launches[i];
+  }
+  return EMB_OK;
+}
+
+int emb_reset_stage_ms(emb_ctx* ctx) {
+  if (!ctx) return fail(nullptr, EMB_EINVAL, "null context");
+  int rc = drain_events(ctx);
+  if (rc) return rc;
+  for (int i = 0; i < ST_COUNT; ++i) {
+    ctx->stage_ms[i] = 0.f;
+    ctx->stage_launches[i] = 0;
+  }
+  return EMB_OK;
+}
+
+uint64_t emb_device_bytes(emb_ctx* ctx) { return ctx ? ctx->device_bytes : 0; }
+
+const char* emb_last_error(emb_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
+
+}  // extern "C"

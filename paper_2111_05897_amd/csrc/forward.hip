@@ -1,0 +1,171 @@
+// Forward: hash + gather + per-slot sum pooling, and the key builder of the backward's dedup.
+//
+// gather_pool: a group of LANES adjacent lanes owns one bag; each lane owns 16 bytes of the row
+// (4 fp32 or 8 bf16 elements), so a row read is one fully coalesced LANES*16-byte access and a
+// wave keeps 64/LANES bags in flight.  Rows of a bag are summed in batch order in fp32; four
+// row loads are issued before the first add so that each lane has several HBM requests in flight.
+#include "device_utils.h"
+#include "launch.h"
+
+namespace pemb {
+namespace {
+
+struct GatherArgs {
+  const uint64_t* ids;
+  const int32_t* offsets;
+  const void* w;
+  uint64_t rows, mask;
+  const uint32_t* slot_list;   // slots reading this table
+  const uint64_t* slot_salt;   // indexed by slot
+  const uint32_t* slot_col;    // indexed by slot
+  uint32_t n_slots_t, S, width;
+  uint32_t n_local_bags;       // B * n_slots_t
+  int mix;
+  float* pooled;
+};
+
+template <typename T, int VEC>
+struct RowVec;
+template <>
+struct RowVec<float, 4> {
+  float v[4];
+  __device__ __forceinline__ void load(const float* p) {
+    float4 t = *reinterpret_cast<const float4*>(p);
+    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+  }
+};
+template <>
+struct RowVec<bf16_t, 8> {
+  float v[8];
+  __device__ __forceinline__ void load(const bf16_t* p) {
+    uint4 t = *reinterpret_cast<const uint4*>(p);
+    v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xFFFF0000u);
+    v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xFFFF0000u);
+    v[4] = __uint_as_float(t.z << 16); v[5] = __uint_as_float(t.z & 0xFFFF0000u);
+    v[6] = __uint_as_float(t.w << 16); v[7] = __uint_as_float(t.w & 0xFFFF0000u);
+  }
+};
+
+template <typename T, int D>
+__global__ __launch_bounds__(kBlock) void k_gather_pool(GatherArgs a) {
+  constexpr int VEC = 16 / (int)sizeof(T);
+  constexpr int LANES = D / VEC;
+  constexpr int GPB = kBlock / LANES;
+  static_assert(LANES >= 1 && LANES <= 64 && (LANES & (LANES - 1)) == 0, "row must map onto a power-of-two lane group");
+  const uint32_t lb = blockIdx.x * GPB + threadIdx.x / LANES;
+  const int lane = threadIdx.x % LANES;
+  if (lb >= a.n_local_bags) return;
+  const uint32_t b = lb / a.n_slots_t;
+  const uint32_t slot = a.slot_list[lb - b * a.n_slots_t];
+  const size_t bag = (size_t)b * a.S + slot;
+  const int beg = a.offsets[bag], end = a.offsets[bag + 1];
+  const uint64_t salt = a.slot_salt[slot];
+  const T* __restrict__ base = reinterpret_cast<const T*>(a.w) + lane * VEC;
+  const uint64_t* __restrict__ ids = a.ids;
+
+  float acc[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+
+  int i = beg;
+  for (; i + 4 <= end; i += 4) {
+    RowVec<T, VEC> r[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      uint32_t row = hash_row(ids[i + j], salt, a.rows, a.mask, a.mix);
+      r[j].load(base + (size_t)row * D);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc[e] += r[j].v[e];
+  }
+  for (; i < end; ++i) {
+    RowVec<T, VEC> r;
+    uint32_t row = hash_row(ids[i], salt, a.rows, a.mask, a.mix);
+    r.load(base + (size_t)row * D);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] += r.v[e];
+  }
+
+  float* out = a.pooled + (size_t)b * a.width + a.slot_col[slot] + lane * VEC;
+#pragma unroll
+  for (int e = 0; e < VEC; e += 4)
+    *reinterpret_cast<float4*>(out + e) = make_float4(acc[e], acc[e + 1], acc[e + 2], acc[e + 3]);
+}
+
+// 8 lanes per bag; lane j takes ids beg+j, beg+j+8, ...
+__global__ __launch_bounds__(kBlock) void k_build_keys(SlotArrays sl, const uint64_t* __restrict__ ids,
+                                                       const int32_t* __restrict__ offsets, uint32_t n_bags,
+                                                       uint32_t S, int mix, int bare_rows,
+                                                       uint32_t* __restrict__ keys_out,
+                                                       uint32_t* __restrict__ bags_out) {
+  const uint32_t bag = blockIdx.x * (kBlock / 8) + threadIdx.x / 8;
+  const int lane = threadIdx.x % 8;
+  if (bag >= n_bags) return;
+  const uint32_t slot = bag % S;
+  const int beg = offsets[bag], end = offsets[bag + 1];
+  const uint64_t salt = sl.salt[slot], rows = sl.rows[slot], mask = sl.mask[slot];
+  const uint32_t kb = bare_rows ? 0u : sl.key_base[slot];
+  for (int i = beg + lane; i < end; i += 8) {
+    keys_out[i] = kb + hash_row(ids[i], salt, rows, mask, mix);
+    if (bags_out) bags_out[i] = bag;
+  }
+}
+
+template <typename T, int D>
+hipError_t launch_gp(const GatherArgs& a, hipStream_t stream) {
+  constexpr int LANES = D / (16 / (int)sizeof(T));
+  constexpr int GPB = kBlock / LANES;
+  const uint32_t grid = (a.n_local_bags + GPB - 1) / GPB;
+  hipLaunchKernelGGL((k_gather_pool<T, D>), dim3(grid), dim3(kBlock), 0, stream, a);
+  return hipGetLastError();
+}
+
+template <typename T>
+hipError_t dispatch_dim(uint32_t dim, const GatherArgs& a, hipStream_t stream) {
+  switch (dim) {
+    case 8: return launch_gp<T, 8>(a, stream);
+    case 16: return launch_gp<T, 16>(a, stream);
+    case 32: return launch_gp<T, 32>(a, stream);
+    case 64: return launch_gp<T, 64>(a, stream);
+    case 128: return launch_gp<T, 128>(a, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_gather_pool(const TableView& t, const SlotArrays& sl, const uint64_t* ids, const int32_t* offsets,
+                              uint32_t B, uint32_t S, uint32_t width, int mix, float* pooled, hipStream_t stream) {
+  if (B == 0 || t.n_slots == 0) return hipSuccess;
+  GatherArgs a;
+  a.ids = ids;
+  a.offsets = offsets;
+  a.w = t.w;
+  a.rows = t.rows;
+  a.mask = t.mask;
+  a.slot_list = t.slot_list;
+  a.slot_salt = sl.salt;
+  a.slot_col = sl.col;
+  a.n_slots_t = t.n_slots;
+  a.S = S;
+  a.width = width;
+  a.n_local_bags = B * t.n_slots;
+  a.mix = mix;
+  a.pooled = pooled;
+  return t.dtype == 1 ? dispatch_dim<bf16_t>(t.dim, a, stream) : dispatch_dim<float>(t.dim, a, stream);
+}
+
+hipError_t launch_build_keys(const SlotArrays& sl, const uint64_t* ids, const int32_t* offsets, uint32_t B,
+                             uint32_t S, int mix, int bare_rows, uint32_t* keys_out, uint32_t* bags_out,
+                             hipStream_t stream) {
+  const uint32_t n_bags = B * S;
+  if (n_bags == 0) return hipSuccess;
+  const uint32_t grid = (n_bags + kBlock / 8 - 1) / (kBlock / 8);
+  hipLaunchKernelGGL(k_build_keys, dim3(grid), dim3(kBlock), 0, stream, sl, ids, offsets, n_bags, S, mix, bare_rows,
+                     keys_out, bags_out);
+  return hipGetLastError();
+}
+
+}  // namespace pemb

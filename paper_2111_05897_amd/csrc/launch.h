@@ -1,0 +1,95 @@
+// Host-side launchers of the kernels; each only enqueues on `stream` and returns the launch status.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pemb {
+
+// Occurrences per tile of the segmented reduce: one lane-group walks this many sorted occurrences.
+constexpr uint32_t kTile = 32;
+// Radix sort geometry: a block ranks and scatters tiles of 256 threads x 8 keys.
+constexpr uint32_t kSortTile = 2048;
+constexpr uint32_t kSortMaxBlocks = 1024;
+constexpr uint32_t kUniqueTile = 2048;
+
+// What a kernel needs to know about one table.
+struct TableView {
+  void* w;            // [rows, dim] fp32 or bf16
+  float* acc;         // [rows]
+  uint64_t rows;
+  uint64_t mask;      // rows-1 if rows is a power of two, else 0
+  uint32_t dim;
+  int32_t dtype;      // 0 fp32, 1 bf16
+  uint32_t key_base;  // first global row index of the table (sort keys are key_base + row)
+  uint32_t n_slots;   // slots reading this table
+  const uint32_t* slot_list;  // device, [n_slots] slot indices, ascending
+};
+
+// Per-slot arrays, device, [S] each.
+struct SlotArrays {
+  const uint64_t* salt;
+  const uint64_t* rows;
+  const uint64_t* mask;
+  const uint32_t* key_base;
+  const uint32_t* col;
+};
+
+// ---- table.hip ----
+hipError_t launch_init_table(const TableView& t, uint64_t table_key, float scale, float mid, float acc_init,
+                             hipStream_t stream);
+hipError_t launch_read_rows(const TableView& t, const uint64_t* rows_dev, uint64_t n, float* w_out, float* acc_out,
+                            hipStream_t stream);
+hipError_t launch_write_rows(const TableView& t, const uint64_t* rows_dev, uint64_t n, const float* w_in,
+                             const float* acc_in, hipStream_t stream);
+
+// ---- forward.hip ----
+hipError_t launch_gather_pool(const TableView& t, const SlotArrays& sl, const uint64_t* ids, const int32_t* offsets,
+                              uint32_t B, uint32_t S, uint32_t width, int mix, float* pooled, hipStream_t stream);
+// keys_out[i] = key_base(slot) + row (or the bare row when bare_rows != 0); bags_out may be null.
+hipError_t launch_build_keys(const SlotArrays& sl, const uint64_t* ids, const int32_t* offsets, uint32_t B,
+                             uint32_t S, int mix, int bare_rows, uint32_t* keys_out, uint32_t* bags_out,
+                             hipStream_t stream);
+
+// ---- sort.hip ----
+struct SortPlan {
+  uint32_t n, chunk, nblk;
+  int passes, bits;
+};
+SortPlan make_sort_plan(uint32_t n, int key_bits);
+// One LSD pass: digit = (key >> shift) & (2^bits - 1).  hist: [2^bits * nblk], total: [256].
+hipError_t launch_radix_hist(const SortPlan& p, int shift, const uint32_t* keys, uint32_t* hist, hipStream_t stream);
+hipError_t launch_radix_scan(const SortPlan& p, uint32_t* hist, uint32_t* total, hipStream_t stream);
+hipError_t launch_radix_scatter(const SortPlan& p, int shift, const uint32_t* kin, const uint32_t* pin,
+                                uint32_t* kout, uint32_t* pout, const uint32_t* hist, const uint32_t* total,
+                                hipStream_t stream);
+// Run heads of the sorted keys -> unique_keys[U], seg_off[U+1]; counters[0] = U, counters[1] = 0.
+hipError_t launch_unique(const uint32_t* keys, uint32_t n, uint32_t* blk_heads, uint32_t* unique_keys,
+                         uint32_t* seg_off, uint32_t* counters, hipStream_t stream);
+
+// ---- backward.hip ----
+struct BackwardArgs {
+  const uint32_t* keys;      // sorted, [n]
+  const uint32_t* bags;      // sorted with the keys, [n]
+  uint32_t n;
+  const float* d_pooled;     // [B, width]
+  uint32_t S, width;
+  const uint32_t* slot_col;  // device [S]
+  int uniform;               // every slot has this table's dim: gradient of a bag starts at bag*dim
+  float* partials;           // [2 * ntiles, pstride]
+  uint32_t pstride;
+  const uint32_t* range;     // device [2]: occurrences [range[0], range[1]) belong to this table; null = all
+  int opt;
+  float lr, eps;
+  // fix-up only
+  const uint32_t* unique_keys;
+  const uint32_t* seg_off;
+  const uint32_t* counters;  // [0] = U, [1] = number of multi-tile segments
+  uint32_t* multi_list;
+};
+hipError_t launch_table_ranges(const uint32_t* keys, uint32_t n, const uint32_t* key_base_dev, uint32_t num_tables,
+                               uint32_t* ranges /*[num_tables+1]*/, hipStream_t stream);
+hipError_t launch_tile_reduce_update(const TableView& t, const BackwardArgs& a, hipStream_t stream);
+hipError_t launch_find_multi(const BackwardArgs& a, hipStream_t stream);
+hipError_t launch_fixup(const TableView& t, const BackwardArgs& a, hipStream_t stream);
+
+}  // namespace pemb

@@ -1,0 +1,317 @@
+// Dedup of the batch: stable LSD radix sort of (key, bag) pairs and run-length "unique".
+//
+// One radix pass = three kernels.  hist: every block counts the digits of its contiguous chunk.
+// scan: one block per digit turns that digit's per-block counts into exclusive prefixes and
+// emits the digit total.  scatter: every block walks its chunk in tiles of 2048 pairs; inside a
+// tile each wave ranks its keys with ballot-based digit matching (stable: rank = number of
+// earlier pairs of the tile with the same digit), the tile is reordered digit-major through LDS,
+// and written out so that consecutive lanes store to consecutive addresses of a digit's region.
+// Only the significant key bits are sorted (ceil(key_bits / 8) passes).
+#include "device_utils.h"
+#include "launch.h"
+
+namespace pemb {
+namespace {
+
+constexpr int kItems = 8;  // keys per thread per tile
+static_assert(kSortTile == kBlock * kItems, "tile geometry");
+
+template <int BITS>
+__global__ __launch_bounds__(kBlock) void k_radix_hist(const uint32_t* __restrict__ keys, uint32_t n, uint32_t chunk,
+                                                       int shift, uint32_t nblk, uint32_t* __restrict__ hist) {
+  constexpr int NB = 1 << BITS;
+  __shared__ uint32_t h[NB];
+  for (int i = threadIdx.x; i < NB; i += kBlock) h[i] = 0;
+  __syncthreads();
+  const uint32_t beg = blockIdx.x * chunk;
+  const uint32_t end = (n - beg < chunk) ? n : beg + chunk;  // beg < n by construction of the plan
+  for (uint32_t i = beg + threadIdx.x; i < end; i += kBlock) atomicAdd(&h[(keys[i] >> shift) & (NB - 1)], 1u);
+  __syncthreads();
+  for (int d = threadIdx.x; d < NB; d += kBlock) hist[(size_t)d * nblk + blockIdx.x] = h[d];
+}
+
+// Block d: exclusive scan of hist[d*nblk .. (d+1)*nblk) in place, total[d] = sum.
+__global__ __launch_bounds__(kBlock) void k_radix_scan(uint32_t* __restrict__ hist, uint32_t nblk,
+                                                       uint32_t* __restrict__ total) {
+  __shared__ uint32_t s_w[kWavesPerBlock];
+  uint32_t* row = hist + (size_t)blockIdx.x * nblk;
+  const uint32_t per = (nblk + kBlock - 1) / kBlock;
+  const uint32_t b0 = threadIdx.x * per;
+  uint32_t sum = 0;
+  for (uint32_t j = 0; j < per; ++j)
+    if (b0 + j < nblk) sum += row[b0 + j];
+  uint32_t tot;
+  uint32_t run = block_exclusive_scan(sum, s_w, &tot);
+  for (uint32_t j = 0; j < per; ++j)
+    if (b0 + j < nblk) {
+      uint32_t v = row[b0 + j];
+      row[b0 + j] = run;
+      run += v;
+    }
+  if (threadIdx.x == 0) total[blockIdx.x] = tot;
+}
+
+template <int BITS>
+__global__ __launch_bounds__(kBlock) void k_radix_scatter(const uint32_t* __restrict__ kin,
+                                                          const uint32_t* __restrict__ pin,
+                                                          uint32_t* __restrict__ kout, uint32_t* __restrict__ pout,
+                                                          uint32_t n, uint32_t chunk, int shift, uint32_t nblk,
+                                                          const uint32_t* __restrict__ hist,
+                                                          const uint32_t* __restrict__ total) {
+  constexpr int NB = 1 << BITS;
+  __shared__ uint32_t s_key[kSortTile];
+  __shared__ uint32_t s_pay[kSortTile];
+  __shared__ uint32_t s_cnt[kWavesPerBlock][NB];
+  __shared__ uint32_t s_gofs[NB];
+  __shared__ uint32_t s_w[kWavesPerBlock];
+
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+  const uint64_t lt_mask = (1ull << lane) - 1ull;
+
+  // Where this block's first pair of digit `tid` goes: pairs of smaller digits anywhere, plus pairs
+  // of the same digit in earlier blocks.
+  uint32_t running = 0;
+  {
+    uint32_t v = tid < NB ? total[tid] : 0u;
+    uint32_t ex = block_exclusive_scan(v, s_w, nullptr);
+    if (tid < NB) running = ex + hist[(size_t)tid * nblk + blockIdx.x];
+  }
+
+  const uint32_t beg = blockIdx.x * chunk;
+  const uint32_t end = (n - beg < chunk) ? n : beg + chunk;
+
+  for (uint32_t tile_base = beg; tile_base < end; tile_base += kSortTile) {
+    const uint32_t tile_cnt = (end - tile_base < kSortTile) ? end - tile_base : kSortTile;
+    for (int i = tid; i < kWavesPerBlock * NB; i += kBlock) (&s_cnt[0][0])[i] = 0;
+    __syncthreads();
+
+    uint32_t key[kItems], pay[kItems], lrank[kItems];
+#pragma unroll
+    for (int k = 0; k < kItems; ++k) {
+      const uint32_t off = wave * (kWave * kItems) + k * kWave + lane;  // position inside the tile
+      const bool valid = off < tile_cnt;
+      key[k] = valid ? kin[tile_base + off] : 0xFFFFFFFFu;
+      pay[k] = valid ? pin[tile_base + off] : 0u;
+    }
+#pragma unroll
+    for (int k = 0; k < kItems; ++k) {
+      const uint32_t off = wave * (kWave * kItems) + k * kWave + lane;
+      const bool valid = off < tile_cnt;
+      const uint32_t d = (key[k] >> shift) & (NB - 1);
+      uint64_t peers = __ballot(valid);
+#pragma unroll
+      for (int b = 0; b < BITS; ++b) {
+        const bool bit = (d >> b) & 1u;
+        const uint64_t bt = __ballot(bit);
+        peers &= bit ? bt : ~bt;
+      }
+      lrank[k] = 0;
+      if (valid) {  // peers: the valid lanes of this wave whose key has the same digit (includes this lane)
+        const int leader = __ffsll((unsigned long long)peers) - 1;
+        uint32_t old = 0;
+        if (lane == leader) old = atomicAdd(&s_cnt[wave][d], (uint32_t)__popcll(peers));
+        old = __shfl(old, leader);
+        lrank[k] = old + (uint32_t)__popcll(peers & lt_mask);
+      }
+    }
+    __syncthreads();
+
+    // Digit-major layout of the tile: digit start, then waves in order.
+    uint32_t c[kWavesPerBlock], tot = 0;
+    if (tid < NB) {
+#pragma unroll
+      for (int w = 0; w < kWavesPerBlock; ++w) {
+        c[w] = s_cnt[w][tid];
+        tot += c[w];
+      }
+    }
+    const uint32_t ex = block_exclusive_scan(tid < NB ? tot : 0u, s_w, nullptr);
+    if (tid < NB) {
+      uint32_t run = ex;
+#pragma unroll
+      for (int w = 0; w < kWavesPerBlock; ++w) {
+        s_cnt[w][tid] = run;
+        run += c[w];
+      }
+      s_gofs[tid] = running - ex;  // global index = s_gofs[digit] + position in the reordered tile
+      running += tot;
+    }
+    __syncthreads();
+
+#pragma unroll
+    for (int k = 0; k < kItems; ++k) {
+      const uint32_t off = wave * (kWave * kItems) + k * kWave + lane;
+      if (off < tile_cnt) {
+        const uint32_t d = (key[k] >> shift) & (NB - 1);
+        const uint32_t pos = s_cnt[wave][d] + lrank[k];
+        s_key[pos] = key[k];
+        s_pay[pos] = pay[k];
+      }
+    }
+    __syncthreads();
+
+    for (uint32_t j = tid; j < tile_cnt; j += kBlock) {
+      const uint32_t kk = s_key[j];
+      const uint32_t g = s_gofs[(kk >> shift) & (NB - 1)] + j;
+      kout[g] = kk;
+      pout[g] = s_pay[j];
+    }
+    __syncthreads();
+  }
+}
+
+// ---- unique: heads of runs in the sorted keys ----
+// Thread t of a block owns the 8 consecutive positions base + 8t .. base + 8t + 7.
+__device__ __forceinline__ uint32_t head_flags(const uint32_t* __restrict__ keys, uint32_t n, uint32_t i0,
+                                               uint32_t (&k)[kItems]) {
+  uint32_t flags = 0;
+  if (i0 >= n) return 0;
+  uint32_t prev = i0 ? keys[i0 - 1] : 0u;
+  if (i0 + kItems <= n) {
+    const uint4 a = *reinterpret_cast<const uint4*>(keys + i0);
+    const uint4 b = *reinterpret_cast<const uint4*>(keys + i0 + 4);
+    k[0] = a.x; k[1] = a.y; k[2] = a.z; k[3] = a.w; k[4] = b.x; k[5] = b.y; k[6] = b.z; k[7] = b.w;
+  } else {
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) k[j] = (i0 + j < n) ? keys[i0 + j] : 0u;
+  }
+#pragma unroll
+  for (int j = 0; j < kItems; ++j) {
+    if (i0 + j < n && (i0 + j == 0 || k[j] != prev)) flags |= 1u << j;
+    prev = k[j];
+  }
+  return flags;
+}
+
+__global__ __launch_bounds__(kBlock) void k_unique_count(const uint32_t* __restrict__ keys, uint32_t n,
+                                                         uint32_t* __restrict__ blk_heads) {
+  __shared__ uint32_t s_w[kWavesPerBlock];
+  uint32_t k[kItems];
+  const uint32_t i0 = blockIdx.x * kUniqueTile + threadIdx.x * kItems;
+  uint32_t cnt = __popc(head_flags(keys, n, i0, k));
+  uint32_t tot;
+  block_exclusive_scan(cnt, s_w, &tot);
+  if (threadIdx.x == 0) blk_heads[blockIdx.x] = tot;
+}
+
+// Single block: exclusive scan of blk_heads[nb] in place; counters[0] = U, counters[1] = 0; seg_off[U] = n.
+__global__ __launch_bounds__(kBlock) void k_unique_scan(uint32_t* __restrict__ blk_heads, uint32_t nb, uint32_t n,
+                                                        uint32_t* __restrict__ counters,
+                                                        uint32_t* __restrict__ seg_off) {
+  __shared__ uint32_t s_w[kWavesPerBlock];
+  uint32_t carry = 0;
+  for (uint32_t base = 0; base < nb; base += kBlock) {
+    const uint32_t i = base + threadIdx.x;
+    const uint32_t v = i < nb ? blk_heads[i] : 0u;
+    uint32_t tot;
+    const uint32_t ex = block_exclusive_scan(v, s_w, &tot);
+    if (i < nb) blk_heads[i] = carry + ex;
+    carry += tot;
+  }
+  if (threadIdx.x == 0) {
+    counters[0] = carry;
+    counters[1] = 0;
+    seg_off[carry] = n;
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void k_unique_write(const uint32_t* __restrict__ keys, uint32_t n,
+                                                         const uint32_t* __restrict__ blk_heads,
+                                                         uint32_t* __restrict__ unique_keys,
+                                                         uint32_t* __restrict__ seg_off) {
+  __shared__ uint32_t s_w[kWavesPerBlock];
+  uint32_t k[kItems];
+  const uint32_t i0 = blockIdx.x * kUniqueTile + threadIdx.x * kItems;
+  const uint32_t flags = head_flags(keys, n, i0, k);
+  uint32_t u = blk_heads[blockIdx.x] + block_exclusive_scan(__popc(flags), s_w, nullptr);
+#pragma unroll
+  for (int j = 0; j < kItems; ++j)
+    if (flags & (1u << j)) {
+      unique_keys[u] = k[j];
+      seg_off[u] = i0 + j;
+      ++u;
+    }
+}
+
+template <int BITS>
+hipError_t pass_hist(const SortPlan& p, int shift, const uint32_t* keys, uint32_t* hist, hipStream_t stream) {
+  hipLaunchKernelGGL(k_radix_hist<BITS>, dim3(p.nblk), dim3(kBlock), 0, stream, keys, p.n, p.chunk, shift, p.nblk,
+                     hist);
+  return hipGetLastError();
+}
+template <int BITS>
+hipError_t pass_scatter(const SortPlan& p, int shift, const uint32_t* kin, const uint32_t* pin, uint32_t* kout,
+                        uint32_t* pout, const uint32_t* hist, const uint32_t* total, hipStream_t stream) {
+  hipLaunchKernelGGL(k_radix_scatter<BITS>, dim3(p.nblk), dim3(kBlock), 0, stream, kin, pin, kout, pout, p.n, p.chunk,
+                     shift, p.nblk, hist, total);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+SortPlan make_sort_plan(uint32_t n, int key_bits) {
+  SortPlan p;
+  p.n = n;
+  if (key_bits < 1) key_bits = 1;
+  p.passes = (key_bits + 7) / 8;
+  p.bits = (key_bits + p.passes - 1) / p.passes;
+  uint32_t tiles = (n + kSortTile - 1) / kSortTile;
+  if (tiles == 0) tiles = 1;
+  uint32_t target = tiles < kSortMaxBlocks ? tiles : kSortMaxBlocks;
+  uint32_t tiles_per_blk = (tiles + target - 1) / target;
+  p.chunk = tiles_per_blk * kSortTile;
+  p.nblk = (tiles + tiles_per_blk - 1) / tiles_per_blk;  // every block starts below n
+  return p;
+}
+
+#define PEMB_BITS_SWITCH(bits, CALL) \
+  switch (bits) {                    \
+    case 1: return CALL(1);          \
+    case 2: return CALL(2);          \
+    case 3: return CALL(3);          \
+    case 4: return CALL(4);          \
+    case 5: return CALL(5);          \
+    case 6: return CALL(6);          \
+    case 7: return CALL(7);          \
+    case 8: return CALL(8);          \
+    default: return hipErrorInvalidValue; \
+  }
+
+hipError_t launch_radix_hist(const SortPlan& p, int shift, const uint32_t* keys, uint32_t* hist, hipStream_t stream) {
+#define CALL(B) pass_hist<B>(p, shift, keys, hist, stream)
+  PEMB_BITS_SWITCH(p.bits, CALL)
+#undef CALL
+}
+
+hipError_t launch_radix_scan(const SortPlan& p, uint32_t* hist, uint32_t* total, hipStream_t stream) {
+  hipLaunchKernelGGL(k_radix_scan, dim3(1u << p.bits), dim3(kBlock), 0, stream, hist, p.nblk, total);
+  return hipGetLastError();
+}
+
+hipError_t launch_radix_scatter(const SortPlan& p, int shift, const uint32_t* kin, const uint32_t* pin,
+                                uint32_t* kout, uint32_t* pout, const uint32_t* hist, const uint32_t* total,
+                                hipStream_t stream) {
+#define CALL(B) pass_scatter<B>(p, shift, kin, pin, kout, pout, hist, total, stream)
+  PEMB_BITS_SWITCH(p.bits, CALL)
+#undef CALL
+}
+
+hipError_t launch_unique(const uint32_t* keys, uint32_t n, uint32_t* blk_heads, uint32_t* unique_keys,
+                         uint32_t* seg_off, uint32_t* counters, hipStream_t stream) {
+  const uint32_t nb = (n + kUniqueTile - 1) / kUniqueTile;  // 0 when n == 0
+  if (nb) {
+    hipLaunchKernelGGL(k_unique_count, dim3(nb), dim3(kBlock), 0, stream, keys, n, blk_heads);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(k_unique_scan, dim3(1), dim3(kBlock), 0, stream, blk_heads, nb, n, counters, seg_off);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (nb) {
+    hipLaunchKernelGGL(k_unique_write, dim3(nb), dim3(kBlock), 0, stream, keys, n, blk_heads, unique_keys, seg_off);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+}  // namespace pemb

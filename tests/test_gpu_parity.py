@@ -1,0 +1,152 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same
+seeded inputs.  Integer outputs (rows, unique keys, segment offsets, bag lists) bit-exact; pooled
+activations and updated rows within 1e-5 rel + 1e-6 abs (fp32 tables) or 2e-2 rel (bf16 tables)."""
+import numpy as np
+import pytest
+
+from oracle import oracle as O
+from paper_2111_05897_amd import workload as W
+from tests import util
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2111_05897_amd import binding
+    binding.load_library()   # no fallback: a missing library is an error
+    return binding
+
+
+def _cfg(tables, slot_tables, **kw):
+    return W.EmbConfig(tables=[W.TableDesc(*t) for t in tables],
+                       slots=[W.SlotDesc(t, W.default_salt(s)) for s, t in enumerate(slot_tables)], **kw)
+
+
+# ----------------------------------------------------------------------------- init + row io
+@pytest.mark.parametrize("dtype", [W.F32, W.BF16])
+def test_table_init_bit_identical_to_oracle(B, dtype):
+    cfg = _cfg([(5000, 16, dtype), (1 << 12, 128, dtype)], [0, 1], init_seed=99, init_lo=-0.5, init_hi=0.25)
+    ctx = B.EmbContext.from_config(cfg, max_batch=4, max_ids=16)
+    orc = O.Oracle.from_config(cfg, dense=True)
+    for t, td in enumerate(cfg.tables):
+        rows = np.arange(td.rows, dtype=np.uint64)
+        gw, ga = ctx.emb_read_rows(t, rows)
+        ow, oa = orc.read_rows(t, rows)
+        np.testing.assert_array_equal(gw.view(np.uint32), ow.view(np.uint32))
+        np.testing.assert_array_equal(ga, oa)
+    # write_rows / read_rows round trip (values rounded to the storage type)
+    rows = np.array([3, 4999, 17], dtype=np.uint64)
+    vals = np.random.default_rng(0).standard_normal((3, 16)).astype(np.float32)
+    ctx.emb_write_rows(0, rows, vals, np.array([1.0, 2.0, 3.0], np.float32))
+    orc.write_rows(0, rows, vals, np.array([1.0, 2.0, 3.0], np.float32))
+    gw, ga = ctx.emb_read_rows(0, rows)
+    ow, oa = orc.read_rows(0, rows)
+    np.testing.assert_array_equal(gw, ow)
+    np.testing.assert_array_equal(ga, oa)
+    ctx.close()
+
+
+def test_argument_validation_returns_errors(B):
+    with pytest.raises(B.EmbError):
+        B.EmbContext([(100, 12, 0)], [(0, 1)], 1, 0, 0.1, 1e-8, 0.1, 1, -1.0, 1.0, 8, 64)      # dim 12
+    with pytest.raises(B.EmbError):
+        B.EmbContext([(100, 8, 0)], [(1, 1)], 1, 0, 0.1, 1e-8, 0.1, 1, -1.0, 1.0, 8, 64)       # slot -> table 1
+    with pytest.raises(B.EmbError):
+        B.EmbContext([(1 << 31, 8, 0)], [(0, 1)], 1, 0, 0.1, 1e-8, 0.1, 1, -1.0, 1.0, 8, 64)   # too many rows
+    ctx = B.EmbContext([(100, 8, 0)], [(0, 1)], 1, 0, 0.1, 1e-8, 0.1, 1, -1.0, 1.0, 8, 64)
+    b = W.random_batch(1, 16, 1, 3, 1000, allow_empty=False)                                  # batch 16 > max 8
+    with pytest.raises(B.EmbError) as ei:
+        ctx.emb_lookup_pool(B.DeviceBatch(b.batch_size, b.ids, b.offsets))
+    assert ei.value.code == B.EMB_EINVAL
+    with pytest.raises(B.EmbError) as ei:
+        ctx.emb_read_dedup()                                                                  # no backward yet
+    assert ei.value.code == B.EMB_ESTATE
+    with pytest.raises(B.EmbError):
+        ctx.emb_read_rows(0, np.array([100], np.uint64))                                      # row out of range
+    ctx.close()
+
+
+# ----------------------------------------------------------------------------- small irregular cases
+@pytest.mark.parametrize("dtype", [W.F32, W.BF16])
+@pytest.mark.parametrize("dim", [8, 16, 32, 64, 128])
+@pytest.mark.parametrize("opt", [W.OPT_SGD, W.OPT_ROWWISE_ADAGRAD])
+def test_small_ragged_batches_every_dim_dtype_optimizer(B, dtype, dim, opt):
+    # empty bags, duplicates inside bags, rows not a power of two, N not a multiple of any tile
+    cfg = _cfg([(1000, dim, dtype)], [0, 0, 0], opt=opt, lr=0.05, init_seed=dim + 7 * dtype)
+    w = W.Workload("ragged", 0, cfg, 37, "uniform", 0, 9, "uniform", 5000, seed=dim)
+    batches = [W.random_batch(10 * dim + s, 37, 3, 9, 5000) for s in range(2)]
+    grads = [np.random.default_rng(s).standard_normal((37, 3 * dim)).astype(np.float32) for s in range(2)]
+    util.run_steps(B, W, O, w, steps=2, batches=batches, grads=grads)
+
+
+def test_mixed_tables_and_dims(B):
+    cfg = _cfg([(300, 8, W.BF16), (1 << 10, 16, W.F32), (77, 32, W.BF16), (1 << 9, 64, W.F32), (200, 128, W.BF16)],
+               [s % 5 for s in range(12)], init_seed=5)
+    w = W.Workload("mixed", 0, cfg, 53, "uniform", 0, 6, "uniform", 3000, seed=3)
+    batches = [W.random_batch(70 + s, 53, 12, 6, 3000) for s in range(2)]
+    grads = [np.random.default_rng(s).standard_normal((53, cfg.pooled_width)).astype(np.float32) for s in range(2)]
+    util.run_steps(B, W, O, w, steps=2, batches=batches, grads=grads)
+
+
+def test_degenerate_batches(B):
+    cfg = _cfg([(64, 64, W.F32)], [0, 0], hash_kind=W.HASH_IDENTITY_MOD)
+    w = W.Workload("degenerate", 0, cfg, 4, "const", 1, 1, "uniform", 64, seed=1)
+    S, D = 2, 64
+    rng = np.random.default_rng(4)
+
+    def grad(Bsz):
+        return rng.standard_normal((Bsz, S * D)).astype(np.float32)
+
+    cases = []
+    # no ids at all (every bag empty)
+    cases.append((W.Batch(4, np.zeros(0, np.uint64), np.zeros(4 * S + 1, np.int32)), grad(4)))
+    # a single id
+    off = np.zeros(4 * S + 1, np.int32)
+    off[3:] = 1
+    cases.append((W.Batch(4, np.array([9], np.uint64), off), grad(4)))
+    # one key repeated 5000 times: a single segment crossing more than a hundred tiles
+    n = 5000
+    Bsz = 50
+    lens = np.full(Bsz * S, n // (Bsz * S), np.int64)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    cases.append((W.Batch(Bsz, np.full(int(off[-1]), 7, np.uint64), off), grad(Bsz)))
+    # every id distinct (U = N), in descending order
+    off = np.arange(0, 32 * S + 1, dtype=np.int32)
+    cases.append((W.Batch(32, np.arange(63, -1, -1, dtype=np.uint64), off), grad(32)))
+    # two keys only, lengths chosen so segment ends fall exactly on tile edges (32) and next to them
+    for n0 in (31, 32, 33, 64, 2047, 2048, 2049):
+        ids = np.concatenate([np.full(n0, 1, np.uint64), np.full(40, 2, np.uint64)])
+        off = np.zeros(2 * S + 1, np.int32)
+        off[1:] = [n0, n0, n0 + 40, n0 + 40]
+        cases.append((W.Batch(2, ids, off), grad(2)))
+    for b, g in cases:
+        util.run_steps(B, W, O, w, steps=1, batches=[b], grads=[g])
+
+
+def test_hot_key_segments_are_summed_accurately(B):
+    # Zipf-like skew: a few keys own most occurrences, so segments span thousands of tiles
+    cfg = _cfg([(1 << 12, 64, W.F32)], [0] * 4, hash_kind=W.HASH_IDENTITY_MOD)
+    Bsz, S = 2048, 4
+    rng = np.random.default_rng(8)
+    lens = rng.integers(1, 40, size=Bsz * S)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    n = int(off[-1])
+    ids = np.where(rng.random(n) < 0.6, rng.integers(0, 3, n), rng.integers(0, 1 << 12, n)).astype(np.uint64)
+    w = W.Workload("hot", 0, cfg, Bsz, "const", 1, 1, "uniform", 1 << 12, seed=1)
+    util.run_steps(B, W, O, w, steps=2, batches=[W.Batch(Bsz, ids, off)] * 2,
+                   grads=[rng.standard_normal((Bsz, S * 64)).astype(np.float32) for _ in range(2)])
+
+
+# ----------------------------------------------------------------------------- the five configurations
+@pytest.mark.parametrize("index,scale,steps", [(0, 1.0, 2), (1, 1 / 16, 2), (2, 1 / 64, 3), (3, 1 / 256, 1),
+                                               (4, 1 / 256, 2)])
+def test_configs_scaled(B, index, scale, steps):
+    w = W.make_workload(index, scale=scale)
+    util.run_steps(B, W, O, w, steps=steps)
+
+
+def test_config1_full_size(B):
+    util.run_steps(B, W, O, W.make_workload(1), steps=1, dense=False)
