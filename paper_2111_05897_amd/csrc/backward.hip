@@ -21,6 +21,13 @@ __device__ __forceinline__ float4 add4(float4 a, float4 b) {
   return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w);
 }
 
+__device__ __forceinline__ void kahan_add4(float4& s, float4& c, float4 x) {
+  kahan_add(s.x, c.x, x.x);
+  kahan_add(s.y, c.y, x.y);
+  kahan_add(s.z, c.z, x.z);
+  kahan_add(s.w, c.w, x.w);
+}
+
 // Row update by a group of LG lanes; lane owns elements [4*lane, 4*lane+4) and G holds its part of
 // the row's gradient.  OPT 0: SGD.  OPT 1: row-wise Adagrad (mean of G^2 over the row feeds one
 // accumulator; eps outside the square root).
@@ -178,17 +185,18 @@ __global__ __launch_bounds__(kBlock) void k_fixup(FixupArgs a) {
     const uint32_t s = a.seg_off[u], end = a.seg_off[u + 1];
     const uint32_t t0 = s / kTile, t1 = (end - 1) / kTile;
     const uint32_t np = t1 - t0 + 1;
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    // compensated sums: a hot key's segment can span thousands of tiles
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f), comp = acc;
     for (uint32_t k = g; k < np; k += NG) {
       const size_t slot = (k == 0) ? (size_t)2 * t0 + 1 : (size_t)2 * (t0 + k);
-      acc = add4(acc, load_frag4(a.partials + slot * a.pstride + lane * 4));
+      kahan_add4(acc, comp, load_frag4(a.partials + slot * a.pstride + lane * 4));
     }
     store_frag4(&s_part[g][lane * 4], acc);
     __syncthreads();
     if (g == 0) {
-      float4 tot = make_float4(0.f, 0.f, 0.f, 0.f);
+      float4 tot = make_float4(0.f, 0.f, 0.f, 0.f), tc = tot;
       const int ng = np < (uint32_t)NG ? (int)np : NG;
-      for (int gg = 0; gg < ng; ++gg) tot = add4(tot, load_frag4(&s_part[gg][lane * 4]));
+      for (int gg = 0; gg < ng; ++gg) kahan_add4(tot, tc, load_frag4(&s_part[gg][lane * 4]));
       apply_update<T, D, OPT>(w, a.accs, key - a.key_base, tot, lane, a.lr, a.eps);
     }
     __syncthreads();

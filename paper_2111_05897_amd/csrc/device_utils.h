@@ -39,9 +39,20 @@ __device__ __forceinline__ uint32_t f32_to_bf16(float f) {
 
 // Initial value of one table element (definition in include/persia_emb.h): separate multiply and add.
 __device__ __forceinline__ float init_value(uint64_t table_key, uint64_t elem, float scale, float mid) {
+#pragma clang fp contract(off)  // two roundings: the product must not fuse into the add
   uint64_t h = mix64(table_key + elem);
   int k = (int)(h >> 40) - (1 << 23);
-  return __fadd_rn(__fmul_rn((float)k, scale), mid);
+  float prod = (float)k * scale;
+  return prod + mid;
+}
+
+// Compensated add: sum += x with the rounding error of every add carried in comp.
+__device__ __forceinline__ void kahan_add(float& sum, float& comp, float x) {
+#pragma clang fp contract(off)
+  const float y = x - comp;
+  const float t = sum + y;
+  comp = (t - sum) - y;
+  sum = t;
 }
 
 // ---- 4-element row fragments (what one lane owns of a row in the backward kernels) ----

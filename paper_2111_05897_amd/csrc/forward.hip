@@ -63,9 +63,11 @@ __global__ __launch_bounds__(kBlock) void k_gather_pool(GatherArgs a) {
   const T* __restrict__ base = reinterpret_cast<const T*>(a.w) + lane * VEC;
   const uint64_t* __restrict__ ids = a.ids;
 
-  float acc[VEC];
+  // Compensated (Kahan) fp32 sum in batch order: the error stays at one or two roundings of the
+  // result however long the bag is; the extra adds are free next to the row loads.
+  float acc[VEC], comp[VEC];
 #pragma unroll
-  for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+  for (int e = 0; e < VEC; ++e) acc[e] = comp[e] = 0.f;
 
   int i = beg;
   for (; i + 4 <= end; i += 4) {
@@ -78,14 +80,14 @@ __global__ __launch_bounds__(kBlock) void k_gather_pool(GatherArgs a) {
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) acc[e] += r[j].v[e];
+      for (int e = 0; e < VEC; ++e) kahan_add(acc[e], comp[e], r[j].v[e]);
   }
   for (; i < end; ++i) {
     RowVec<T, VEC> r;
     uint32_t row = hash_row(ids[i], salt, a.rows, a.mask, a.mix);
     r.load(base + (size_t)row * D);
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) acc[e] += r.v[e];
+    for (int e = 0; e < VEC; ++e) kahan_add(acc[e], comp[e], r.v[e]);
   }
 
   float* out = a.pooled + (size_t)b * a.width + a.slot_col[slot] + lane * VEC;

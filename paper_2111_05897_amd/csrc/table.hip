@@ -15,11 +15,7 @@ __global__ __launch_bounds__(kBlock) void k_init_table(T* __restrict__ w, uint64
     uint64_t e = q * 4;
     float4 v = make_float4(init_value(table_key, e, scale, mid), init_value(table_key, e + 1, scale, mid),
                            init_value(table_key, e + 2, scale, mid), init_value(table_key, e + 3, scale, mid));
-    if constexpr (sizeof(T) == 2) {  // the fp32 value is rounded to bf16 storage
-      store_frag4(w + e, v);
-    } else {
-      store_frag4(w + e, v);
-    }
+    store_frag4(w + e, v);  // bf16 tables round the fp32 value to storage here
   }
 }
 
