@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of the embedding hot path on one MI355X.
+
+A step = one pass of the whole path (emb_lookup_pool, then emb_backward_update: hash, gather +
+sum-pool, key build, radix-sort dedup, segmented gradient reduce, fused row-wise optimizer) over one
+synthetic batch that is already resident in HBM.  Prints ONE JSON line with the throughput in
+embedding IDs/s, the roofline figure of the dominant kernel (algorithmic bytes per launch / average
+launch time from HIP events on the launch stream) and the CPU oracle timed beside it.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes(N, bags, U, U_multi, D, e):
+    """Bytes the method itself must move per launch of each kernel stage and per whole step
+    (sort passes and partial sums are implementation overhead and not counted)."""
+    fwd = 8 * N + 4 * (bags + 1) + N * D * e + bags * D * 4        # ids, offsets, row gathers, pooled write
+    keys = 8 * N + 4 * (bags + 1) + 8 * N                            # ids re-read, (key, bag) pairs written
+    red = 8 * N + N * D * 4 + (U - U_multi) * (2 * D * e + 8)        # sorted pairs, grad gathers, row + acc RMW
+    fix = U_multi * (2 * D * e + 8)                                  # rows of segments that span tiles
+    step = fwd + 4 * N + 8 * N + 8 * U + N * D * 4 + U * (2 * D * e + 8)
+    return {"gather_pool": fwd, "build_keys": keys, "reduce_update": red, "fixup": fix, "step": step}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="index into BASELINE.json configs (single-table ones)")
+    ap.add_argument("--distinct-batches", type=int, default=4, help="synthetic batches generated and cycled")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain 1 GiB device-to-device copies (reference for rocprofv3 byte counters)")
+    ap.add_argument("--cpu-samples", type=int, default=0, help="samples of batch 0 the oracle is timed on (0 = all)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2111_05897_amd import binding, workload as W
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    binding.load_library()
+    w = W.make_workload(args.config)
+    cfg = w.cfg
+    assert len(cfg.tables) == 1, "bench covers the single-table configurations"
+    D, e = cfg.tables[0].dim, (2 if cfg.tables[0].dtype == W.BF16 else 4)
+    nb = max(1, min(args.distinct_batches, args.steps))
+    t0 = time.time()
+    host_batches = [W.make_batch(w, s) for s in range(nb)]
+    batches = [binding.DeviceBatch(b.batch_size, b.ids, b.offsets) for b in host_batches]
+    gen = torch.Generator(device="cuda")
+    grads = []
+    for s in range(nb):
+        gen.manual_seed(w.seed * 1000 + s)
+        grads.append(torch.randn((w.batch, cfg.pooled_width), generator=gen, device="cuda", dtype=torch.float32))
+    ctx = binding.EmbContext.from_config(cfg, max_batch=w.batch, max_ids=max(b.num_ids for b in batches))
+    pooled = torch.empty((w.batch, cfg.pooled_width), dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    def step(i):
+        b = batches[i % nb]
+        ctx.emb_lookup_pool(b, pooled)
+        ctx.emb_backward_update(b, grads[i % nb])
+        return b.num_ids
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ids_done = 0
+    for i in range(args.steps):
+        ids_done += step(args.warmup + i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    ids_per_s = ids_done / elapsed
+
+    # per-kernel timing pass (HIP events on the launch stream, inside the library)
+    ctx.emb_set_profiling(True)
+    ctx.emb_reset_stage_ms()
+    N_sum = U_sum = Um_sum = 0
+    for i in range(args.steps):
+        N_sum += step(args.warmup + i)
+        keys, seg_off, _ = ctx.emb_read_dedup()
+        U_sum += len(keys)
+        s, en = seg_off[:-1].astype(np.int64), seg_off[1:].astype(np.int64)
+        Um_sum += int(np.count_nonzero(s // 32 != (en - 1) // 32))
+    stages = ctx.emb_read_stage_ms()
+    ctx.emb_set_profiling(False)
+    N_avg, U_avg, Um_avg = N_sum / args.steps, U_sum / args.steps, Um_sum / args.steps
+    ab = algorithmic_bytes(N_avg, w.bags, U_avg, Um_avg, D, e)
+    stage_ms = {k: (ms / max(c, 1), c // args.steps) for k, (ms, c) in stages.items() if c}
+    per_step_ms = {k: ms / args.steps for k, (ms, c) in stages.items() if c}
+    dom = max((k for k in per_step_ms if k in ab), key=lambda k: per_step_ms[k])
+    dom_ms = stage_ms[dom][0]
+    achieved = ab[dom] / (dom_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "avg_launch_ms": round(dom_ms, 4), "algorithmic_bytes_per_launch": int(ab[dom])}
+    traffic_file = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json")
+    if os.path.exists(traffic_file):   # HBM bytes per launch measured with rocprofv3 --pmc (see profiles/)
+        try:
+            roofline["traffic"] = json.load(open(traffic_file)).get(dom)
+        except Exception:
+            pass
+
+    out = {
+        "metric": "embedding IDs/sec (lookup+bwd+update), 1 GPU", "value": round(ids_per_s, 1), "unit": "IDs/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32" if e == 4 else "bf16",
+        "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "slots": cfg.num_slots, "rows": cfg.tables[0].rows, "dim": D,
+                   "ids_per_step": round(N_avg), "unique_rows_per_step": round(U_avg),
+                   "distinct_batches": nb, "optimizer": "rowwise_adagrad" if cfg.opt else "sgd"},
+        "effective_GBps_step": round(ab["step"] / (ms_per_step * 1e-3) / 1e9, 1),
+        "effective_frac_of_hbm_peak": round(ab["step"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "stage_ms_per_step": {k: round(v, 4) for k, v in per_step_ms.items()},
+        "stage_GBps": {k: round(ab[k] / (stage_ms[k][0] * 1e-3) / 1e9, 1) for k in stage_ms if k in ab},
+        "setup_s": round(setup_s, 1),
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import oracle as O   # the checker, timed as a baseline only
+        hb = host_batches[0]
+        S = cfg.num_slots
+        bs = args.cpu_samples if args.cpu_samples else hb.batch_size
+        bs = min(bs, hb.batch_size)
+        off = hb.offsets[: bs * S + 1]
+        ids = hb.ids[: int(off[-1])]
+        dp = grads[0][:bs].cpu().numpy()
+        orc = O.Oracle.from_config(cfg, dense=False)
+        t0 = time.perf_counter()
+        orc.lookup_pool(ids, off)
+        orc.backward_update(ids, off, dp)
+        cpu_s = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(len(ids) / cpu_s, 1), "unit": "IDs/s", "cores": 1, "kind": "oracle",
+                               "sample": f"{bs} of {hb.batch_size} samples of batch 0 ({len(ids)} IDs), one "
+                                         f"lookup+bwd+update step, sparse-table oracle, {cpu_s:.1f} s, "
+                                         f"{os.cpu_count()} cores visible"}
+        orc.close()
+    ctx.close()
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

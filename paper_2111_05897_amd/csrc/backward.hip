@@ -8,7 +8,7 @@
 //   - a run that began before the tile is stored as a partial in slot first[tile];
 //   - otherwise a run that continues past the tile is stored in slot last[tile];
 //   - every other run is a complete segment and the optimizer is applied to its row at once.
-// Segments that span tiles are listed by find_multi and finished by the fix-up kernel, which adds
+// Segments that span tiles are listed by the unique kernels and finished by the fix-up kernel, which adds
 // last[t0], first[t0+1], ..., first[t1] in a fixed order and then applies the optimizer.  No float
 // atomics: the summation order is a function of the batch alone, so results are reproducible.
 #include "device_utils.h"
@@ -144,16 +144,6 @@ __global__ __launch_bounds__(kBlock) void k_tile_reduce_update(TileArgs a) {
     apply_update<T, D, OPT>(w, a.accs, cur - a.key_base, acc, lane, a.lr, a.eps);
 }
 
-// Thread per unique key: list the segments that cross a tile edge.
-__global__ __launch_bounds__(kBlock) void k_find_multi(const uint32_t* __restrict__ seg_off,
-                                                       uint32_t* __restrict__ counters,
-                                                       uint32_t* __restrict__ multi_list) {
-  const uint32_t u = blockIdx.x * kBlock + threadIdx.x;
-  if (u >= counters[0]) return;
-  const uint32_t s = seg_off[u], e = seg_off[u + 1];
-  if (s / kTile != (e - 1) / kTile) multi_list[atomicAdd(&counters[1], 1u)] = u;
-}
-
 struct FixupArgs {
   const uint32_t* unique_keys;
   const uint32_t* seg_off;
@@ -187,9 +177,17 @@ __global__ __launch_bounds__(kBlock) void k_fixup(FixupArgs a) {
     const uint32_t np = t1 - t0 + 1;
     // compensated sums: a hot key's segment can span thousands of tiles
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f), comp = acc;
-    for (uint32_t k = g; k < np; k += NG) {
-      const size_t slot = (k == 0) ? (size_t)2 * t0 + 1 : (size_t)2 * (t0 + k);
-      kahan_add4(acc, comp, load_frag4(a.partials + slot * a.pstride + lane * 4));
+    for (uint32_t k0 = g; k0 < np; k0 += 4 * NG) {  // four loads in flight per lane
+      float4 v[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t k = k0 + j * NG;
+        const size_t slot = (k == 0) ? (size_t)2 * t0 + 1 : (size_t)2 * (t0 + k);
+        v[j] = k < np ? load_frag4(a.partials + slot * a.pstride + lane * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (k0 + j * NG < np) kahan_add4(acc, comp, v[j]);
     }
     store_frag4(&s_part[g][lane * 4], acc);
     __syncthreads();
@@ -287,14 +285,6 @@ hipError_t launch_tile_reduce_update(const TableView& t, const BackwardArgs& b, 
   } else {
     PEMB_DIM_SWITCH(float, t.dim, launch_tile_td, a, b.opt, stream)
   }
-}
-
-hipError_t launch_find_multi(const BackwardArgs& b, hipStream_t stream) {
-  if (b.n == 0) return hipSuccess;
-  const uint32_t grid = (b.n + kBlock - 1) / kBlock;  // U <= n; threads past U exit
-  hipLaunchKernelGGL(k_find_multi, dim3(grid), dim3(kBlock), 0, stream, b.seg_off, const_cast<uint32_t*>(b.counters),
-                     b.multi_list);
-  return hipGetLastError();
 }
 
 hipError_t launch_fixup(const TableView& t, const BackwardArgs& b, hipStream_t stream) {

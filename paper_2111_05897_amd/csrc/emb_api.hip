@@ -25,12 +25,11 @@ enum Stage {
   ST_SORT_SCATTER,
   ST_UNIQUE,
   ST_REDUCE_UPDATE,
-  ST_FIND_MULTI,
   ST_FIXUP,
   ST_COUNT
 };
 const char* const kStageNames[ST_COUNT] = {"gather_pool", "build_keys",    "sort_hist",  "sort_scan", "sort_scatter",
-                                           "unique",      "reduce_update", "find_multi", "fixup"};
+                                           "unique",      "reduce_update", "fixup"};
 
 struct EventRec {
   int stage;
@@ -56,7 +55,7 @@ struct emb_ctx {
   uint32_t* key_base_dev = nullptr;  // [T]
   // workspace
   uint32_t *keys[2] = {nullptr, nullptr}, *bags[2] = {nullptr, nullptr};
-  uint32_t *hist = nullptr, *total = nullptr, *blk_heads = nullptr;
+  uint32_t *hist = nullptr, *total = nullptr, *blk_heads = nullptr, *blk_multi = nullptr;
   uint32_t *unique_keys = nullptr, *seg_off = nullptr, *multi_list = nullptr, *counters = nullptr, *ranges = nullptr;
   float* partials = nullptr;
   // last backward
@@ -386,7 +385,8 @@ int emb_backward_update(emb_ctx* ctx, const emb_batch* batch, const float* d_poo
   ctx->have_dedup = true;
   ctx->sorted_buf = 0;
   if (n == 0) {  // nothing to update; leave an empty index form behind
-    CKH(launch_unique(ctx->keys[0], 0, ctx->blk_heads, ctx->unique_keys, ctx->seg_off, ctx->counters, stream),
+    CKH(launch_unique(ctx->keys[0], 0, ctx->blk_heads, ctx->blk_multi, ctx->unique_keys, ctx->seg_off,
+                      ctx->multi_list, ctx->counters, stream),
         "unique");
     return EMB_OK;
   }
@@ -419,7 +419,8 @@ int emb_backward_update(emb_ctx* ctx, const emb_batch* batch, const float* d_poo
   ctx->sorted_buf = src;
   {
     StageTimer tm(ctx, ST_UNIQUE, stream);
-    CKH(launch_unique(ctx->keys[src], n, ctx->blk_heads, ctx->unique_keys, ctx->seg_off, ctx->counters, stream),
+    CKH(launch_unique(ctx->keys[src], n, ctx->blk_heads, ctx->blk_multi, ctx->unique_keys, ctx->seg_off,
+                      ctx->multi_list, ctx->counters, stream),
         "unique");
   }
   BackwardArgs a{};
@@ -449,10 +450,6 @@ int emb_backward_update(emb_ctx* ctx, const emb_batch* batch, const float* d_poo
     StageTimer tm(ctx, ST_REDUCE_UPDATE, stream);
     a.range = multi_table ? ctx->ranges + t : nullptr;
     CKH(launch_tile_reduce_update(ctx->tables[t], a, stream), "tile_reduce_update");
-  }
-  {
-    StageTimer tm(ctx, ST_FIND_MULTI, stream);
-    CKH(launch_find_multi(a, stream), "find_multi");
   }
   for (size_t t = 0; t < ctx->tables.size(); ++t) {
     StageTimer tm(ctx, ST_FIXUP, stream);

@@ -160,7 +160,7 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(const uint32_t* __rest
   }
 }
 
-// ---- unique: heads of runs in the sorted keys ----
+// ---- unique: heads of runs in the sorted keys, and the list of runs that cross a tile edge ----
 // Thread t of a block owns the 8 consecutive positions base + 8t .. base + 8t + 7.
 __device__ __forceinline__ uint32_t head_flags(const uint32_t* __restrict__ keys, uint32_t n, uint32_t i0,
                                                uint32_t (&k)[kItems]) {
@@ -183,52 +183,107 @@ __device__ __forceinline__ uint32_t head_flags(const uint32_t* __restrict__ keys
   return flags;
 }
 
-__global__ __launch_bounds__(kBlock) void k_unique_count(const uint32_t* __restrict__ keys, uint32_t n,
-                                                         uint32_t* __restrict__ blk_heads) {
-  __shared__ uint32_t s_w[kWavesPerBlock];
-  uint32_t k[kItems];
-  const uint32_t i0 = blockIdx.x * kUniqueTile + threadIdx.x * kItems;
-  uint32_t cnt = __popc(head_flags(keys, n, i0, k));
-  uint32_t tot;
-  block_exclusive_scan(cnt, s_w, &tot);
-  if (threadIdx.x == 0) blk_heads[blockIdx.x] = tot;
+// End to assume for the last run of a block's stretch [.., blk_end): if the run goes on in the next
+// block it crosses the tile edge at blk_end (the stretch ends on one), which "blk_end + 1" expresses;
+// otherwise it ends where the stretch (or the list) ends.
+__device__ __forceinline__ uint32_t stretch_limit(const uint32_t* __restrict__ keys, uint32_t n, uint32_t blk_end) {
+  if (blk_end >= n) return n;
+  return keys[blk_end] == keys[blk_end - 1] ? blk_end + 1 : blk_end;
 }
 
-// Single block: exclusive scan of blk_heads[nb] in place; counters[0] = U, counters[1] = 0; seg_off[U] = n.
-__global__ __launch_bounds__(kBlock) void k_unique_scan(uint32_t* __restrict__ blk_heads, uint32_t nb, uint32_t n,
+// Shared by the count and the write kernel.  Returns, for this thread's heads, a bit mask of the
+// ones whose run crosses an edge between tiles of kTile positions.  first_local = index, among the
+// block's heads, of this thread's first head; n_heads = heads in the block; limit = stretch_limit().
+__device__ __forceinline__ uint32_t multi_flags(uint32_t flags, uint32_t i0, uint32_t first_local, uint32_t n_heads,
+                                                uint32_t limit, uint32_t* s_heads) {
+  uint32_t h = first_local;
+#pragma unroll
+  for (int j = 0; j < kItems; ++j)
+    if (flags & (1u << j)) s_heads[h++] = i0 + j;
+  __syncthreads();
+  uint32_t multi = 0;
+  h = first_local;
+#pragma unroll
+  for (int j = 0; j < kItems; ++j)
+    if (flags & (1u << j)) {
+      const uint32_t s = i0 + j;
+      const uint32_t e = (h + 1 < n_heads) ? s_heads[h + 1] : limit;  // end of the run, or a lower bound past an edge
+      if (s / kTile != (e - 1) / kTile) multi |= 1u << j;
+      ++h;
+    }
+  return multi;
+}
+
+__global__ __launch_bounds__(kBlock) void k_unique_count(const uint32_t* __restrict__ keys, uint32_t n,
+                                                         uint32_t* __restrict__ blk_heads,
+                                                         uint32_t* __restrict__ blk_multi) {
+  __shared__ uint32_t s_w[kWavesPerBlock];
+  __shared__ uint32_t s_heads[kUniqueTile];
+  uint32_t k[kItems];
+  const uint32_t i0 = blockIdx.x * kUniqueTile + threadIdx.x * kItems;
+  const uint32_t blk_end = (blockIdx.x + 1) * kUniqueTile;
+  const uint32_t limit = stretch_limit(keys, n, blk_end);
+  const uint32_t flags = head_flags(keys, n, i0, k);
+  uint32_t n_heads;
+  const uint32_t first_local = block_exclusive_scan(__popc(flags), s_w, &n_heads);
+  const uint32_t multi = multi_flags(flags, i0, first_local, n_heads, limit, s_heads);
+  uint32_t n_multi;
+  block_exclusive_scan(__popc(multi), s_w, &n_multi);
+  if (threadIdx.x == 0) {
+    blk_heads[blockIdx.x] = n_heads;
+    blk_multi[blockIdx.x] = n_multi;
+  }
+}
+
+// Single block: exclusive scans of blk_heads[nb] and blk_multi[nb] in place; counters[0] = U,
+// counters[1] = number of multi-tile runs; seg_off[U] = n.
+__global__ __launch_bounds__(kBlock) void k_unique_scan(uint32_t* __restrict__ blk_heads,
+                                                        uint32_t* __restrict__ blk_multi, uint32_t nb, uint32_t n,
                                                         uint32_t* __restrict__ counters,
                                                         uint32_t* __restrict__ seg_off) {
   __shared__ uint32_t s_w[kWavesPerBlock];
-  uint32_t carry = 0;
+  uint32_t carry = 0, carry_m = 0;
   for (uint32_t base = 0; base < nb; base += kBlock) {
     const uint32_t i = base + threadIdx.x;
-    const uint32_t v = i < nb ? blk_heads[i] : 0u;
     uint32_t tot;
-    const uint32_t ex = block_exclusive_scan(v, s_w, &tot);
+    const uint32_t ex = block_exclusive_scan(i < nb ? blk_heads[i] : 0u, s_w, &tot);
     if (i < nb) blk_heads[i] = carry + ex;
     carry += tot;
+    const uint32_t exm = block_exclusive_scan(i < nb ? blk_multi[i] : 0u, s_w, &tot);
+    if (i < nb) blk_multi[i] = carry_m + exm;
+    carry_m += tot;
   }
   if (threadIdx.x == 0) {
     counters[0] = carry;
-    counters[1] = 0;
+    counters[1] = carry_m;
     seg_off[carry] = n;
   }
 }
 
 __global__ __launch_bounds__(kBlock) void k_unique_write(const uint32_t* __restrict__ keys, uint32_t n,
                                                          const uint32_t* __restrict__ blk_heads,
+                                                         const uint32_t* __restrict__ blk_multi,
                                                          uint32_t* __restrict__ unique_keys,
-                                                         uint32_t* __restrict__ seg_off) {
+                                                         uint32_t* __restrict__ seg_off,
+                                                         uint32_t* __restrict__ multi_list) {
   __shared__ uint32_t s_w[kWavesPerBlock];
+  __shared__ uint32_t s_heads[kUniqueTile];
   uint32_t k[kItems];
   const uint32_t i0 = blockIdx.x * kUniqueTile + threadIdx.x * kItems;
+  const uint32_t blk_end = (blockIdx.x + 1) * kUniqueTile;
+  const uint32_t limit = stretch_limit(keys, n, blk_end);
   const uint32_t flags = head_flags(keys, n, i0, k);
-  uint32_t u = blk_heads[blockIdx.x] + block_exclusive_scan(__popc(flags), s_w, nullptr);
+  uint32_t n_heads;
+  const uint32_t first_local = block_exclusive_scan(__popc(flags), s_w, &n_heads);
+  const uint32_t multi = multi_flags(flags, i0, first_local, n_heads, limit, s_heads);
+  uint32_t m = blk_multi[blockIdx.x] + block_exclusive_scan(__popc(multi), s_w, nullptr);
+  uint32_t u = blk_heads[blockIdx.x] + first_local;
 #pragma unroll
   for (int j = 0; j < kItems; ++j)
     if (flags & (1u << j)) {
       unique_keys[u] = k[j];
       seg_off[u] = i0 + j;
+      if (multi & (1u << j)) multi_list[m++] = u;
       ++u;
     }
 }
@@ -296,19 +351,21 @@ hipError_t launch_radix_scatter(const SortPlan& p, int shift, const uint32_t* ki
 #undef CALL
 }
 
-hipError_t launch_unique(const uint32_t* keys, uint32_t n, uint32_t* blk_heads, uint32_t* unique_keys,
-                         uint32_t* seg_off, uint32_t* counters, hipStream_t stream) {
+hipError_t launch_unique(const uint32_t* keys, uint32_t n, uint32_t* blk_heads, uint32_t* blk_multi,
+                         uint32_t* unique_keys, uint32_t* seg_off, uint32_t* multi_list, uint32_t* counters,
+                         hipStream_t stream) {
   const uint32_t nb = (n + kUniqueTile - 1) / kUniqueTile;  // 0 when n == 0
   if (nb) {
-    hipLaunchKernelGGL(k_unique_count, dim3(nb), dim3(kBlock), 0, stream, keys, n, blk_heads);
+    hipLaunchKernelGGL(k_unique_count, dim3(nb), dim3(kBlock), 0, stream, keys, n, blk_heads, blk_multi);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(k_unique_scan, dim3(1), dim3(kBlock), 0, stream, blk_heads, nb, n, counters, seg_off);
+  hipLaunchKernelGGL(k_unique_scan, dim3(1), dim3(kBlock), 0, stream, blk_heads, blk_multi, nb, n, counters, seg_off);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (nb) {
-    hipLaunchKernelGGL(k_unique_write, dim3(nb), dim3(kBlock), 0, stream, keys, n, blk_heads, unique_keys, seg_off);
+    hipLaunchKernelGGL(k_unique_write, dim3(nb), dim3(kBlock), 0, stream, keys, n, blk_heads, blk_multi, unique_keys,
+                       seg_off, multi_list);
     e = hipGetLastError();
   }
   return e;
