@@ -162,6 +162,19 @@ int check_batch(emb_ctx* ctx, const emb_batch* b) {
   return EMB_OK;
 }
 
+// Every buffer the backward kernels dereference; a null here would be a device-side fault.
+bool workspace_complete(const emb_ctx* c) {
+  const void* ptrs[] = {c->keys[0],  c->keys[1],     c->bags[0], c->bags[1],    c->hist,     c->total,
+                        c->blk_heads, c->blk_multi,  c->unique_keys, c->seg_off, c->multi_list, c->counters,
+                        c->ranges,    c->partials,   c->key_base_dev, c->slots.salt, c->slots.rows, c->slots.mask,
+                        c->slots.key_base, c->slots.col};
+  for (const void* p : ptrs)
+    if (!p) return false;
+  for (const TableView& t : c->tables)
+    if (!t.w || !t.acc || !t.slot_list) return false;
+  return true;
+}
+
 int bit_length(uint64_t v) {
   int b = 0;
   while (v) {
@@ -318,6 +331,7 @@ int emb_create(const emb_config* cfg, emb_ctx** out) {
   CK(dev_alloc(ctx, &ctx->hist, (uint64_t)256 * kSortMaxBlocks), "hipMalloc(histograms)");
   CK(dev_alloc(ctx, &ctx->total, 256), "hipMalloc(digit totals)");
   CK(dev_alloc(ctx, &ctx->blk_heads, (cap + kUniqueTile - 1) / kUniqueTile + 1), "hipMalloc(block heads)");
+  CK(dev_alloc(ctx, &ctx->blk_multi, (cap + kUniqueTile - 1) / kUniqueTile + 1), "hipMalloc(block multi-tile counts)");
   CK(dev_alloc(ctx, &ctx->unique_keys, cap), "hipMalloc(unique keys)");
   CK(dev_alloc(ctx, &ctx->seg_off, cap + 1), "hipMalloc(segment offsets)");
   CK(dev_alloc(ctx, &ctx->multi_list, ntiles), "hipMalloc(multi-tile list)");
@@ -377,6 +391,7 @@ int emb_hash_rows(emb_ctx* ctx, const emb_batch* batch, uint32_t* rows_out, void
 int emb_backward_update(emb_ctx* ctx, const emb_batch* batch, const float* d_pooled, void* hip_stream) {
   int rc = check_batch(ctx, batch);
   if (rc) return rc;
+  if (!workspace_complete(ctx)) return fail(ctx, EMB_ESTATE, "workspace is incomplete (a buffer is null)");
   if (batch->batch_size && !d_pooled) return fail(ctx, EMB_EINVAL, "null d_pooled");
   hipStream_t stream = (hipStream_t)hip_stream;
   CKH(hipSetDevice(ctx->device), "hipSetDevice");
