@@ -4,6 +4,7 @@
 
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -47,6 +48,7 @@ struct emb_ctx {
   int mix = 0, opt = 0;
   float lr = 0, eps = 0;
   int key_bits = 1;
+  int sort_max_bits = 8;
   int uniform = 0;
   uint32_t pstride = 0;
   std::vector<TableView> tables;
@@ -242,6 +244,7 @@ int emb_create(const emb_config* cfg, emb_ctx** out) {
   ctx->key_bits = bit_length(total_rows - 1);
   if (ctx->key_bits < 1) ctx->key_bits = 1;
   ctx->uniform = cfg->num_tables == 1;
+  if (const char* v = std::getenv("PEMB_SORT_MAX_BITS")) ctx->sort_max_bits = std::atoi(v);  // tuning knob
   ctx->pstride = max_dim;
 
 #define CK(call, what)                                  \
@@ -328,8 +331,8 @@ int emb_create(const emb_config* cfg, emb_ctx** out) {
     CK(dev_alloc(ctx, &ctx->keys[i], cap), "hipMalloc(sort keys)");
     CK(dev_alloc(ctx, &ctx->bags[i], cap), "hipMalloc(sort payload)");
   }
-  CK(dev_alloc(ctx, &ctx->hist, (uint64_t)256 * kSortMaxBlocks), "hipMalloc(histograms)");
-  CK(dev_alloc(ctx, &ctx->total, 256), "hipMalloc(digit totals)");
+  CK(dev_alloc(ctx, &ctx->hist, ((uint64_t)1 << kSortMaxBits) * kSortMaxBlocks), "hipMalloc(histograms)");
+  CK(dev_alloc(ctx, &ctx->total, (uint64_t)1 << kSortMaxBits), "hipMalloc(digit totals)");
   CK(dev_alloc(ctx, &ctx->blk_heads, (cap + kUniqueTile - 1) / kUniqueTile + 1), "hipMalloc(block heads)");
   CK(dev_alloc(ctx, &ctx->blk_multi, (cap + kUniqueTile - 1) / kUniqueTile + 1), "hipMalloc(block multi-tile counts)");
   CK(dev_alloc(ctx, &ctx->unique_keys, cap), "hipMalloc(unique keys)");
@@ -411,7 +414,7 @@ int emb_backward_update(emb_ctx* ctx, const emb_batch* batch, const float* d_poo
                           ctx->keys[0], ctx->bags[0], stream),
         "build_keys");
   }
-  const SortPlan plan = make_sort_plan(n, ctx->key_bits);
+  const SortPlan plan = make_sort_plan(n, ctx->key_bits, ctx->sort_max_bits);
   int src = 0;
   for (int pass = 0; pass < plan.passes; ++pass) {
     const int shift = pass * plan.bits;

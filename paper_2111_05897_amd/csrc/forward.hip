@@ -2,8 +2,9 @@
 //
 // gather_pool: a group of LANES adjacent lanes owns one bag; each lane owns 16 bytes of the row
 // (4 fp32 or 8 bf16 elements), so a row read is one fully coalesced LANES*16-byte access and a
-// wave keeps 64/LANES bags in flight.  Rows of a bag are summed in batch order in fp32; four
-// row loads are issued before the first add so that each lane has several HBM requests in flight.
+// wave keeps 64/LANES bags in flight.  Per round the group fetches max(LANES, 8) ids with one
+// coalesced load, each lane hashes its own id(s), rows are broadcast inside the group, and eight
+// row loads are issued before the first add so that every lane keeps several HBM requests in flight.
 #include "device_utils.h"
 #include "launch.h"
 
@@ -24,37 +25,46 @@ struct GatherArgs {
   float* pooled;
 };
 
-template <typename T, int VEC>
-struct RowVec;
-template <>
-struct RowVec<float, 4> {
-  float v[4];
-  __device__ __forceinline__ void load(const float* p) {
-    float4 t = *reinterpret_cast<const float4*>(p);
-    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+// 16 bytes of a row as loaded, widened to fp32 only when it is added.
+template <typename T>
+struct Raw16 {
+  uint4 v;
+  static constexpr int VEC = 16 / (int)sizeof(T);
+  __device__ __forceinline__ void load(const T* p) { v = *reinterpret_cast<const uint4*>(p); }
+  __device__ __forceinline__ void zero() { v = make_uint4(0u, 0u, 0u, 0u); }
+  __device__ __forceinline__ void add_to(float (&s)[VEC]) const {
+    if constexpr (sizeof(T) == 4) {
+      s[0] += __uint_as_float(v.x); s[1] += __uint_as_float(v.y);
+      s[2] += __uint_as_float(v.z); s[3] += __uint_as_float(v.w);
+    } else {
+      s[0] += __uint_as_float(v.x << 16); s[1] += __uint_as_float(v.x & 0xFFFF0000u);
+      s[2] += __uint_as_float(v.y << 16); s[3] += __uint_as_float(v.y & 0xFFFF0000u);
+      s[4] += __uint_as_float(v.z << 16); s[5] += __uint_as_float(v.z & 0xFFFF0000u);
+      s[6] += __uint_as_float(v.w << 16); s[7] += __uint_as_float(v.w & 0xFFFF0000u);
+    }
   }
 };
-template <>
-struct RowVec<bf16_t, 8> {
-  float v[8];
-  __device__ __forceinline__ void load(const bf16_t* p) {
-    uint4 t = *reinterpret_cast<const uint4*>(p);
-    v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xFFFF0000u);
-    v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xFFFF0000u);
-    v[4] = __uint_as_float(t.z << 16); v[5] = __uint_as_float(t.z & 0xFFFF0000u);
-    v[6] = __uint_as_float(t.w << 16); v[7] = __uint_as_float(t.w & 0xFFFF0000u);
-  }
-};
+
+// Value of `v` held by lane `src` of this lane's group of LANES adjacent lanes.
+template <int LANES>
+__device__ __forceinline__ uint32_t group_bcast(uint32_t v, int src) {
+  if constexpr (LANES == 1) return v;
+  else return (uint32_t)__shfl((int)v, src, LANES);
+}
 
 template <typename T, int D>
 __global__ __launch_bounds__(kBlock) void k_gather_pool(GatherArgs a) {
   constexpr int VEC = 16 / (int)sizeof(T);
-  constexpr int LANES = D / VEC;
-  constexpr int GPB = kBlock / LANES;
+  constexpr int LANES = D / VEC;            // lanes that cover one row with 16 bytes each
+  constexpr int GPB = kBlock / LANES;       // bags per workgroup
+  constexpr int CH = LANES > 8 ? LANES : 8; // ids the group fetches and hashes per round, one or more per lane
+  constexpr int IPL = CH / LANES;           // ids per lane per round
+  constexpr int RIF = 8;                    // row loads in flight per lane
   static_assert(LANES >= 1 && LANES <= 64 && (LANES & (LANES - 1)) == 0, "row must map onto a power-of-two lane group");
+  static_assert(CH % RIF == 0 && CH % LANES == 0, "round geometry");
   const uint32_t lb = blockIdx.x * GPB + threadIdx.x / LANES;
   const int lane = threadIdx.x % LANES;
-  if (lb >= a.n_local_bags) return;
+  if (lb >= a.n_local_bags) return;         // whole groups leave together
   const uint32_t b = lb / a.n_slots_t;
   const uint32_t slot = a.slot_list[lb - b * a.n_slots_t];
   const size_t bag = (size_t)b * a.S + slot;
@@ -63,31 +73,41 @@ __global__ __launch_bounds__(kBlock) void k_gather_pool(GatherArgs a) {
   const T* __restrict__ base = reinterpret_cast<const T*>(a.w) + lane * VEC;
   const uint64_t* __restrict__ ids = a.ids;
 
-  // Compensated (Kahan) fp32 sum in batch order: the error stays at one or two roundings of the
-  // result however long the bag is; the extra adds are free next to the row loads.
+  // Rows are summed in batch order: plain fp32 inside a sub-chunk of RIF rows, and the sub-chunk
+  // sums are added with compensation (Kahan), so the error does not grow with the bag length.
   float acc[VEC], comp[VEC];
 #pragma unroll
   for (int e = 0; e < VEC; ++e) acc[e] = comp[e] = 0.f;
 
-  int i = beg;
-  for (; i + 4 <= end; i += 4) {
-    RowVec<T, VEC> r[4];
+  for (int cbase = beg; cbase < end; cbase += CH) {
+    const int cnt = end - cbase < CH ? end - cbase : CH;
+    // each id of the round is loaded and hashed by exactly one lane of the group
+    uint32_t myrow[IPL];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      uint32_t row = hash_row(ids[i + j], salt, a.rows, a.mask, a.mix);
-      r[j].load(base + (size_t)row * D);
+    for (int q = 0; q < IPL; ++q) {
+      const int idx = cbase + q * LANES + lane;
+      myrow[q] = idx < end ? hash_row(ids[idx], salt, a.rows, a.mask, a.mix) : 0u;
     }
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j0 = 0; j0 < CH; j0 += RIF) {
+      if (j0 < cnt) {  // same for all lanes of the group
+        Raw16<T> r[RIF];
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) kahan_add(acc[e], comp[e], r[j].v[e]);
-  }
-  for (; i < end; ++i) {
-    RowVec<T, VEC> r;
-    uint32_t row = hash_row(ids[i], salt, a.rows, a.mask, a.mix);
-    r.load(base + (size_t)row * D);
+        for (int jj = 0; jj < RIF; ++jj) {
+          const int j = j0 + jj;  // compile-time: id j of the round sits in lane j % LANES, register j / LANES
+          const uint32_t row = group_bcast<LANES>(myrow[j / LANES], j % LANES);
+          if (j < cnt) r[jj].load(base + (size_t)row * D);
+          else r[jj].zero();
+        }
+        float s[VEC];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) kahan_add(acc[e], comp[e], r.v[e]);
+        for (int e = 0; e < VEC; ++e) s[e] = 0.f;
+#pragma unroll
+        for (int jj = 0; jj < RIF; ++jj) r[jj].add_to(s);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) kahan_add(acc[e], comp[e], s[e]);
+      }
+    }
   }
 
   float* out = a.pooled + (size_t)b * a.width + a.slot_col[slot] + lane * VEC;

@@ -10,6 +10,7 @@ constexpr uint32_t kTile = 32;
 // Radix sort geometry: a block ranks and scatters tiles of 256 threads x 8 keys.
 constexpr uint32_t kSortTile = 2048;
 constexpr uint32_t kSortMaxBlocks = 1024;
+constexpr int kSortMaxBits = 9;                 // widest digit a pass may use (512 bins)
 constexpr uint32_t kUniqueTile = 2048;
 
 // What a kernel needs to know about one table.
@@ -55,8 +56,8 @@ struct SortPlan {
   uint32_t n, chunk, nblk;
   int passes, bits;
 };
-SortPlan make_sort_plan(uint32_t n, int key_bits);
-// One LSD pass: digit = (key >> shift) & (2^bits - 1).  hist: [2^bits * nblk], total: [256].
+SortPlan make_sort_plan(uint32_t n, int key_bits, int max_bits);
+// One LSD pass: digit = (key >> shift) & (2^bits - 1).  hist: [2^bits * nblk], total: [2^bits].
 hipError_t launch_radix_hist(const SortPlan& p, int shift, const uint32_t* keys, uint32_t* hist, hipStream_t stream);
 hipError_t launch_radix_scan(const SortPlan& p, uint32_t* hist, uint32_t* total, hipStream_t stream);
 hipError_t launch_radix_scatter(const SortPlan& p, int shift, const uint32_t* kin, const uint32_t* pin,

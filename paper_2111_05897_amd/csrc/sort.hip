@@ -6,7 +6,7 @@
 // tile each wave ranks its keys with ballot-based digit matching (stable: rank = number of
 // earlier pairs of the tile with the same digit), the tile is reordered digit-major through LDS,
 // and written out so that consecutive lanes store to consecutive addresses of a digit's region.
-// Only the significant key bits are sorted (ceil(key_bits / 8) passes).
+// Only the significant key bits are sorted, in passes of equal width of at most kSortMaxBits bits.
 #include "device_utils.h"
 #include "launch.h"
 
@@ -59,6 +59,8 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(const uint32_t* __rest
                                                           const uint32_t* __restrict__ hist,
                                                           const uint32_t* __restrict__ total) {
   constexpr int NB = 1 << BITS;
+  constexpr int DPT = NB > kBlock ? NB / kBlock : 1;  // digits owned by a thread: tid*DPT .. tid*DPT + DPT-1
+  static_assert(NB <= kBlock || NB % kBlock == 0, "digit ownership");
   __shared__ uint32_t s_key[kSortTile];
   __shared__ uint32_t s_pay[kSortTile];
   __shared__ uint32_t s_cnt[kWavesPerBlock][NB];
@@ -67,14 +69,24 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(const uint32_t* __rest
 
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
   const uint64_t lt_mask = (1ull << lane) - 1ull;
+  const bool owner = tid * DPT < NB;
 
-  // Where this block's first pair of digit `tid` goes: pairs of smaller digits anywhere, plus pairs
-  // of the same digit in earlier blocks.
-  uint32_t running = 0;
+  // Where this block's first pair of each owned digit goes: pairs of smaller digits anywhere, plus
+  // pairs of the same digit in earlier blocks.
+  uint32_t running[DPT];
   {
-    uint32_t v = tid < NB ? total[tid] : 0u;
-    uint32_t ex = block_exclusive_scan(v, s_w, nullptr);
-    if (tid < NB) running = ex + hist[(size_t)tid * nblk + blockIdx.x];
+    uint32_t v[DPT], sum = 0;
+#pragma unroll
+    for (int q = 0; q < DPT; ++q) {
+      v[q] = owner ? total[tid * DPT + q] : 0u;
+      sum += v[q];
+    }
+    uint32_t ex = block_exclusive_scan(sum, s_w, nullptr);
+#pragma unroll
+    for (int q = 0; q < DPT; ++q) {
+      running[q] = owner ? ex + hist[(size_t)(tid * DPT + q) * nblk + blockIdx.x] : 0u;
+      ex += v[q];
+    }
   }
 
   const uint32_t beg = blockIdx.x * chunk;
@@ -117,24 +129,31 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(const uint32_t* __rest
     __syncthreads();
 
     // Digit-major layout of the tile: digit start, then waves in order.
-    uint32_t c[kWavesPerBlock], tot = 0;
-    if (tid < NB) {
+    uint32_t c[DPT][kWavesPerBlock], tot[DPT], sum = 0;
+#pragma unroll
+    for (int q = 0; q < DPT; ++q) {
+      tot[q] = 0;
 #pragma unroll
       for (int w = 0; w < kWavesPerBlock; ++w) {
-        c[w] = s_cnt[w][tid];
-        tot += c[w];
+        c[q][w] = owner ? s_cnt[w][tid * DPT + q] : 0u;
+        tot[q] += c[q][w];
       }
+      sum += tot[q];
     }
-    const uint32_t ex = block_exclusive_scan(tid < NB ? tot : 0u, s_w, nullptr);
-    if (tid < NB) {
-      uint32_t run = ex;
+    uint32_t ex = block_exclusive_scan(sum, s_w, nullptr);
+    if (owner) {
 #pragma unroll
-      for (int w = 0; w < kWavesPerBlock; ++w) {
-        s_cnt[w][tid] = run;
-        run += c[w];
+      for (int q = 0; q < DPT; ++q) {
+        uint32_t run = ex;
+#pragma unroll
+        for (int w = 0; w < kWavesPerBlock; ++w) {
+          s_cnt[w][tid * DPT + q] = run;
+          run += c[q][w];
+        }
+        s_gofs[tid * DPT + q] = running[q] - ex;  // global index = s_gofs[digit] + position in the reordered tile
+        running[q] += tot[q];
+        ex += tot[q];
       }
-      s_gofs[tid] = running - ex;  // global index = s_gofs[digit] + position in the reordered tile
-      running += tot;
     }
     __syncthreads();
 
@@ -304,11 +323,13 @@ hipError_t pass_scatter(const SortPlan& p, int shift, const uint32_t* kin, const
 
 }  // namespace
 
-SortPlan make_sort_plan(uint32_t n, int key_bits) {
+SortPlan make_sort_plan(uint32_t n, int key_bits, int max_bits) {
   SortPlan p;
   p.n = n;
   if (key_bits < 1) key_bits = 1;
-  p.passes = (key_bits + 7) / 8;
+  if (max_bits < 4) max_bits = 4;
+  if (max_bits > kSortMaxBits) max_bits = kSortMaxBits;
+  p.passes = (key_bits + max_bits - 1) / max_bits;
   p.bits = (key_bits + p.passes - 1) / p.passes;
   uint32_t tiles = (n + kSortTile - 1) / kSortTile;
   if (tiles == 0) tiles = 1;
@@ -329,6 +350,7 @@ SortPlan make_sort_plan(uint32_t n, int key_bits) {
     case 6: return CALL(6);          \
     case 7: return CALL(7);          \
     case 8: return CALL(8);          \
+    case 9: return CALL(9);          \
     default: return hipErrorInvalidValue; \
   }
 
