@@ -8,8 +8,8 @@
 //   - a run that began before the tile is stored as a partial in slot first[tile];
 //   - otherwise a run that continues past the tile is stored in slot last[tile];
 //   - every other run is a complete segment and the optimizer is applied to its row at once.
-// Segments that span tiles are listed by the unique kernels and finished by the fix-up kernel, which adds
-// last[t0], first[t0+1], ..., first[t1] in a fixed order and then applies the optimizer.  No float
+// Segments that span tiles are listed by the unique kernels and finished by the fix-up kernels, which add
+// last[t0], first[t0+1], ..., first[t1] in a fixed order and then apply the optimizer.  No float
 // atomics: the summation order is a function of the batch alone, so results are reproducible.
 #include "device_utils.h"
 #include "launch.h"
@@ -29,14 +29,14 @@ __device__ __forceinline__ void kahan_add4(float4& s, float4& c, float4 x) {
 }
 
 // Row update by a group of LG lanes; lane owns elements [4*lane, 4*lane+4) and G holds its part of
-// the row's gradient.  OPT 0: SGD.  OPT 1: row-wise Adagrad (mean of G^2 over the row feeds one
-// accumulator; eps outside the square root).
+// the row's gradient; v = the lane's part of the row, a_old = the row's accumulator (both may have
+// been fetched long before).  OPT 0: SGD.  OPT 1: row-wise Adagrad (mean of G^2 over the row feeds
+// one accumulator; eps outside the square root).
 template <typename T, int D, int OPT>
-__device__ __forceinline__ void apply_update(T* __restrict__ w, float* __restrict__ accs, uint32_t row, float4 G,
-                                             int lane, float lr, float eps) {
+__device__ __forceinline__ void finish_update(T* __restrict__ w, float* __restrict__ accs, uint32_t row, float4 G,
+                                              float4 v, float a_old, int lane, float lr, float eps) {
   constexpr int LG = D / 4;
   T* p = w + (size_t)row * D + lane * 4;
-  float4 v = load_frag4(p);
   if constexpr (OPT == 0) {
     v.x = fmaf(-lr, G.x, v.x);
     v.y = fmaf(-lr, G.y, v.y);
@@ -46,7 +46,7 @@ __device__ __forceinline__ void apply_update(T* __restrict__ w, float* __restric
     float sq = G.x * G.x + G.y * G.y + G.z * G.z + G.w * G.w;
 #pragma unroll
     for (int m = LG / 2; m >= 1; m >>= 1) sq += __shfl_xor(sq, m);
-    const float a = accs[row] + sq * (1.0f / D);
+    const float a = a_old + sq * (1.0f / D);
     const float step = lr / (sqrtf(a) + eps);
     v.x = fmaf(-step, G.x, v.x);
     v.y = fmaf(-step, G.y, v.y);
@@ -55,6 +55,14 @@ __device__ __forceinline__ void apply_update(T* __restrict__ w, float* __restric
     if (lane == 0) accs[row] = a;
   }
   store_frag4(p, v);
+}
+
+template <typename T, int D, int OPT>
+__device__ __forceinline__ void apply_update(T* __restrict__ w, float* __restrict__ accs, uint32_t row, float4 G,
+                                             int lane, float lr, float eps) {
+  const float4 v = load_frag4(w + (size_t)row * D + lane * 4);
+  const float a_old = OPT == 0 ? 0.f : accs[row];
+  finish_update<T, D, OPT>(w, accs, row, G, v, a_old, lane, lr, eps);
 }
 
 struct TileArgs {
@@ -84,14 +92,30 @@ __device__ __forceinline__ const float* grad_ptr(const TileArgs& a, uint32_t bag
 
 template <typename T, int D, int OPT>
 __global__ __launch_bounds__(kBlock) void k_tile_reduce_update(TileArgs a) {
-  constexpr int LG = D / 4;
-  constexpr int GPB = kBlock / LG;
-  const uint32_t tile = blockIdx.x * GPB + threadIdx.x / LG;
-  const int lane = threadIdx.x % LG;
+  constexpr int LG = D / 4;          // lanes per tile
+  constexpr int GPB = kBlock / LG;   // tiles per workgroup
+  constexpr int SC = 4;              // entries fetched together: SC gradient rows + the table rows of the runs they start
+  static_assert(kTile % SC == 0, "sub-chunk geometry");
+  __shared__ uint32_t s_key[GPB][kTile];
+  __shared__ uint32_t s_bag[GPB][kTile];
+  const int grp = threadIdx.x / LG, lane = threadIdx.x % LG;
+  const uint32_t tile = blockIdx.x * GPB + grp;
   const uint64_t p0_64 = (uint64_t)tile * kTile;
-  if (p0_64 >= a.n) return;
-  const uint32_t p0 = (uint32_t)p0_64;
-  const uint32_t p1 = (a.n - p0 < kTile) ? a.n : p0 + kTile;
+  const bool in_list = p0_64 < a.n;
+  const uint32_t p0 = in_list ? (uint32_t)p0_64 : 0u;
+  const uint32_t p1 = in_list ? ((a.n - p0 < kTile) ? a.n : p0 + kTile) : 0u;
+  const uint32_t* __restrict__ keys = a.keys;
+  const uint32_t* __restrict__ bags = a.bags;
+
+  // stage the tile's (key, bag) pairs in LDS with coalesced loads
+  for (uint32_t e = lane; e < kTile; e += LG) {
+    const bool ok = p0 + e < p1;
+    s_key[grp][e] = ok ? keys[p0 + e] : 0u;
+    s_bag[grp][e] = ok ? bags[p0 + e] : 0u;
+  }
+  __syncthreads();
+  if (!in_list) return;
+
   uint32_t q0 = p0, q1 = p1;
   if (a.range) {  // several tables: only this table's stretch of the sorted list
     const uint32_t rb = a.range[0], re = a.range[1];
@@ -99,37 +123,56 @@ __global__ __launch_bounds__(kBlock) void k_tile_reduce_update(TileArgs a) {
     q1 = q1 < re ? q1 : re;
     if (q0 >= q1) return;
   }
-  const uint32_t* __restrict__ keys = a.keys;
-  const uint32_t* __restrict__ bags = a.bags;
   T* w = reinterpret_cast<T*>(a.w);
+  const uint32_t* sk = s_key[grp];
+  const uint32_t* sb = s_bag[grp];
 
-  const bool cont_in = (q0 == p0) && p0 > 0 && keys[p0 - 1] == keys[p0];
-  const bool cont_out = (q1 == p1) && p1 < a.n && keys[p1] == keys[p1 - 1];
+  const bool cont_in = (q0 == p0) && p0 > 0 && keys[p0 - 1] == sk[0];
+  const bool cont_out = (q1 == p1) && p1 < a.n && keys[p1] == sk[p1 - 1 - p0];
+  const uint32_t last_key = sk[q1 - 1 - p0];
 
-  uint32_t cur = keys[q0];
+  // the run being summed: its key, sum, and (fetched when the run started) its table row + accumulator
+  uint32_t cur = sk[q0 - p0];
+  uint32_t prev = cont_in ? cur : ~cur;   // key before entry q0: equal = the first run came in from the left
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  bool first = true;
+  float4 cur_row = acc;
+  float cur_a = 0.f;
+  bool first = true, have_run = cont_in;
 
-  for (uint32_t i = q0; i < q1; i += 4) {
-    uint32_t k[4];
-    float4 g[4];
+  for (uint32_t i = q0; i < q1; i += SC) {
+    uint32_t k[SC];
+    float4 g[SC], wr[SC];
+    float av[SC];
+    bool start[SC];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < SC; ++j) {
       const bool ok = i + j < q1;
-      k[j] = ok ? keys[i + j] : cur;
-      const uint32_t bag = ok ? bags[i + j] : 0u;
+      k[j] = ok ? sk[i + j - p0] : prev;
+      const uint32_t bag = ok ? sb[i + j - p0] : 0u;
+      start[j] = ok && k[j] != (j == 0 ? prev : k[j - 1]);
       g[j] = ok ? load_frag4(grad_ptr<D>(a, bag, lane)) : make_float4(0.f, 0.f, 0.f, 0.f);
+      // a run that starts here and ends inside the tile is updated by this group: fetch its row now
+      const bool need_row = start[j] && !(cont_out && k[j] == last_key);
+      const uint32_t row = k[j] - a.key_base;
+      wr[j] = need_row ? load_frag4(w + (size_t)row * D + lane * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+      av[j] = (need_row && OPT != 0) ? a.accs[row] : 0.f;
     }
+    prev = k[SC - 1];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < SC; ++j) {
       if (i + j < q1) {
-        if (k[j] != cur) {  // the run of `cur` ended inside the tile
-          if (first && cont_in)
-            store_frag4(a.partials + (size_t)(2 * tile) * a.pstride + lane * 4, acc);
-          else
-            apply_update<T, D, OPT>(w, a.accs, cur - a.key_base, acc, lane, a.lr, a.eps);
-          first = false;
+        if (start[j]) {
+          if (have_run) {  // the run of `cur` ended inside the tile
+            if (first && cont_in)
+              store_frag4(a.partials + (size_t)(2 * tile) * a.pstride + lane * 4, acc);
+            else
+              finish_update<T, D, OPT>(w, a.accs, cur - a.key_base, acc, cur_row, cur_a, lane, a.lr, a.eps);
+            first = false;
+          }
+          have_run = true;
           cur = k[j];
+          cur_row = wr[j];
+          cur_a = av[j];
           acc = make_float4(0.f, 0.f, 0.f, 0.f);
         }
         acc = add4(acc, g[j]);
@@ -141,7 +184,7 @@ __global__ __launch_bounds__(kBlock) void k_tile_reduce_update(TileArgs a) {
   else if (cont_out)
     store_frag4(a.partials + (size_t)(2 * tile + 1) * a.pstride + lane * 4, acc);
   else
-    apply_update<T, D, OPT>(w, a.accs, cur - a.key_base, acc, lane, a.lr, a.eps);
+    finish_update<T, D, OPT>(w, a.accs, cur - a.key_base, acc, cur_row, cur_a, lane, a.lr, a.eps);
 }
 
 struct FixupArgs {
@@ -158,24 +201,64 @@ struct FixupArgs {
   float lr, eps;
 };
 
-// Block per listed segment (grid-stride).  Group g adds partials g, g+NG, ... of the segment in
-// order; the NG group sums are then added in group order and the row is updated.
+// Segments that span at most kShortSpan tiles: one lane-group per listed segment (grid-stride), the
+// partials added in tile order.
+constexpr uint32_t kShortSpan = 16;
+
 template <typename T, int D, int OPT>
-__global__ __launch_bounds__(kBlock) void k_fixup(FixupArgs a) {
+__global__ __launch_bounds__(kBlock) void k_fixup_short(FixupArgs a) {
   constexpr int LG = D / 4;
-  constexpr int NG = kBlock / LG;
-  __shared__ float s_part[NG][D];
-  const int g = threadIdx.x / LG, lane = threadIdx.x % LG;
+  constexpr int GPB = kBlock / LG;
+  const int lane = threadIdx.x % LG;
   const uint32_t count = a.counters[1];
   T* w = reinterpret_cast<T*>(a.w);
-  for (uint32_t e = blockIdx.x; e < count; e += gridDim.x) {
+  for (uint32_t e = blockIdx.x * GPB + threadIdx.x / LG; e < count; e += gridDim.x * GPB) {
     const uint32_t u = a.multi_list[e];
     const uint32_t key = a.unique_keys[u];
     if (key < a.key_base || (uint64_t)(key - a.key_base) >= a.rows) continue;  // another table's row
     const uint32_t s = a.seg_off[u], end = a.seg_off[u + 1];
     const uint32_t t0 = s / kTile, t1 = (end - 1) / kTile;
     const uint32_t np = t1 - t0 + 1;
-    // compensated sums: a hot key's segment can span thousands of tiles
+    if (np > kShortSpan) continue;  // left to k_fixup_long
+    const uint32_t row = key - a.key_base;
+    const float4 v = load_frag4(w + (size_t)row * D + lane * 4);  // in flight together with the partials
+    const float a_old = OPT == 0 ? 0.f : a.accs[row];
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (uint32_t k0 = 0; k0 < np; k0 += 4) {
+      float4 pv[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t k = k0 + j;
+        const size_t slot = (k == 0) ? (size_t)2 * t0 + 1 : (size_t)2 * (t0 + k);
+        pv[j] = k < np ? load_frag4(a.partials + slot * a.pstride + lane * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (k0 + j < np) acc = add4(acc, pv[j]);
+    }
+    finish_update<T, D, OPT>(w, a.accs, row, acc, v, a_old, lane, a.lr, a.eps);
+  }
+}
+
+// Longer segments (hot keys): one workgroup per listed segment (grid-stride).  Group g adds partials
+// g, g+NG, ... of the segment in order (compensated); the NG group sums are then added in group order
+// and the row is updated.
+template <typename T, int D, int OPT>
+__global__ __launch_bounds__(kBlock) void k_fixup_long(FixupArgs a) {
+  constexpr int LG = D / 4;
+  constexpr int NG = kBlock / LG;
+  __shared__ float s_part[NG][D];
+  const int g = threadIdx.x / LG, lane = threadIdx.x % LG;
+  const uint32_t count = a.counters[1];
+  T* w = reinterpret_cast<T*>(a.w);
+  for (uint32_t e = blockIdx.x; e < count; e += gridDim.x) {  // every branch below is uniform over the workgroup
+    const uint32_t u = a.multi_list[e];
+    const uint32_t key = a.unique_keys[u];
+    if (key < a.key_base || (uint64_t)(key - a.key_base) >= a.rows) continue;  // another table's row
+    const uint32_t s = a.seg_off[u], end = a.seg_off[u + 1];
+    const uint32_t t0 = s / kTile, t1 = (end - 1) / kTile;
+    const uint32_t np = t1 - t0 + 1;
+    if (np <= kShortSpan) continue;  // done by k_fixup_short
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f), comp = acc;
     for (uint32_t k0 = g; k0 < np; k0 += 4 * NG) {  // four loads in flight per lane
       float4 v[4];
@@ -233,11 +316,19 @@ hipError_t launch_tile_td(const TileArgs& a, int opt, hipStream_t stream) {
 }
 
 template <typename T, int D>
-hipError_t launch_fixup_td(const FixupArgs& a, int opt, uint32_t grid, hipStream_t stream) {
-  if (opt == 0)
-    hipLaunchKernelGGL((k_fixup<T, D, 0>), dim3(grid), dim3(kBlock), 0, stream, a);
-  else
-    hipLaunchKernelGGL((k_fixup<T, D, 1>), dim3(grid), dim3(kBlock), 0, stream, a);
+hipError_t launch_fixup_td(const FixupArgs& a, int opt, uint32_t tiles, hipStream_t stream) {
+  constexpr int GPB = kBlock / (D / 4);
+  // multi-tile segments <= tiles; both kernels stride over the list, so the grids only need to fill the chip
+  const uint32_t want_s = (tiles + GPB - 1) / GPB;
+  const uint32_t grid_s = want_s < 4096u ? want_s : 4096u;
+  const uint32_t grid_l = tiles < 2048u ? tiles : 2048u;
+  if (opt == 0) {
+    hipLaunchKernelGGL((k_fixup_short<T, D, 0>), dim3(grid_s), dim3(kBlock), 0, stream, a);
+    hipLaunchKernelGGL((k_fixup_long<T, D, 0>), dim3(grid_l), dim3(kBlock), 0, stream, a);
+  } else {
+    hipLaunchKernelGGL((k_fixup_short<T, D, 1>), dim3(grid_s), dim3(kBlock), 0, stream, a);
+    hipLaunchKernelGGL((k_fixup_long<T, D, 1>), dim3(grid_l), dim3(kBlock), 0, stream, a);
+  }
   return hipGetLastError();
 }
 
@@ -303,11 +394,10 @@ hipError_t launch_fixup(const TableView& t, const BackwardArgs& b, hipStream_t s
   a.lr = b.lr;
   a.eps = b.eps;
   const uint32_t tiles = (b.n + kTile - 1) / kTile;
-  const uint32_t grid = tiles < 4096u ? tiles : 4096u;  // multi-tile segments <= tiles
   if (t.dtype == 1) {
-    PEMB_DIM_SWITCH(bf16_t, t.dim, launch_fixup_td, a, b.opt, grid, stream)
+    PEMB_DIM_SWITCH(bf16_t, t.dim, launch_fixup_td, a, b.opt, tiles, stream)
   } else {
-    PEMB_DIM_SWITCH(float, t.dim, launch_fixup_td, a, b.opt, grid, stream)
+    PEMB_DIM_SWITCH(float, t.dim, launch_fixup_td, a, b.opt, tiles, stream)
   }
 }
 
