@@ -76,6 +76,7 @@ struct TileArgs {
   float* partials;
   uint32_t pstride;
   const uint32_t* range;
+  const uint32_t* tile_perm;
   void* w;
   float* accs;
   uint32_t key_base;
@@ -99,7 +100,9 @@ __global__ __launch_bounds__(kBlock) void k_tile_reduce_update(TileArgs a) {
   __shared__ uint32_t s_key[GPB][kTile];
   __shared__ uint32_t s_bag[GPB][kTile];
   const int grp = threadIdx.x / LG, lane = threadIdx.x % LG;
-  const uint32_t tile = blockIdx.x * GPB + grp;
+  const uint32_t slot_idx = blockIdx.x * GPB + grp;  // position in the processing order
+  const uint32_t n_tiles = (a.n + kTile - 1) / kTile;
+  const uint32_t tile = slot_idx < n_tiles ? (a.tile_perm ? a.tile_perm[slot_idx] : slot_idx) : n_tiles;
   const uint64_t p0_64 = (uint64_t)tile * kTile;
   const bool in_list = p0_64 < a.n;
   const uint32_t p0 = in_list ? (uint32_t)p0_64 : 0u;
@@ -284,6 +287,16 @@ __global__ __launch_bounds__(kBlock) void k_fixup_long(FixupArgs a) {
   }
 }
 
+// tile_key[t] = (first bag of tile t) >> shift, tile_val[t] = t.
+__global__ __launch_bounds__(kBlock) void k_tile_keys(const uint32_t* __restrict__ bags, uint32_t n_tiles, int shift,
+                                                      uint32_t* __restrict__ tile_key,
+                                                      uint32_t* __restrict__ tile_val) {
+  const uint32_t t = blockIdx.x * kBlock + threadIdx.x;
+  if (t >= n_tiles) return;
+  tile_key[t] = bags[(size_t)t * kTile] >> shift;
+  tile_val[t] = t;
+}
+
 // Thread t <= num_tables: ranges[t] = first position whose key >= key_base[t] (ranges[num_tables] = n).
 __global__ void k_table_ranges(const uint32_t* __restrict__ keys, uint32_t n, const uint32_t* __restrict__ key_base,
                                uint32_t num_tables, uint32_t* __restrict__ ranges) {
@@ -352,6 +365,26 @@ hipError_t launch_table_ranges(const uint32_t* keys, uint32_t n, const uint32_t*
   return hipGetLastError();
 }
 
+hipError_t launch_tile_order(const uint32_t* bags, uint32_t n, int shift, uint32_t* const tile_key[2],
+                             uint32_t* const tile_val[2], uint32_t* hist, uint32_t* total,
+                             const uint32_t** perm_out, hipStream_t stream) {
+  const uint32_t n_tiles = (n + kTile - 1) / kTile;
+  *perm_out = nullptr;
+  if (n_tiles < 2) return hipSuccess;  // nothing to order
+  hipLaunchKernelGGL(k_tile_keys, dim3((n_tiles + kBlock - 1) / kBlock), dim3(kBlock), 0, stream, bags, n_tiles, shift,
+                     tile_key[0], tile_val[0]);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const SortPlan plan = make_sort_plan(n_tiles, 8, 8);  // keys are < 256 by the choice of shift: one pass
+  if ((e = launch_radix_hist(plan, 0, tile_key[0], hist, stream)) != hipSuccess) return e;
+  if ((e = launch_radix_scan(plan, hist, total, stream)) != hipSuccess) return e;
+  if ((e = launch_radix_scatter(plan, 0, tile_key[0], tile_val[0], tile_key[1], tile_val[1], hist, total, stream)) !=
+      hipSuccess)
+    return e;
+  *perm_out = tile_val[1];
+  return hipSuccess;
+}
+
 hipError_t launch_tile_reduce_update(const TableView& t, const BackwardArgs& b, hipStream_t stream) {
   if (b.n == 0) return hipSuccess;
   TileArgs a;
@@ -366,6 +399,7 @@ hipError_t launch_tile_reduce_update(const TableView& t, const BackwardArgs& b, 
   a.partials = b.partials;
   a.pstride = b.pstride;
   a.range = b.range;
+  a.tile_perm = b.tile_perm;
   a.w = t.w;
   a.accs = t.acc;
   a.key_base = t.key_base;

@@ -25,12 +25,13 @@ enum Stage {
   ST_SORT_SCAN,
   ST_SORT_SCATTER,
   ST_UNIQUE,
+  ST_TILE_ORDER,
   ST_REDUCE_UPDATE,
   ST_FIXUP,
   ST_COUNT
 };
 const char* const kStageNames[ST_COUNT] = {"gather_pool", "build_keys",    "sort_hist",  "sort_scan", "sort_scatter",
-                                           "unique",      "reduce_update", "fixup"};
+                                           "unique",      "tile_order",    "reduce_update", "fixup"};
 
 struct EventRec {
   int stage;
@@ -49,6 +50,7 @@ struct emb_ctx {
   float lr = 0, eps = 0;
   int key_bits = 1;
   int sort_max_bits = 8;
+  int tile_order = 1;
   int uniform = 0;
   uint32_t pstride = 0;
   std::vector<TableView> tables;
@@ -60,6 +62,7 @@ struct emb_ctx {
   uint32_t *hist = nullptr, *total = nullptr, *blk_heads = nullptr, *blk_multi = nullptr;
   uint32_t *unique_keys = nullptr, *seg_off = nullptr, *multi_list = nullptr, *counters = nullptr, *ranges = nullptr;
   float* partials = nullptr;
+  uint32_t *tile_key[2] = {nullptr, nullptr}, *tile_val[2] = {nullptr, nullptr};
   // last backward
   int sorted_buf = 0;
   uint64_t last_n = 0;
@@ -168,6 +171,7 @@ int check_batch(emb_ctx* ctx, const emb_batch* b) {
 bool workspace_complete(const emb_ctx* c) {
   const void* ptrs[] = {c->keys[0],  c->keys[1],     c->bags[0], c->bags[1],    c->hist,     c->total,
                         c->blk_heads, c->blk_multi,  c->unique_keys, c->seg_off, c->multi_list, c->counters,
+                        c->tile_key[0], c->tile_key[1], c->tile_val[0], c->tile_val[1],
                         c->ranges,    c->partials,   c->key_base_dev, c->slots.salt, c->slots.rows, c->slots.mask,
                         c->slots.key_base, c->slots.col};
   for (const void* p : ptrs)
@@ -244,7 +248,8 @@ int emb_create(const emb_config* cfg, emb_ctx** out) {
   ctx->key_bits = bit_length(total_rows - 1);
   if (ctx->key_bits < 1) ctx->key_bits = 1;
   ctx->uniform = cfg->num_tables == 1;
-  if (const char* v = std::getenv("PEMB_SORT_MAX_BITS")) ctx->sort_max_bits = std::atoi(v);  // tuning knob
+  if (const char* v = std::getenv("PEMB_SORT_MAX_BITS")) ctx->sort_max_bits = std::atoi(v);  // tuning knobs
+  if (const char* v = std::getenv("PEMB_TILE_ORDER")) ctx->tile_order = std::atoi(v);
   ctx->pstride = max_dim;
 
 #define CK(call, what)                                  \
@@ -341,6 +346,11 @@ int emb_create(const emb_config* cfg, emb_ctx** out) {
   CK(dev_alloc(ctx, &ctx->counters, 8), "hipMalloc(counters)");
   CK(dev_alloc(ctx, &ctx->ranges, cfg->num_tables + 1), "hipMalloc(table ranges)");
   CK(dev_alloc(ctx, &ctx->partials, 2 * ntiles * ctx->pstride), "hipMalloc(partials)");
+  for (int i = 0; i < 2; ++i) {
+    CK(dev_alloc(ctx, &ctx->tile_key[i], ntiles), "hipMalloc(tile order keys)");
+    CK(dev_alloc(ctx, &ctx->tile_val[i], ntiles), "hipMalloc(tile order)");
+  }
+
   CK(hipDeviceSynchronize(), "table initialisation");
 #undef CK
   *out = ctx;
@@ -453,6 +463,7 @@ int emb_backward_update(emb_ctx* ctx, const emb_batch* batch, const float* d_poo
   a.partials = ctx->partials;
   a.pstride = ctx->pstride;
   a.range = nullptr;
+  a.tile_perm = nullptr;
   a.opt = ctx->opt;
   a.lr = ctx->lr;
   a.eps = ctx->eps;
@@ -460,6 +471,15 @@ int emb_backward_update(emb_ctx* ctx, const emb_batch* batch, const float* d_poo
   a.seg_off = ctx->seg_off;
   a.counters = ctx->counters;
   a.multi_list = ctx->multi_list;
+  if (ctx->tile_order) {
+    StageTimer tm(ctx, ST_TILE_ORDER, stream);
+    // 256 buckets of consecutive bags (sample-major), whatever the batch size
+    int shift = bit_length((uint64_t)batch->batch_size * ctx->S - 1) - 8;
+    if (shift < 0) shift = 0;
+    CKH(launch_tile_order(a.bags, n, shift, ctx->tile_key, ctx->tile_val, ctx->hist, ctx->total, &a.tile_perm,
+                          stream),
+        "tile_order");
+  }
   const bool multi_table = ctx->tables.size() > 1;
   if (multi_table)
     CKH(launch_table_ranges(a.keys, n, ctx->key_base_dev, (uint32_t)ctx->tables.size(), ctx->ranges, stream),
