@@ -16,18 +16,45 @@ namespace {
 constexpr int kItems = 8;  // keys per thread per tile
 static_assert(kSortTile == kBlock * kItems, "tile geometry");
 
+constexpr int kHistThreads = 1024;  // the histogram is latency-bound: more waves per chunk than the scatter uses
+
 template <int BITS>
-__global__ __launch_bounds__(kBlock) void k_radix_hist(const uint32_t* __restrict__ keys, uint32_t n, uint32_t chunk,
-                                                       int shift, uint32_t nblk, uint32_t* __restrict__ hist) {
+__global__ __launch_bounds__(kHistThreads) void k_radix_hist(const uint32_t* __restrict__ keys, uint32_t n,
+                                                             uint32_t chunk, int shift, uint32_t nblk,
+                                                             uint32_t* __restrict__ hist) {
   constexpr int NB = 1 << BITS;
+  constexpr uint32_t TH = kHistThreads;
   __shared__ uint32_t h[NB];
-  for (int i = threadIdx.x; i < NB; i += kBlock) h[i] = 0;
+  for (int i = threadIdx.x; i < NB; i += TH) h[i] = 0;
   __syncthreads();
   const uint32_t beg = blockIdx.x * chunk;
   const uint32_t end = (n - beg < chunk) ? n : beg + chunk;  // beg < n by construction of the plan
-  for (uint32_t i = beg + threadIdx.x; i < end; i += kBlock) atomicAdd(&h[(keys[i] >> shift) & (NB - 1)], 1u);
+  // beg is a multiple of the tile size and the buffer is 256-byte aligned: 16-byte loads, two in flight
+  const uint32_t nvec = (end - beg) / 4;
+  const uint4* __restrict__ kv = reinterpret_cast<const uint4*>(keys + beg);
+  uint32_t v = threadIdx.x;
+  for (; v + TH < nvec; v += 2 * TH) {
+    const uint4 a = kv[v], b = kv[v + TH];
+    atomicAdd(&h[(a.x >> shift) & (NB - 1)], 1u);
+    atomicAdd(&h[(a.y >> shift) & (NB - 1)], 1u);
+    atomicAdd(&h[(a.z >> shift) & (NB - 1)], 1u);
+    atomicAdd(&h[(a.w >> shift) & (NB - 1)], 1u);
+    atomicAdd(&h[(b.x >> shift) & (NB - 1)], 1u);
+    atomicAdd(&h[(b.y >> shift) & (NB - 1)], 1u);
+    atomicAdd(&h[(b.z >> shift) & (NB - 1)], 1u);
+    atomicAdd(&h[(b.w >> shift) & (NB - 1)], 1u);
+  }
+  for (; v < nvec; v += TH) {
+    const uint4 a = kv[v];
+    atomicAdd(&h[(a.x >> shift) & (NB - 1)], 1u);
+    atomicAdd(&h[(a.y >> shift) & (NB - 1)], 1u);
+    atomicAdd(&h[(a.z >> shift) & (NB - 1)], 1u);
+    atomicAdd(&h[(a.w >> shift) & (NB - 1)], 1u);
+  }
+  for (uint32_t i = beg + nvec * 4 + threadIdx.x; i < end; i += TH)
+    atomicAdd(&h[(keys[i] >> shift) & (NB - 1)], 1u);
   __syncthreads();
-  for (int d = threadIdx.x; d < NB; d += kBlock) hist[(size_t)d * nblk + blockIdx.x] = h[d];
+  for (int d = threadIdx.x; d < NB; d += TH) hist[(size_t)d * nblk + blockIdx.x] = h[d];
 }
 
 // Block d: exclusive scan of hist[d*nblk .. (d+1)*nblk) in place, total[d] = sum.
@@ -309,8 +336,8 @@ __global__ __launch_bounds__(kBlock) void k_unique_write(const uint32_t* __restr
 
 template <int BITS>
 hipError_t pass_hist(const SortPlan& p, int shift, const uint32_t* keys, uint32_t* hist, hipStream_t stream) {
-  hipLaunchKernelGGL(k_radix_hist<BITS>, dim3(p.nblk), dim3(kBlock), 0, stream, keys, p.n, p.chunk, shift, p.nblk,
-                     hist);
+  hipLaunchKernelGGL(k_radix_hist<BITS>, dim3(p.nblk), dim3(kHistThreads), 0, stream, keys, p.n, p.chunk, shift,
+                     p.nblk, hist);
   return hipGetLastError();
 }
 template <int BITS>
