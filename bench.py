@@ -121,12 +121,14 @@ def main() -> int:
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                 "avg_launch_ms": round(dom_ms, 4), "algorithmic_bytes_per_launch": int(ab[dom])}
-    traffic_file = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json")
-    if os.path.exists(traffic_file):   # HBM bytes per launch measured with rocprofv3 --pmc (see profiles/)
-        try:
-            roofline["traffic"] = json.load(open(traffic_file)).get(dom)
-        except Exception:
-            pass
+    # bytes per launch between L2 and the fabric, from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    # WRITE_SIZE runs of this same script, scaled by a plain copy kernel); null if no summary covers the workload
+    traffic_file = os.path.join(ROOT, "profiles", f"{w.name}_hbm_traffic.txt")
+    if os.path.exists(traffic_file):
+        for line in open(traffic_file):
+            f = line.split()
+            if len(f) == 3 and f[0] == "traffic" and f[1] == dom:
+                roofline["traffic"] = int(f[2])
 
     out = {
         "metric": "embedding IDs/sec (lookup+bwd+update), 1 GPU", "value": round(ids_per_s, 1), "unit": "IDs/s",

@@ -282,27 +282,36 @@ __global__ __launch_bounds__(kBlock) void k_unique_count(const uint32_t* __restr
 }
 
 // Single block: exclusive scans of blk_heads[nb] and blk_multi[nb] in place; counters[0] = U,
-// counters[1] = number of multi-tile runs; seg_off[U] = n.
+// counters[1] = number of multi-tile runs; seg_off[U] = n.  Thread t owns the entries
+// [t*per, (t+1)*per): serial sum, one block scan, serial write-back.
 __global__ __launch_bounds__(kBlock) void k_unique_scan(uint32_t* __restrict__ blk_heads,
                                                         uint32_t* __restrict__ blk_multi, uint32_t nb, uint32_t n,
                                                         uint32_t* __restrict__ counters,
                                                         uint32_t* __restrict__ seg_off) {
   __shared__ uint32_t s_w[kWavesPerBlock];
-  uint32_t carry = 0, carry_m = 0;
-  for (uint32_t base = 0; base < nb; base += kBlock) {
-    const uint32_t i = base + threadIdx.x;
-    uint32_t tot;
-    const uint32_t ex = block_exclusive_scan(i < nb ? blk_heads[i] : 0u, s_w, &tot);
-    if (i < nb) blk_heads[i] = carry + ex;
-    carry += tot;
-    const uint32_t exm = block_exclusive_scan(i < nb ? blk_multi[i] : 0u, s_w, &tot);
-    if (i < nb) blk_multi[i] = carry_m + exm;
-    carry_m += tot;
-  }
+  const uint32_t per = (nb + kBlock - 1) / kBlock;
+  const uint32_t b0 = threadIdx.x * per;
+  uint32_t sum_h = 0, sum_m = 0;
+  for (uint32_t j = 0; j < per; ++j)
+    if (b0 + j < nb) {
+      sum_h += blk_heads[b0 + j];
+      sum_m += blk_multi[b0 + j];
+    }
+  uint32_t tot_h, tot_m;
+  uint32_t run_h = block_exclusive_scan(sum_h, s_w, &tot_h);
+  uint32_t run_m = block_exclusive_scan(sum_m, s_w, &tot_m);
+  for (uint32_t j = 0; j < per; ++j)
+    if (b0 + j < nb) {
+      const uint32_t vh = blk_heads[b0 + j], vm = blk_multi[b0 + j];
+      blk_heads[b0 + j] = run_h;
+      blk_multi[b0 + j] = run_m;
+      run_h += vh;
+      run_m += vm;
+    }
   if (threadIdx.x == 0) {
-    counters[0] = carry;
-    counters[1] = carry_m;
-    seg_off[carry] = n;
+    counters[0] = tot_h;
+    counters[1] = tot_m;
+    seg_off[tot_h] = n;
   }
 }
 
