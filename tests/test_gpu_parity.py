@@ -150,3 +150,84 @@ def test_configs_scaled(B, index, scale, steps):
 
 def test_config1_full_size(B):
     util.run_steps(B, W, O, W.make_workload(1), steps=1, dense=False)
+
+
+def test_config2_full_size_whole_oracle(B):
+    # the headline configuration, in the launch configuration bench.py times, against the full (sparse) oracle
+    util.run_steps(B, W, O, W.make_workload(2), steps=1, dense=False)
+
+
+@pytest.mark.parametrize("index", [3, 4])
+def test_configs_3_and_4_full_size_sampled(B, index):
+    util.sampled_step_check(B, W, O, W.make_workload(index))
+
+
+def test_sampled_check_agrees_with_whole_oracle_on_a_small_case(B):
+    # the sampling harness itself, on a size where the whole-oracle comparison also runs
+    w = W.make_workload(3, scale=1 / 256)
+    util.sampled_step_check(B, W, O, w, n_bags=500, n_rows=300)
+    util.run_steps(B, W, O, w, steps=1)
+
+
+# ----------------------------------------------------------------------------- bounded staleness (two streams)
+def test_staleness1_overlap_envelope(B):
+    """lookup(t+1) runs on a second stream while update(t) runs on the first (section 5: the embedding
+    read may be one update stale).  The table trajectory must equal the synchronous one (the upstream
+    gradients here do not depend on the lookups); an overlapped lookup may see any mix of rows before and
+    after update(t), so every pooled element must lie within sum_j |W_after[r_j] - W_before[r_j]| of the
+    pooled value on the table before update(t)."""
+    import torch
+    base = W.make_workload(4, scale=1 / 64)
+    cfg = W.EmbConfig(tables=[W.TableDesc(base.cfg.tables[0].rows, 64, W.F32)], slots=base.cfg.slots, init_seed=77)
+    w = W.Workload("overlap", 4, cfg, base.batch, base.len_kind, base.len_a, base.len_b, base.id_kind, base.id_space,
+                   base.zipf_s, 4, base.seed)
+    steps = 4
+    batches = [W.make_batch(w, s) for s in range(steps)]
+    grads = [W.make_d_pooled(w, s) for s in range(steps)]
+    ctx = B.EmbContext.from_config(cfg, max_batch=w.batch, max_ids=max(b.num_ids for b in batches))
+    dbs = [B.DeviceBatch(b.batch_size, b.ids, b.offsets) for b in batches]
+    dgr = [torch.from_numpy(g).cuda() for g in grads]
+    pooled = [torch.empty((w.batch, cfg.pooled_width), dtype=torch.float32, device="cuda") for _ in range(steps)]
+    s_upd, s_look = torch.cuda.Stream(), torch.cuda.Stream()          # default priority, both
+    ev_f = [torch.cuda.Event() for _ in range(steps)]
+    ev_b = [torch.cuda.Event() for _ in range(steps)]
+    torch.cuda.synchronize()
+    ctx.emb_lookup_pool(dbs[0], pooled[0], stream=s_look)
+    ev_f[0].record(s_look)
+    for t in range(steps):
+        if t + 1 < steps:
+            if t >= 1:
+                s_look.wait_event(ev_b[t - 1])       # staleness bound: lookup(t+1) sees updates 0..t-1 at least
+            ctx.emb_lookup_pool(dbs[t + 1], pooled[t + 1], stream=s_look)
+            ev_f[t + 1].record(s_look)
+        s_upd.wait_event(ev_f[t])                    # the dense side needs lookup(t) before it can return gradients
+        ctx.emb_backward_update(dbs[t], dgr[t], stream=s_upd)
+        ev_b[t].record(s_upd)
+    torch.cuda.synchronize()
+    got = [p.cpu().numpy() for p in pooled]
+
+    orc = O.Oracle.from_config(cfg, dense=False)
+    zero_cfg = W.EmbConfig(tables=cfg.tables, slots=cfg.slots, init_seed=1, init_lo=0.0, init_hi=0.0)
+    np.testing.assert_allclose(got[0], orc.lookup_pool(batches[0].ids, batches[0].offsets), rtol=1e-5, atol=1e-6)
+    touched = []
+    for t in range(steps):
+        b = batches[t]
+        keys, _, _ = orc.dedup(b.ids, b.offsets)
+        rows = keys & util.LOW32
+        w_before, _ = orc.read_rows(0, rows)
+        if t + 1 < steps:
+            nb = batches[t + 1]
+            pooled_before = orc.lookup_pool(nb.ids, nb.offsets)
+        orc.backward_update(b.ids, b.offsets, grads[t])
+        w_after, _ = orc.read_rows(0, rows)
+        touched.append(keys)
+        if t + 1 < steps:
+            delta = O.Oracle.from_config(zero_cfg, dense=False)     # table of |W_after - W_before|, zero elsewhere
+            delta.write_rows(0, rows, np.abs(w_after.astype(np.float64) - w_before).astype(np.float32))
+            envelope = delta.lookup_pool(nb.ids, nb.offsets).astype(np.float64)
+            delta.close()
+            err = np.abs(got[t + 1].astype(np.float64) - pooled_before)
+            slack = 1e-5 * np.abs(pooled_before) + 1e-6 + 1e-6 * envelope
+            assert (err <= envelope + slack).all(), f"step {t + 1}: pooled outside the staleness envelope"
+    util.compare_rows(ctx, orc, cfg, np.unique(np.concatenate(touched)))
+    ctx.close()
