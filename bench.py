@@ -22,15 +22,21 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 
 
-def algorithmic_bytes(N, bags, U, U_multi, D, e):
-    """Bytes the method itself must move per launch of each kernel stage and per whole step
-    (sort passes and partial sums are implementation overhead and not counted)."""
-    fwd = 8 * N + 4 * (bags + 1) + N * D * e + bags * D * 4        # ids, offsets, row gathers, pooled write
-    keys = 8 * N + 4 * (bags + 1) + 8 * N                            # ids re-read, (key, bag) pairs written
-    red = 8 * N + N * D * 4 + (U - U_multi) * (2 * D * e + 8)        # sorted pairs, grad gathers, row + acc RMW
-    fix = U_multi * (2 * D * e + 8)                                  # rows of segments that span tiles
-    step = fwd + 4 * N + 8 * N + 8 * U + N * D * 4 + U * (2 * D * e + 8)
-    return {"gather_pool": fwd, "build_keys": keys, "reduce_update": red, "fixup": fix, "step": step}
+def algorithmic_bytes(tables):
+    """Bytes the method itself must move per step in each kernel stage and in the whole step (sort passes
+    and partial sums are implementation overhead and not counted).  `tables`: one dict per table with
+    N (ids hashed into it), bags (bags reading it), U (unique rows), Um (unique rows whose segment spans
+    tiles), D (dim), e (bytes per stored element).  Kernels that run once per table sum over tables."""
+    out = {"gather_pool": 0.0, "build_keys": 0.0, "reduce_update": 0.0, "fixup": 0.0, "step": 0.0}
+    for t in tables:
+        N, bags, U, Um, D, e = t["N"], t["bags"], t["U"], t["Um"], t["D"], t["e"]
+        fwd = 8 * N + 4 * (bags + 1) + N * D * e + bags * D * 4      # ids, offsets, row gathers, pooled write
+        out["gather_pool"] += fwd
+        out["build_keys"] += 8 * N + 4 * (bags + 1) + 8 * N          # ids re-read, (key, bag) pairs written
+        out["reduce_update"] += 8 * N + N * D * 4 + (U - Um) * (2 * D * e + 8)   # sorted pairs, grad gathers, row+acc RMW
+        out["fixup"] += Um * (2 * D * e + 8)                         # rows of segments that span tiles
+        out["step"] += fwd + 4 * N + 8 * N + 8 * U + N * D * 4 + U * (2 * D * e + 8)
+    return out
 
 
 def main() -> int:
@@ -59,8 +65,9 @@ def main() -> int:
     binding.load_library()
     w = W.make_workload(args.config)
     cfg = w.cfg
-    assert len(cfg.tables) == 1, "bench covers the single-table configurations"
-    D, e = cfg.tables[0].dim, (2 if cfg.tables[0].dtype == W.BF16 else 4)
+    T = len(cfg.tables)
+    e_of = [2 if t.dtype == W.BF16 else 4 for t in cfg.tables]
+    slot_table = np.array([s.table for s in cfg.slots])
     nb = max(1, min(args.distinct_batches, args.steps))
     t0 = time.time()
     host_batches = [W.make_batch(w, s) for s in range(nb)]
@@ -136,25 +143,31 @@ def main() -> int:
     # per-kernel timing pass (HIP events on the launch stream, inside the library)
     ctx.emb_set_profiling(True)
     ctx.emb_reset_stage_ms()
-    N_sum = U_sum = Um_sum = 0
+    N_t, U_t, Um_t = np.zeros(T), np.zeros(T), np.zeros(T)
+    N_sum = 0
     for i in range(args.steps):
         N_sum += step(args.warmup + i)
         keys, seg_off, _ = ctx.emb_read_dedup()
-        U_sum += len(keys)
         s, en = seg_off[:-1].astype(np.int64), seg_off[1:].astype(np.int64)
-        Um_sum += int(np.count_nonzero(s // 32 != (en - 1) // 32))
+        kt = (keys >> np.uint64(32)).astype(np.int64)
+        U_t += np.bincount(kt, minlength=T)
+        Um_t += np.bincount(kt[s // 32 != (en - 1) // 32], minlength=T)
+        N_t += np.bincount(kt, weights=(en - s), minlength=T)
     stages = ctx.emb_read_stage_ms()
     ctx.emb_set_profiling(False)
-    N_avg, U_avg, Um_avg = N_sum / args.steps, U_sum / args.steps, Um_sum / args.steps
-    ab = algorithmic_bytes(N_avg, w.bags, U_avg, Um_avg, D, e)
-    stage_ms = {k: (ms / max(c, 1), c // args.steps) for k, (ms, c) in stages.items() if c}
+    N_avg, U_avg = N_sum / args.steps, float(U_t.sum()) / args.steps
+    ab = algorithmic_bytes([{"N": N_t[t] / args.steps, "bags": w.batch * int((slot_table == t).sum()),
+                             "U": U_t[t] / args.steps, "Um": Um_t[t] / args.steps, "D": cfg.tables[t].dim,
+                             "e": e_of[t]} for t in range(T)])
     per_step_ms = {k: ms / args.steps for k, (ms, c) in stages.items() if c}
+    launches = {k: c / args.steps for k, (ms, c) in stages.items() if c}
     dom = max((k for k in per_step_ms if k in ab), key=lambda k: per_step_ms[k])
-    dom_ms = stage_ms[dom][0]
-    achieved = ab[dom] / (dom_ms * 1e-3) / 1e9
+    # launches of a stage that run once per table are taken together: bytes of all / time of all
+    achieved = ab[dom] / (per_step_ms[dom] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                "avg_launch_ms": round(dom_ms, 4), "algorithmic_bytes_per_launch": int(ab[dom])}
+                "avg_launch_ms": round(per_step_ms[dom] / launches[dom], 4),
+                "algorithmic_bytes_per_launch": int(ab[dom] / launches[dom])}
     # bytes per launch between L2 and the fabric, from the committed rocprofv3 --pmc summary (FETCH_SIZE and
     # WRITE_SIZE runs of this same script, scaled by a plain copy kernel); null if no summary covers the workload
     traffic_file = os.path.join(ROOT, "profiles", f"{w.name}_hbm_traffic.txt")
@@ -167,16 +180,18 @@ def main() -> int:
     out = {
         "metric": "embedding IDs/sec (lookup+bwd+update), 1 GPU", "value": round(ids_per_s, 1), "unit": "IDs/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32" if e == 4 else "bf16",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if all(x == 4 for x in e_of) else "bf16",
         "data": "synthetic",
-        "config": {"workload": w.name, "batch": w.batch, "slots": cfg.num_slots, "rows": cfg.tables[0].rows, "dim": D,
+        "config": {"workload": w.name, "batch": w.batch, "slots": cfg.num_slots,
+                   "rows": [t.rows for t in cfg.tables], "dim": [t.dim for t in cfg.tables],
                    "ids_per_step": round(N_avg), "unique_rows_per_step": round(U_avg),
                    "distinct_batches": nb, "optimizer": "rowwise_adagrad" if cfg.opt else "sgd",
                    "schedule": "staleness-1 overlap, two streams" if args.overlap else "synchronous, one stream"},
         "effective_GBps_step": round(ab["step"] / (ms_per_step * 1e-3) / 1e9, 1),
         "effective_frac_of_hbm_peak": round(ab["step"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "stage_ms_per_step": {k: round(v, 4) for k, v in per_step_ms.items()},
-        "stage_GBps": {k: round(ab[k] / (stage_ms[k][0] * 1e-3) / 1e9, 1) for k in stage_ms if k in ab},
+        "stage_GBps": {k: round(ab[k] / (per_step_ms[k] * 1e-3) / 1e9, 1) for k in per_step_ms if k in ab},
         "setup_s": round(setup_s, 1),
         "roofline": roofline,
     }

@@ -104,9 +104,16 @@ __global__ __launch_bounds__(kBlock) void k_tile_reduce_update(TileArgs a) {
   const uint32_t n_tiles = (a.n + kTile - 1) / kTile;
   const uint32_t tile = slot_idx < n_tiles ? (a.tile_perm ? a.tile_perm[slot_idx] : slot_idx) : n_tiles;
   const uint64_t p0_64 = (uint64_t)tile * kTile;
-  const bool in_list = p0_64 < a.n;
-  const uint32_t p0 = in_list ? (uint32_t)p0_64 : 0u;
-  const uint32_t p1 = in_list ? ((a.n - p0 < kTile) ? a.n : p0 + kTile) : 0u;
+  bool in_list = p0_64 < a.n;
+  uint32_t p0 = in_list ? (uint32_t)p0_64 : 0u;
+  uint32_t p1 = in_list ? ((a.n - p0 < kTile) ? a.n : p0 + kTile) : 0u;
+  uint32_t q0 = p0, q1 = p1;
+  if (a.range) {  // several tables: only this table's stretch of the sorted list
+    const uint32_t rb = a.range[0], re = a.range[1];
+    q0 = q0 > rb ? q0 : rb;
+    q1 = q1 < re ? q1 : re;
+    if (q0 >= q1) in_list = false, p0 = p1 = 0u;  // nothing of this table in the tile: stage nothing
+  }
   const uint32_t* __restrict__ keys = a.keys;
   const uint32_t* __restrict__ bags = a.bags;
 
@@ -118,14 +125,6 @@ __global__ __launch_bounds__(kBlock) void k_tile_reduce_update(TileArgs a) {
   }
   __syncthreads();
   if (!in_list) return;
-
-  uint32_t q0 = p0, q1 = p1;
-  if (a.range) {  // several tables: only this table's stretch of the sorted list
-    const uint32_t rb = a.range[0], re = a.range[1];
-    q0 = q0 > rb ? q0 : rb;
-    q1 = q1 < re ? q1 : re;
-    if (q0 >= q1) return;
-  }
   T* w = reinterpret_cast<T*>(a.w);
   const uint32_t* sk = s_key[grp];
   const uint32_t* sb = s_bag[grp];
@@ -287,13 +286,21 @@ __global__ __launch_bounds__(kBlock) void k_fixup_long(FixupArgs a) {
   }
 }
 
-// tile_key[t] = (first bag of tile t) >> shift, tile_val[t] = t.
-__global__ __launch_bounds__(kBlock) void k_tile_keys(const uint32_t* __restrict__ bags, uint32_t n_tiles, int shift,
+// tile_key[t] = (table of the tile's first key) << 8 | (first bag of tile t) >> shift, tile_val[t] = t.
+__global__ __launch_bounds__(kBlock) void k_tile_keys(const uint32_t* __restrict__ keys,
+                                                      const uint32_t* __restrict__ bags, uint32_t n_tiles, int shift,
+                                                      const uint32_t* __restrict__ key_base, uint32_t num_tables,
                                                       uint32_t* __restrict__ tile_key,
                                                       uint32_t* __restrict__ tile_val) {
   const uint32_t t = blockIdx.x * kBlock + threadIdx.x;
   if (t >= n_tiles) return;
-  tile_key[t] = bags[(size_t)t * kTile] >> shift;
+  uint32_t table = 0;
+  if (num_tables > 1) {
+    const uint32_t k = keys[(size_t)t * kTile];
+    while (table + 1 < num_tables && k >= key_base[table + 1]) ++table;
+  }
+  const uint32_t bucket = bags[(size_t)t * kTile] >> shift;
+  tile_key[t] = (table << 8) | (bucket < 255u ? bucket : 255u);
   tile_val[t] = t;
 }
 
@@ -365,23 +372,31 @@ hipError_t launch_table_ranges(const uint32_t* keys, uint32_t n, const uint32_t*
   return hipGetLastError();
 }
 
-hipError_t launch_tile_order(const uint32_t* bags, uint32_t n, int shift, uint32_t* const tile_key[2],
+hipError_t launch_tile_order(const uint32_t* keys, const uint32_t* bags, uint32_t n, int shift,
+                             const uint32_t* key_base_dev, uint32_t num_tables, uint32_t* const tile_key[2],
                              uint32_t* const tile_val[2], uint32_t* hist, uint32_t* total,
                              const uint32_t** perm_out, hipStream_t stream) {
   const uint32_t n_tiles = (n + kTile - 1) / kTile;
   *perm_out = nullptr;
   if (n_tiles < 2) return hipSuccess;  // nothing to order
-  hipLaunchKernelGGL(k_tile_keys, dim3((n_tiles + kBlock - 1) / kBlock), dim3(kBlock), 0, stream, bags, n_tiles, shift,
-                     tile_key[0], tile_val[0]);
+  hipLaunchKernelGGL(k_tile_keys, dim3((n_tiles + kBlock - 1) / kBlock), dim3(kBlock), 0, stream, keys, bags, n_tiles,
+                     shift, key_base_dev, num_tables, tile_key[0], tile_val[0]);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const SortPlan plan = make_sort_plan(n_tiles, 8, 8);  // keys are < 256 by the choice of shift: one pass
-  if ((e = launch_radix_hist(plan, 0, tile_key[0], hist, stream)) != hipSuccess) return e;
-  if ((e = launch_radix_scan(plan, hist, total, stream)) != hipSuccess) return e;
-  if ((e = launch_radix_scatter(plan, 0, tile_key[0], tile_val[0], tile_key[1], tile_val[1], hist, total, stream)) !=
-      hipSuccess)
-    return e;
-  *perm_out = tile_val[1];
+  int table_bits = 0;
+  while ((1u << table_bits) < num_tables) ++table_bits;
+  const SortPlan plan = make_sort_plan(n_tiles, 8 + table_bits, 8);  // one pass for a single table
+  int src = 0;
+  for (int pass = 0; pass < plan.passes; ++pass) {
+    const int sh = pass * plan.bits;
+    if ((e = launch_radix_hist(plan, sh, tile_key[src], hist, stream)) != hipSuccess) return e;
+    if ((e = launch_radix_scan(plan, hist, total, stream)) != hipSuccess) return e;
+    if ((e = launch_radix_scatter(plan, sh, tile_key[src], tile_val[src], tile_key[src ^ 1], tile_val[src ^ 1], hist,
+                                  total, stream)) != hipSuccess)
+      return e;
+    src ^= 1;
+  }
+  *perm_out = tile_val[src];
   return hipSuccess;
 }
 

@@ -476,8 +476,8 @@ int emb_backward_update(emb_ctx* ctx, const emb_batch* batch, const float* d_poo
     // 256 buckets of consecutive bags (sample-major), whatever the batch size
     int shift = bit_length((uint64_t)batch->batch_size * ctx->S - 1) - 8;
     if (shift < 0) shift = 0;
-    CKH(launch_tile_order(a.bags, n, shift, ctx->tile_key, ctx->tile_val, ctx->hist, ctx->total, &a.tile_perm,
-                          stream),
+    CKH(launch_tile_order(a.keys, a.bags, n, shift, ctx->key_base_dev, (uint32_t)ctx->tables.size(), ctx->tile_key,
+                          ctx->tile_val, ctx->hist, ctx->total, &a.tile_perm, stream),
         "tile_order");
   }
   const bool multi_table = ctx->tables.size() > 1;

@@ -93,11 +93,13 @@ struct BackwardArgs {
 };
 hipError_t launch_table_ranges(const uint32_t* keys, uint32_t n, const uint32_t* key_base_dev, uint32_t num_tables,
                                uint32_t* ranges /*[num_tables+1]*/, hipStream_t stream);
-// Processing order of the tiles: ascending by (first bag of the tile >> shift), ties in tile order.
-// Tiles that read the same stretch of d_pooled then run close together in time, so a gradient row
+// Processing order of the tiles: ascending by (table of the tile's first key, first bag of the tile >> shift),
+// ties in tile order.  Each table's tiles are then contiguous in the order, and within a table
+// tiles that read the same stretch of d_pooled run close together in time, so a gradient row
 // that several hot keys need is fetched from HBM once and found in the memory-side cache afterwards.
 // tile_key / tile_val: two buffers of ntiles entries each; returns the sorted permutation in *perm_out.
-hipError_t launch_tile_order(const uint32_t* bags, uint32_t n, int shift, uint32_t* const tile_key[2],
+hipError_t launch_tile_order(const uint32_t* keys, const uint32_t* bags, uint32_t n, int shift,
+                             const uint32_t* key_base_dev, uint32_t num_tables, uint32_t* const tile_key[2],
                              uint32_t* const tile_val[2], uint32_t* hist, uint32_t* total,
                              const uint32_t** perm_out, hipStream_t stream);
 hipError_t launch_tile_reduce_update(const TableView& t, const BackwardArgs& a, hipStream_t stream);
