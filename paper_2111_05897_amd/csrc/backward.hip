@@ -192,8 +192,9 @@ __global__ __launch_bounds__(kBlock) void k_tile_reduce_update(TileArgs a) {
 struct FixupArgs {
   const uint32_t* unique_keys;
   const uint32_t* seg_off;
-  const uint32_t* counters;
+  const uint32_t* counters;   // [1] = entries of multi_list, [2] = entries of long_list
   const uint32_t* multi_list;
+  const uint32_t* long_list;
   const float* partials;
   uint32_t pstride;
   void* w;
@@ -242,7 +243,31 @@ __global__ __launch_bounds__(kBlock) void k_fixup_short(FixupArgs a) {
   }
 }
 
-// Longer segments (hot keys): one workgroup per listed segment (grid-stride).  Group g adds partials
+// Thread per multi-tile segment: those spanning more than kShortSpan tiles go to long_list (one
+// atomic per wave; the list's order varies from run to run, what is computed per entry does not).
+__global__ __launch_bounds__(kBlock) void k_classify_multi(const uint32_t* __restrict__ seg_off,
+                                                           const uint32_t* __restrict__ multi_list,
+                                                           uint32_t* __restrict__ counters,
+                                                           uint32_t* __restrict__ long_list) {
+  const uint32_t e = blockIdx.x * kBlock + threadIdx.x;
+  bool is_long = false;
+  uint32_t u = 0;
+  if (e < counters[1]) {
+    u = multi_list[e];
+    const uint32_t s = seg_off[u], end = seg_off[u + 1];
+    is_long = (end - 1) / kTile - s / kTile + 1 > kShortSpan;
+  }
+  const uint64_t m = __ballot(is_long);
+  if (m == 0) return;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int leader = __ffsll((unsigned long long)m) - 1;
+  uint32_t base = 0;
+  if (lane == leader) base = atomicAdd(&counters[2], (uint32_t)__popcll(m));
+  base = __shfl(base, leader);
+  if (is_long) long_list[base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull))] = u;
+}
+
+// Longer segments (hot keys): one workgroup per entry of long_list (grid-stride).  Group g adds partials
 // g, g+NG, ... of the segment in order (compensated); the NG group sums are then added in group order
 // and the row is updated.
 template <typename T, int D, int OPT>
@@ -251,16 +276,15 @@ __global__ __launch_bounds__(kBlock) void k_fixup_long(FixupArgs a) {
   constexpr int NG = kBlock / LG;
   __shared__ float s_part[NG][D];
   const int g = threadIdx.x / LG, lane = threadIdx.x % LG;
-  const uint32_t count = a.counters[1];
+  const uint32_t count = a.counters[2];
   T* w = reinterpret_cast<T*>(a.w);
   for (uint32_t e = blockIdx.x; e < count; e += gridDim.x) {  // every branch below is uniform over the workgroup
-    const uint32_t u = a.multi_list[e];
+    const uint32_t u = a.long_list[e];
     const uint32_t key = a.unique_keys[u];
     if (key < a.key_base || (uint64_t)(key - a.key_base) >= a.rows) continue;  // another table's row
     const uint32_t s = a.seg_off[u], end = a.seg_off[u + 1];
     const uint32_t t0 = s / kTile, t1 = (end - 1) / kTile;
     const uint32_t np = t1 - t0 + 1;
-    if (np <= kShortSpan) continue;  // done by k_fixup_short
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f), comp = acc;
     for (uint32_t k0 = g; k0 < np; k0 += 4 * NG) {  // four loads in flight per lane
       float4 v[4];
@@ -427,6 +451,14 @@ hipError_t launch_tile_reduce_update(const TableView& t, const BackwardArgs& b, 
   }
 }
 
+hipError_t launch_classify_multi(const BackwardArgs& b, uint32_t* counters, uint32_t* long_list, hipStream_t stream) {
+  if (b.n == 0) return hipSuccess;
+  const uint32_t tiles = (b.n + kTile - 1) / kTile;  // multi-tile segments <= tiles; threads past the list idle
+  hipLaunchKernelGGL(k_classify_multi, dim3((tiles + kBlock - 1) / kBlock), dim3(kBlock), 0, stream, b.seg_off,
+                     b.multi_list, counters, long_list);
+  return hipGetLastError();
+}
+
 hipError_t launch_fixup(const TableView& t, const BackwardArgs& b, hipStream_t stream) {
   if (b.n == 0) return hipSuccess;
   FixupArgs a;
@@ -434,6 +466,7 @@ hipError_t launch_fixup(const TableView& t, const BackwardArgs& b, hipStream_t s
   a.seg_off = b.seg_off;
   a.counters = b.counters;
   a.multi_list = b.multi_list;
+  a.long_list = b.long_list;
   a.partials = b.partials;
   a.pstride = b.pstride;
   a.w = t.w;

@@ -4,7 +4,6 @@
 
 #include <cmath>
 #include <cstdio>
-#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -49,8 +48,7 @@ struct emb_ctx {
   int mix = 0, opt = 0;
   float lr = 0, eps = 0;
   int key_bits = 1;
-  int sort_max_bits = 8;
-  int tile_order = 1;
+  int sort_max_bits = 8;  // 9-bit digits save a pass at 26 key bits but scatter in shorter runs: measured no faster
   int uniform = 0;
   uint32_t pstride = 0;
   std::vector<TableView> tables;
@@ -60,7 +58,8 @@ struct emb_ctx {
   // workspace
   uint32_t *keys[2] = {nullptr, nullptr}, *bags[2] = {nullptr, nullptr};
   uint32_t *hist = nullptr, *total = nullptr, *blk_heads = nullptr, *blk_multi = nullptr;
-  uint32_t *unique_keys = nullptr, *seg_off = nullptr, *multi_list = nullptr, *counters = nullptr, *ranges = nullptr;
+  uint32_t *unique_keys = nullptr, *seg_off = nullptr, *multi_list = nullptr, *long_list = nullptr;
+  uint32_t *counters = nullptr, *ranges = nullptr;
   float* partials = nullptr;
   uint32_t *tile_key[2] = {nullptr, nullptr}, *tile_val[2] = {nullptr, nullptr};
   // last backward
@@ -170,7 +169,7 @@ int check_batch(emb_ctx* ctx, const emb_batch* b) {
 // Every buffer the backward kernels dereference; a null here would be a device-side fault.
 bool workspace_complete(const emb_ctx* c) {
   const void* ptrs[] = {c->keys[0],  c->keys[1],     c->bags[0], c->bags[1],    c->hist,     c->total,
-                        c->blk_heads, c->blk_multi,  c->unique_keys, c->seg_off, c->multi_list, c->counters,
+                        c->blk_heads, c->blk_multi,  c->unique_keys, c->seg_off, c->multi_list, c->long_list, c->counters,
                         c->tile_key[0], c->tile_key[1], c->tile_val[0], c->tile_val[1],
                         c->ranges,    c->partials,   c->key_base_dev, c->slots.salt, c->slots.rows, c->slots.mask,
                         c->slots.key_base, c->slots.col};
@@ -194,7 +193,7 @@ int bit_length(uint64_t v) {
 
 extern "C" {
 
-int emb_create(const emb_config* cfg, emb_ctx** out) {
+static int emb_create_impl(const emb_config* cfg, emb_ctx** out) {
   if (!cfg || !out) return fail(nullptr, EMB_EINVAL, "null argument");
   if (cfg->num_tables == 0 || cfg->num_tables > 1023 || !cfg->tables)
     return fail(nullptr, EMB_EINVAL, "num_tables must be in 1..1023");
@@ -237,6 +236,15 @@ int emb_create(const emb_config* cfg, emb_ctx** out) {
 
   emb_ctx* ctx = new (std::nothrow) emb_ctx();
   if (!ctx) return fail(nullptr, EMB_ENOMEM, "out of host memory");
+  struct Guard {  // frees a half-built context on every early exit, exceptions included
+    emb_ctx* c;
+    ~Guard() {
+      if (c) {
+        free_all(c);
+        delete c;
+      }
+    }
+  } guard{ctx};
   ctx->device = cfg->device;
   ctx->S = cfg->num_slots;
   ctx->max_batch = cfg->max_batch;
@@ -248,19 +256,12 @@ int emb_create(const emb_config* cfg, emb_ctx** out) {
   ctx->key_bits = bit_length(total_rows - 1);
   if (ctx->key_bits < 1) ctx->key_bits = 1;
   ctx->uniform = cfg->num_tables == 1;
-  if (const char* v = std::getenv("PEMB_SORT_MAX_BITS")) ctx->sort_max_bits = std::atoi(v);  // tuning knobs
-  if (const char* v = std::getenv("PEMB_TILE_ORDER")) ctx->tile_order = std::atoi(v);
   ctx->pstride = max_dim;
 
-#define CK(call, what)                                  \
-  do {                                                  \
-    hipError_t _e = (call);                             \
-    if (_e != hipSuccess) {                             \
-      int _rc = fail_hip(nullptr, what, _e);            \
-      free_all(ctx);                                    \
-      delete ctx;                                       \
-      return _rc;                                       \
-    }                                                   \
+#define CK(call, what)                                         \
+  do {                                                         \
+    hipError_t _e = (call);                                    \
+    if (_e != hipSuccess) return fail_hip(nullptr, what, _e);  \
   } while (0)
 
   // tables + state
@@ -343,6 +344,7 @@ int emb_create(const emb_config* cfg, emb_ctx** out) {
   CK(dev_alloc(ctx, &ctx->unique_keys, cap), "hipMalloc(unique keys)");
   CK(dev_alloc(ctx, &ctx->seg_off, cap + 1), "hipMalloc(segment offsets)");
   CK(dev_alloc(ctx, &ctx->multi_list, ntiles), "hipMalloc(multi-tile list)");
+  CK(dev_alloc(ctx, &ctx->long_list, ntiles), "hipMalloc(long segment list)");
   CK(dev_alloc(ctx, &ctx->counters, 8), "hipMalloc(counters)");
   CK(dev_alloc(ctx, &ctx->ranges, cfg->num_tables + 1), "hipMalloc(table ranges)");
   CK(dev_alloc(ctx, &ctx->partials, 2 * ntiles * ctx->pstride), "hipMalloc(partials)");
@@ -353,6 +355,7 @@ int emb_create(const emb_config* cfg, emb_ctx** out) {
 
   CK(hipDeviceSynchronize(), "table initialisation");
 #undef CK
+  guard.c = nullptr;
   *out = ctx;
   return EMB_OK;
 }
@@ -372,7 +375,7 @@ int emb_destroy(emb_ctx* ctx) {
     if (_e != hipSuccess) return fail_hip(ctx, what, _e);    \
   } while (0)
 
-int emb_lookup_pool(emb_ctx* ctx, const emb_batch* batch, float* pooled, void* hip_stream) {
+static int emb_lookup_pool_impl(emb_ctx* ctx, const emb_batch* batch, float* pooled, void* hip_stream) {
   int rc = check_batch(ctx, batch);
   if (rc) return rc;
   if (batch->batch_size == 0) return EMB_OK;
@@ -388,7 +391,7 @@ int emb_lookup_pool(emb_ctx* ctx, const emb_batch* batch, float* pooled, void* h
   return EMB_OK;
 }
 
-int emb_hash_rows(emb_ctx* ctx, const emb_batch* batch, uint32_t* rows_out, void* hip_stream) {
+static int emb_hash_rows_impl(emb_ctx* ctx, const emb_batch* batch, uint32_t* rows_out, void* hip_stream) {
   int rc = check_batch(ctx, batch);
   if (rc) return rc;
   if (batch->num_ids == 0) return EMB_OK;
@@ -401,7 +404,7 @@ int emb_hash_rows(emb_ctx* ctx, const emb_batch* batch, uint32_t* rows_out, void
   return EMB_OK;
 }
 
-int emb_backward_update(emb_ctx* ctx, const emb_batch* batch, const float* d_pooled, void* hip_stream) {
+static int emb_backward_update_impl(emb_ctx* ctx, const emb_batch* batch, const float* d_pooled, void* hip_stream) {
   int rc = check_batch(ctx, batch);
   if (rc) return rc;
   if (!workspace_complete(ctx)) return fail(ctx, EMB_ESTATE, "workspace is incomplete (a buffer is null)");
@@ -471,7 +474,8 @@ int emb_backward_update(emb_ctx* ctx, const emb_batch* batch, const float* d_poo
   a.seg_off = ctx->seg_off;
   a.counters = ctx->counters;
   a.multi_list = ctx->multi_list;
-  if (ctx->tile_order) {
+  a.long_list = ctx->long_list;
+  {
     StageTimer tm(ctx, ST_TILE_ORDER, stream);
     // 256 buckets of consecutive bags (sample-major), whatever the batch size
     int shift = bit_length((uint64_t)batch->batch_size * ctx->S - 1) - 8;
@@ -489,6 +493,10 @@ int emb_backward_update(emb_ctx* ctx, const emb_batch* batch, const float* d_poo
     a.range = multi_table ? ctx->ranges + t : nullptr;
     CKH(launch_tile_reduce_update(ctx->tables[t], a, stream), "tile_reduce_update");
   }
+  {
+    StageTimer tm(ctx, ST_FIXUP, stream);
+    CKH(launch_classify_multi(a, ctx->counters, ctx->long_list, stream), "classify_multi");
+  }
   for (size_t t = 0; t < ctx->tables.size(); ++t) {
     StageTimer tm(ctx, ST_FIXUP, stream);
     CKH(launch_fixup(ctx->tables[t], a, stream), "fixup");
@@ -496,7 +504,7 @@ int emb_backward_update(emb_ctx* ctx, const emb_batch* batch, const float* d_poo
   return EMB_OK;
 }
 
-int emb_dedup_sizes(emb_ctx* ctx, uint64_t* num_unique, uint64_t* num_ids) {
+static int emb_dedup_sizes_impl(emb_ctx* ctx, uint64_t* num_unique, uint64_t* num_ids) {
   if (!ctx) return fail(nullptr, EMB_EINVAL, "null context");
   if (!ctx->have_dedup) return fail(ctx, EMB_ESTATE, "no emb_backward_update has run on this context");
   CKH(hipSetDevice(ctx->device), "hipSetDevice");
@@ -508,9 +516,9 @@ int emb_dedup_sizes(emb_ctx* ctx, uint64_t* num_unique, uint64_t* num_ids) {
   return EMB_OK;
 }
 
-int emb_read_dedup(emb_ctx* ctx, uint64_t* keys, uint32_t* seg_off, uint32_t* seg_bags) {
+static int emb_read_dedup_impl(emb_ctx* ctx, uint64_t* keys, uint32_t* seg_off, uint32_t* seg_bags) {
   uint64_t U = 0, N = 0;
-  int rc = emb_dedup_sizes(ctx, &U, &N);
+  int rc = emb_dedup_sizes_impl(ctx, &U, &N);
   if (rc) return rc;
   if (keys && U) {
     std::vector<uint32_t> tmp(U);
@@ -569,7 +577,7 @@ static int rows_io(emb_ctx* ctx, uint32_t table, const uint64_t* rows, uint64_t 
   return EMB_OK;
 }
 
-int emb_read_rows(emb_ctx* ctx, uint32_t table, const uint64_t* rows, uint64_t n, float* w, float* acc) {
+static int emb_read_rows_impl(emb_ctx* ctx, uint32_t table, const uint64_t* rows, uint64_t n, float* w, float* acc) {
   if (ctx) {
     (void)hipSetDevice(ctx->device);
     (void)hipDeviceSynchronize();
@@ -577,7 +585,7 @@ int emb_read_rows(emb_ctx* ctx, uint32_t table, const uint64_t* rows, uint64_t n
   return rows_io(ctx, table, rows, n, w, acc, nullptr, nullptr, false);
 }
 
-int emb_write_rows(emb_ctx* ctx, uint32_t table, const uint64_t* rows, uint64_t n, const float* w, const float* acc) {
+static int emb_write_rows_impl(emb_ctx* ctx, uint32_t table, const uint64_t* rows, uint64_t n, const float* w, const float* acc) {
   if (ctx) {
     (void)hipSetDevice(ctx->device);
     (void)hipDeviceSynchronize();
@@ -619,7 +627,7 @@ static int drain_events(emb_ctx* ctx) {
   return EMB_OK;
 }
 
-int emb_read_stage_ms(emb_ctx* ctx, float* ms, uint32_t* launches) {
+static int emb_read_stage_ms_impl(emb_ctx* ctx, float* ms, uint32_t* launches) {
   if (!ctx) return fail(nullptr, EMB_EINVAL, "null context");
   int rc = drain_events(ctx);
   if (rc) return rc;
@@ -630,7 +638,7 @@ int emb_read_stage_ms(emb_ctx* ctx, float* ms, uint32_t* launches) {
   return EMB_OK;
 }
 
-int emb_reset_stage_ms(emb_ctx* ctx) {
+static int emb_reset_stage_ms_impl(emb_ctx* ctx) {
   if (!ctx) return fail(nullptr, EMB_EINVAL, "null context");
   int rc = drain_events(ctx);
   if (rc) return rc;
@@ -640,6 +648,29 @@ int emb_reset_stage_ms(emb_ctx* ctx) {
   }
   return EMB_OK;
 }
+
+
+// ---- exported entry points: no exception leaves the library ----
+#define PEMB_GUARDED(ctx_expr, call)                                               \
+  try {                                                                            \
+    return call;                                                                   \
+  } catch (const std::bad_alloc&) {                                                \
+    return fail(ctx_expr, EMB_ENOMEM, "out of host memory");                       \
+  } catch (...) {                                                                  \
+    return fail(ctx_expr, EMB_ESTATE, "unexpected exception inside the library");  \
+  }
+
+int emb_create(const emb_config* cfg, emb_ctx** out) { PEMB_GUARDED(nullptr, emb_create_impl(cfg, out)) }
+int emb_lookup_pool(emb_ctx* ctx, const emb_batch* batch, float* pooled, void* hip_stream) { PEMB_GUARDED(ctx, emb_lookup_pool_impl(ctx, batch, pooled, hip_stream)) }
+int emb_hash_rows(emb_ctx* ctx, const emb_batch* batch, uint32_t* rows_out, void* hip_stream) { PEMB_GUARDED(ctx, emb_hash_rows_impl(ctx, batch, rows_out, hip_stream)) }
+int emb_backward_update(emb_ctx* ctx, const emb_batch* batch, const float* d_pooled, void* hip_stream) { PEMB_GUARDED(ctx, emb_backward_update_impl(ctx, batch, d_pooled, hip_stream)) }
+int emb_dedup_sizes(emb_ctx* ctx, uint64_t* num_unique, uint64_t* num_ids) { PEMB_GUARDED(ctx, emb_dedup_sizes_impl(ctx, num_unique, num_ids)) }
+int emb_read_dedup(emb_ctx* ctx, uint64_t* keys, uint32_t* seg_off, uint32_t* seg_bags) { PEMB_GUARDED(ctx, emb_read_dedup_impl(ctx, keys, seg_off, seg_bags)) }
+int emb_read_rows(emb_ctx* ctx, uint32_t table, const uint64_t* rows, uint64_t n, float* w, float* acc) { PEMB_GUARDED(ctx, emb_read_rows_impl(ctx, table, rows, n, w, acc)) }
+int emb_write_rows(emb_ctx* ctx, uint32_t table, const uint64_t* rows, uint64_t n, const float* w, const float* acc) { PEMB_GUARDED(ctx, emb_write_rows_impl(ctx, table, rows, n, w, acc)) }
+int emb_read_stage_ms(emb_ctx* ctx, float* ms, uint32_t* launches) { PEMB_GUARDED(ctx, emb_read_stage_ms_impl(ctx, ms, launches)) }
+int emb_reset_stage_ms(emb_ctx* ctx) { PEMB_GUARDED(ctx, emb_reset_stage_ms_impl(ctx)) }
+#undef PEMB_GUARDED
 
 uint64_t emb_device_bytes(emb_ctx* ctx) { return ctx ? ctx->device_bytes : 0; }
 

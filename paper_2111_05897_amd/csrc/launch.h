@@ -64,7 +64,8 @@ hipError_t launch_radix_scatter(const SortPlan& p, int shift, const uint32_t* ki
                                 uint32_t* kout, uint32_t* pout, const uint32_t* hist, const uint32_t* total,
                                 hipStream_t stream);
 // Run heads of the sorted keys -> unique_keys[U], seg_off[U+1], and multi_list[M] = indices u (ascending)
-// of the runs that cross an edge between tiles of kTile positions; counters[0] = U, counters[1] = M.
+// of the runs that cross an edge between tiles of kTile positions; counters[0] = U, counters[1] = M,
+// counters[2] = 0.
 static_assert(kUniqueTile % kTile == 0, "a unique block must end on a tile edge");
 hipError_t launch_unique(const uint32_t* keys, uint32_t n, uint32_t* blk_heads, uint32_t* blk_multi,
                          uint32_t* unique_keys, uint32_t* seg_off, uint32_t* multi_list, uint32_t* counters,
@@ -88,8 +89,9 @@ struct BackwardArgs {
   // fix-up only
   const uint32_t* unique_keys;
   const uint32_t* seg_off;
-  const uint32_t* counters;  // [0] = U, [1] = number of multi-tile segments
+  const uint32_t* counters;  // [0] = U, [1] = number of multi-tile segments, [2] = of those, the long ones
   const uint32_t* multi_list;
+  const uint32_t* long_list; // multi-tile segments spanning more than 16 tiles (filled by launch_classify_multi)
 };
 hipError_t launch_table_ranges(const uint32_t* keys, uint32_t n, const uint32_t* key_base_dev, uint32_t num_tables,
                                uint32_t* ranges /*[num_tables+1]*/, hipStream_t stream);
@@ -103,6 +105,7 @@ hipError_t launch_tile_order(const uint32_t* keys, const uint32_t* bags, uint32_
                              uint32_t* const tile_val[2], uint32_t* hist, uint32_t* total,
                              const uint32_t** perm_out, hipStream_t stream);
 hipError_t launch_tile_reduce_update(const TableView& t, const BackwardArgs& a, hipStream_t stream);
+hipError_t launch_classify_multi(const BackwardArgs& a, uint32_t* counters, uint32_t* long_list, hipStream_t stream);
 hipError_t launch_fixup(const TableView& t, const BackwardArgs& a, hipStream_t stream);
 
 }  // namespace pemb

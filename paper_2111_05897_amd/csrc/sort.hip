@@ -311,6 +311,7 @@ __global__ __launch_bounds__(kBlock) void k_unique_scan(uint32_t* __restrict__ b
   if (threadIdx.x == 0) {
     counters[0] = tot_h;
     counters[1] = tot_m;
+    counters[2] = 0;
     seg_off[tot_h] = n;
   }
 }

@@ -231,3 +231,26 @@ def test_staleness1_overlap_envelope(B):
             assert (err <= envelope + slack).all(), f"step {t + 1}: pooled outside the staleness envelope"
     util.compare_rows(ctx, orc, cfg, np.unique(np.concatenate(touched)))
     ctx.close()
+
+
+def test_stage_timing_reports_every_kernel_stage(B):
+    import torch
+    w = W.make_workload(1, scale=1 / 16)
+    b = W.make_batch(w)
+    ctx = B.EmbContext.from_config(w.cfg, max_batch=b.batch_size, max_ids=b.num_ids)
+    db = B.DeviceBatch(b.batch_size, b.ids, b.offsets)
+    dp = torch.from_numpy(W.make_d_pooled(w)).cuda()
+    ctx.emb_set_profiling(True)
+    for _ in range(3):
+        ctx.emb_lookup_pool(db)
+        ctx.emb_backward_update(db, dp)
+    st = ctx.emb_read_stage_ms()
+    assert st["gather_pool"][1] == 3 and st["reduce_update"][1] == 3 and st["sort_scatter"][1] == 9
+    assert all(ms > 0 for ms, n in st.values() if n)
+    ctx.emb_reset_stage_ms()
+    assert all(n == 0 for _, n in ctx.emb_read_stage_ms().values())
+    ctx.emb_set_profiling(False)
+    ctx.emb_lookup_pool(db)
+    assert all(n == 0 for _, n in ctx.emb_read_stage_ms().values())
+    assert ctx.emb_device_bytes() > w.cfg.tables[0].rows * w.cfg.tables[0].dim * 4
+    ctx.close()
