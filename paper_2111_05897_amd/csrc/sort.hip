@@ -18,6 +18,31 @@ static_assert(kSortTile == kBlock * kItems, "tile geometry");
 
 constexpr int kHistThreads = 1024;  // the histogram is latency-bound: more waves per chunk than the scatter uses
 
+// Counts the digits of four consecutive keys.  After the first passes the many occurrences of a hot key
+// sit next to each other, and 64 lanes adding to one LDS counter serialise; so equal digits are merged
+// first: inside the lane's four keys, and -- when every lane of the wave holds four keys of one and the
+// same digit -- across the wave, where a single lane adds 256.
+template <int BITS>
+__device__ __forceinline__ void count4(uint32_t* h, uint4 a, int shift, int lane) {
+  constexpr uint32_t M = (1u << BITS) - 1u;
+  const uint32_t d0 = (a.x >> shift) & M, d1 = (a.y >> shift) & M, d2 = (a.z >> shift) & M, d3 = (a.w >> shift) & M;
+  const bool same4 = d0 == d1 && d1 == d2 && d2 == d3;
+  const uint32_t first = __builtin_amdgcn_readfirstlane(d0);
+  if (__all(same4 && d0 == first)) {  // whole wave, one digit (partial waves never get here with inactive lanes)
+    if (lane == 0) atomicAdd(&h[first], 4u * kWave);
+    return;
+  }
+  if (same4) {
+    atomicAdd(&h[d0], 4u);
+    return;
+  }
+  uint32_t c = 1;  // run-length merge of the four digits
+  if (d1 == d0) ++c; else { atomicAdd(&h[d0], c); c = 1; }
+  if (d2 == d1) ++c; else { atomicAdd(&h[d1], c); c = 1; }
+  if (d3 == d2) ++c; else { atomicAdd(&h[d2], c); c = 1; }
+  atomicAdd(&h[d3], c);
+}
+
 template <int BITS>
 __global__ __launch_bounds__(kHistThreads) void k_radix_hist(const uint32_t* __restrict__ keys, uint32_t n,
                                                              uint32_t chunk, int shift, uint32_t nblk,
@@ -25,33 +50,24 @@ __global__ __launch_bounds__(kHistThreads) void k_radix_hist(const uint32_t* __r
   constexpr int NB = 1 << BITS;
   constexpr uint32_t TH = kHistThreads;
   __shared__ uint32_t h[NB];
+  const int lane = threadIdx.x & (kWave - 1);
   for (int i = threadIdx.x; i < NB; i += TH) h[i] = 0;
   __syncthreads();
   const uint32_t beg = blockIdx.x * chunk;
   const uint32_t end = (n - beg < chunk) ? n : beg + chunk;  // beg < n by construction of the plan
-  // beg is a multiple of the tile size and the buffer is 256-byte aligned: 16-byte loads, two in flight
+  // beg is a multiple of the tile size and the buffer is 256-byte aligned: 16-byte loads.
   const uint32_t nvec = (end - beg) / 4;
+  const uint32_t nvec_full = nvec / kWave * kWave;  // vectors that whole waves take (count4 needs all 64 lanes)
   const uint4* __restrict__ kv = reinterpret_cast<const uint4*>(keys + beg);
   uint32_t v = threadIdx.x;
-  for (; v + TH < nvec; v += 2 * TH) {
+  for (; v + TH < nvec_full; v += 2 * TH) {  // both loads in flight before the counting
     const uint4 a = kv[v], b = kv[v + TH];
-    atomicAdd(&h[(a.x >> shift) & (NB - 1)], 1u);
-    atomicAdd(&h[(a.y >> shift) & (NB - 1)], 1u);
-    atomicAdd(&h[(a.z >> shift) & (NB - 1)], 1u);
-    atomicAdd(&h[(a.w >> shift) & (NB - 1)], 1u);
-    atomicAdd(&h[(b.x >> shift) & (NB - 1)], 1u);
-    atomicAdd(&h[(b.y >> shift) & (NB - 1)], 1u);
-    atomicAdd(&h[(b.z >> shift) & (NB - 1)], 1u);
-    atomicAdd(&h[(b.w >> shift) & (NB - 1)], 1u);
+    count4<BITS>(h, a, shift, lane);
+    count4<BITS>(h, b, shift, lane);
   }
-  for (; v < nvec; v += TH) {
-    const uint4 a = kv[v];
-    atomicAdd(&h[(a.x >> shift) & (NB - 1)], 1u);
-    atomicAdd(&h[(a.y >> shift) & (NB - 1)], 1u);
-    atomicAdd(&h[(a.z >> shift) & (NB - 1)], 1u);
-    atomicAdd(&h[(a.w >> shift) & (NB - 1)], 1u);
-  }
-  for (uint32_t i = beg + nvec * 4 + threadIdx.x; i < end; i += TH)
+  for (; v < nvec_full; v += TH) count4<BITS>(h, kv[v], shift, lane);
+  // ragged rest: fewer than 64 vectors, then fewer than 4 keys
+  for (uint32_t i = beg + nvec_full * 4 + threadIdx.x; i < end; i += TH)
     atomicAdd(&h[(keys[i] >> shift) & (NB - 1)], 1u);
   __syncthreads();
   for (int d = threadIdx.x; d < NB; d += TH) hist[(size_t)d * nblk + blockIdx.x] = h[d];
