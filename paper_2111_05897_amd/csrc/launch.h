@@ -9,7 +9,7 @@ namespace pemb {
 constexpr uint32_t kTile = 32;
 // Radix sort geometry: a block ranks and scatters tiles of 256 threads x 8 keys.
 constexpr uint32_t kSortTile = 2048;
-constexpr uint32_t kSortMaxBlocks = 1024;
+constexpr uint32_t kSortMaxBlocks = 2048;
 constexpr int kSortMaxBits = 9;                 // widest digit a pass may use (512 bins)
 constexpr uint32_t kUniqueTile = 2048;
 
