@@ -249,22 +249,27 @@ __global__ __launch_bounds__(kBlock) void k_classify_multi(const uint32_t* __res
                                                            const uint32_t* __restrict__ multi_list,
                                                            uint32_t* __restrict__ counters,
                                                            uint32_t* __restrict__ long_list) {
-  const uint32_t e = blockIdx.x * kBlock + threadIdx.x;
-  bool is_long = false;
-  uint32_t u = 0;
-  if (e < counters[1]) {
-    u = multi_list[e];
-    const uint32_t s = seg_off[u], end = seg_off[u + 1];
-    is_long = (end - 1) / kTile - s / kTile + 1 > kShortSpan;
-  }
-  const uint64_t m = __ballot(is_long);
-  if (m == 0) return;
+  const uint32_t count = counters[1];
   const int lane = threadIdx.x & (kWave - 1);
-  const int leader = __ffsll((unsigned long long)m) - 1;
-  uint32_t base = 0;
-  if (lane == leader) base = atomicAdd(&counters[2], (uint32_t)__popcll(m));
-  base = __shfl(base, leader);
-  if (is_long) long_list[base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull))] = u;
+  // grid-stride; every wave runs the same number of rounds for all its lanes (the ballot needs them all)
+  for (uint32_t e0 = blockIdx.x * kBlock; e0 < count; e0 += gridDim.x * kBlock) {
+    const uint32_t e = e0 + threadIdx.x;
+    bool is_long = false;
+    uint32_t u = 0;
+    if (e < count) {
+      u = multi_list[e];
+      const uint32_t s = seg_off[u], end = seg_off[u + 1];
+      is_long = (end - 1) / kTile - s / kTile + 1 > kShortSpan;
+    }
+    const uint64_t m = __ballot(is_long);
+    if (m != 0) {
+      const int leader = __ffsll((unsigned long long)m) - 1;
+      uint32_t base = 0;
+      if (lane == leader) base = atomicAdd(&counters[2], (uint32_t)__popcll(m));
+      base = __shfl(base, leader);
+      if (is_long) long_list[base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull))] = u;
+    }
+  }
 }
 
 // Longer segments (hot keys): one workgroup per entry of long_list (grid-stride).  Group g adds partials
@@ -453,8 +458,9 @@ hipError_t launch_tile_reduce_update(const TableView& t, const BackwardArgs& b, 
 
 hipError_t launch_classify_multi(const BackwardArgs& b, uint32_t* counters, uint32_t* long_list, hipStream_t stream) {
   if (b.n == 0) return hipSuccess;
-  const uint32_t tiles = (b.n + kTile - 1) / kTile;  // multi-tile segments <= tiles; threads past the list idle
-  hipLaunchKernelGGL(k_classify_multi, dim3((tiles + kBlock - 1) / kBlock), dim3(kBlock), 0, stream, b.seg_off,
+  const uint32_t tiles = (b.n + kTile - 1) / kTile;  // multi-tile segments <= tiles; the kernel strides over the list
+  const uint32_t want = (tiles + kBlock - 1) / kBlock;
+  hipLaunchKernelGGL(k_classify_multi, dim3(want < 512u ? want : 512u), dim3(kBlock), 0, stream, b.seg_off,
                      b.multi_list, counters, long_list);
   return hipGetLastError();
 }

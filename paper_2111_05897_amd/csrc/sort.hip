@@ -297,15 +297,19 @@ __global__ __launch_bounds__(kBlock) void k_unique_count(const uint32_t* __restr
   }
 }
 
-// Single block: exclusive scans of blk_heads[nb] and blk_multi[nb] in place; counters[0] = U,
-// counters[1] = number of multi-tile runs; seg_off[U] = n.  Thread t owns the entries
-// [t*per, (t+1)*per): serial sum, one block scan, serial write-back.
-__global__ __launch_bounds__(kBlock) void k_unique_scan(uint32_t* __restrict__ blk_heads,
-                                                        uint32_t* __restrict__ blk_multi, uint32_t nb, uint32_t n,
-                                                        uint32_t* __restrict__ counters,
-                                                        uint32_t* __restrict__ seg_off) {
-  __shared__ uint32_t s_w[kWavesPerBlock];
-  const uint32_t per = (nb + kBlock - 1) / kBlock;
+// Single block of 1024 threads: exclusive scans of blk_heads[nb] and blk_multi[nb] in place;
+// counters[0] = U, counters[1] = number of multi-tile runs, counters[2] = 0; seg_off[U] = n.
+// Thread t owns the entries [t*per, (t+1)*per): serial sums, one scan over the 1024 sums, serial write-back.
+constexpr int kScanThreads = 1024;
+
+__global__ __launch_bounds__(kScanThreads) void k_unique_scan(uint32_t* __restrict__ blk_heads,
+                                                              uint32_t* __restrict__ blk_multi, uint32_t nb,
+                                                              uint32_t n, uint32_t* __restrict__ counters,
+                                                              uint32_t* __restrict__ seg_off) {
+  constexpr int NW = kScanThreads / kWave;
+  __shared__ uint32_t s_h[NW], s_m[NW];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+  const uint32_t per = (nb + kScanThreads - 1) / kScanThreads;
   const uint32_t b0 = threadIdx.x * per;
   uint32_t sum_h = 0, sum_m = 0;
   for (uint32_t j = 0; j < per; ++j)
@@ -313,9 +317,31 @@ __global__ __launch_bounds__(kBlock) void k_unique_scan(uint32_t* __restrict__ b
       sum_h += blk_heads[b0 + j];
       sum_m += blk_multi[b0 + j];
     }
-  uint32_t tot_h, tot_m;
-  uint32_t run_h = block_exclusive_scan(sum_h, s_w, &tot_h);
-  uint32_t run_m = block_exclusive_scan(sum_m, s_w, &tot_m);
+  uint32_t inc_h = sum_h, inc_m = sum_m;  // inclusive scans inside the wave
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const uint32_t th = __shfl_up(inc_h, off), tm = __shfl_up(inc_m, off);
+    if (lane >= off) {
+      inc_h += th;
+      inc_m += tm;
+    }
+  }
+  if (lane == kWave - 1) {
+    s_h[wave] = inc_h;
+    s_m[wave] = inc_m;
+  }
+  __syncthreads();
+  uint32_t run_h = inc_h - sum_h, run_m = inc_m - sum_m, tot_h = 0, tot_m = 0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    const uint32_t xh = s_h[w], xm = s_m[w];
+    if (w < wave) {
+      run_h += xh;
+      run_m += xm;
+    }
+    tot_h += xh;
+    tot_m += xm;
+  }
   for (uint32_t j = 0; j < per; ++j)
     if (b0 + j < nb) {
       const uint32_t vh = blk_heads[b0 + j], vm = blk_multi[b0 + j];
@@ -435,7 +461,8 @@ hipError_t launch_unique(const uint32_t* keys, uint32_t n, uint32_t* blk_heads, 
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(k_unique_scan, dim3(1), dim3(kBlock), 0, stream, blk_heads, blk_multi, nb, n, counters, seg_off);
+  hipLaunchKernelGGL(k_unique_scan, dim3(1), dim3(kScanThreads), 0, stream, blk_heads, blk_multi, nb, n, counters,
+                     seg_off);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (nb) {
