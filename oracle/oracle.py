@@ -31,40 +31,50 @@ def _p(a, t):
     return a.ctypes.data_as(C.POINTER(t))
 
 
+def load(path: str):
+    """Loads an oracle library from `path` and declares its prototypes (tests use this for deliberately
+    broken copies of the oracle, to show that the pins notice)."""
+    L = C.CDLL(path)
+    _configure(L)
+    return L
+
+
 def lib():
     global _lib
     if _lib is None:
-        L = C.CDLL(build())
-        L.orc_mix64.restype = C.c_uint64
-        L.orc_mix64.argtypes = [C.c_uint64]
-        L.orc_round_bf16.restype = C.c_float
-        L.orc_round_bf16.argtypes = [C.c_float]
-        L.orc_init_value.restype = C.c_float
-        L.orc_init_value.argtypes = [C.c_uint64, C.c_uint32, C.c_uint64, C.c_uint32, C.c_uint32, C.c_float, C.c_float]
-        L.orc_create.restype = C.c_void_p
-        L.orc_create.argtypes = [C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p,
-                                 C.c_int, C.c_int, C.c_float, C.c_float, C.c_float, C.c_uint64, C.c_float, C.c_float,
-                                 C.c_int]
-        L.orc_destroy.argtypes = [C.c_void_p]
-        L.orc_pooled_width.restype = C.c_uint32
-        L.orc_pooled_width.argtypes = [C.c_void_p]
-        L.orc_rows_stored.restype = C.c_uint64
-        L.orc_rows_stored.argtypes = [C.c_void_p, C.c_uint32]
-        for name in ("orc_hash_rows", "orc_lookup_pool"):
-            getattr(L, name).argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p]
-        L.orc_dedup.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32]
-        L.orc_dedup_sizes.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
-        L.orc_dedup_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
-        L.orc_gradient.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p]
-        L.orc_grad_size.restype = C.c_uint64
-        L.orc_grad_size.argtypes = [C.c_void_p]
-        L.orc_grad_copy.argtypes = [C.c_void_p, C.c_void_p]
-        L.orc_apply_update.argtypes = [C.c_void_p]
-        L.orc_backward_update.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p]
-        L.orc_read_rows.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]
-        L.orc_write_rows.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]
-        _lib = L
+        _lib = load(build())
     return _lib
+
+
+def _configure(L):
+    L.orc_mix64.restype = C.c_uint64
+    L.orc_mix64.argtypes = [C.c_uint64]
+    L.orc_round_bf16.restype = C.c_float
+    L.orc_round_bf16.argtypes = [C.c_float]
+    L.orc_init_value.restype = C.c_float
+    L.orc_init_value.argtypes = [C.c_uint64, C.c_uint32, C.c_uint64, C.c_uint32, C.c_uint32, C.c_float, C.c_float]
+    L.orc_create.restype = C.c_void_p
+    L.orc_create.argtypes = [C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p,
+                             C.c_int, C.c_int, C.c_float, C.c_float, C.c_float, C.c_uint64, C.c_float, C.c_float,
+                             C.c_int]
+    L.orc_destroy.argtypes = [C.c_void_p]
+    L.orc_pooled_width.restype = C.c_uint32
+    L.orc_pooled_width.argtypes = [C.c_void_p]
+    L.orc_rows_stored.restype = C.c_uint64
+    L.orc_rows_stored.argtypes = [C.c_void_p, C.c_uint32]
+    for name in ("orc_hash_rows", "orc_lookup_pool"):
+        getattr(L, name).argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p]
+    L.orc_dedup.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32]
+    L.orc_dedup_sizes.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+    L.orc_dedup_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.orc_gradient.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p]
+    L.orc_grad_size.restype = C.c_uint64
+    L.orc_grad_size.argtypes = [C.c_void_p]
+    L.orc_grad_copy.argtypes = [C.c_void_p, C.c_void_p]
+    L.orc_apply_update.argtypes = [C.c_void_p]
+    L.orc_backward_update.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p]
+    L.orc_read_rows.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]
+    L.orc_write_rows.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p]
 
 
 def mix64(x: int) -> int:
