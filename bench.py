@@ -39,6 +39,46 @@ def algorithmic_bytes(tables):
     return out
 
 
+def bench_codec(args, w, binding, torch, np) -> int:
+    """Compress + decompress of one batch of pooled activations, one block per slot vector (section 4.2.3)."""
+    width = w.cfg.pooled_width
+    block_len = w.cfg.tables[0].dim
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(w.seed)
+    v = torch.randn((w.batch, width), generator=gen, device="cuda", dtype=torch.float32) * 0.05
+    n = v.numel()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    for _ in range(args.warmup):
+        q, norm = binding.emb_codec_compress(v, block_len)
+        binding.emb_codec_decompress(q, norm)
+    torch.cuda.synchronize()
+    t_c = t_d = 0.0
+    for _ in range(args.steps):
+        ev[0].record()
+        q, norm = binding.emb_codec_compress(v, block_len)
+        ev[1].record()
+        out = binding.emb_codec_decompress(q, norm)
+        ev[2].record()
+        torch.cuda.synchronize()
+        t_c += ev[0].elapsed_time(ev[1])
+        t_d += ev[1].elapsed_time(ev[2])
+    t_c, t_d = t_c / args.steps, t_d / args.steps
+    bytes_c = 4 * n + 2 * n + 4 * (n // block_len)      # fp32 read, fp16 + norm written
+    bytes_d = 2 * n + 4 * (n // block_len) + 4 * n      # fp16 + norm read, fp32 written
+    out_line = {
+        "metric": "value codec throughput (compress + decompress), 1 GPU", "value": round(n / ((t_c + t_d) * 1e-3), 1),
+        "unit": "values/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(t_c + t_d, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32->f16", "data": "synthetic",
+        "config": {"workload": w.name + "_pooled_codec", "values": n, "block_len": block_len, "kappa": 2.0 ** 15},
+        "roofline": {"bound": "hbm", "kernel": "codec_compress", "achieved": round(bytes_c / (t_c * 1e-3) / 1e9, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(bytes_c / (t_c * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                     "traffic": None, "avg_launch_ms": round(t_c, 4), "algorithmic_bytes_per_launch": bytes_c},
+        "decompress": {"achieved_GBps": round(bytes_d / (t_d * 1e-3) / 1e9, 1), "avg_launch_ms": round(t_d, 4)},
+    }
+    print(json.dumps(out_line))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -48,6 +88,8 @@ def main() -> int:
     ap.add_argument("--distinct-batches", type=int, default=4, help="synthetic batches generated and cycled")
     ap.add_argument("--overlap", action="store_true",
                     help="staleness-1 schedule: lookup(t+1) on a second stream while update(t) runs on the first")
+    ap.add_argument("--codec", action="store_true",
+                    help="instead of the training step, time the scaled-fp16 value codec on this config's pooled shape")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device-to-device copies (reference for rocprofv3 byte counters)")
@@ -65,6 +107,8 @@ def main() -> int:
     binding.load_library()
     w = W.make_workload(args.config)
     cfg = w.cfg
+    if args.codec:
+        return bench_codec(args, w, binding, torch, np)
     T = len(cfg.tables)
     e_of = [2 if t.dtype == W.BF16 else 4 for t in cfg.tables]
     slot_table = np.array([s.table for s in cfg.slots])

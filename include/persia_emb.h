@@ -156,6 +156,18 @@ const char* emb_stage_name(int stage);
 int emb_read_stage_ms(emb_ctx* ctx, float* ms, uint32_t* launches); /* host arrays [emb_stage_count()] */
 int emb_reset_stage_ms(emb_ctx* ctx);
 
+/* Lossy value codec for pooled activations and their gradients (section 4.2.3, "Lossy compression"):
+ * every block of block_len consecutive fp32 values v is scaled by kappa / ||v||_inf and converted to
+ * fp16 (round to nearest even); the inverse converts back to fp32 and divides by the same factor.
+ * The factor is formed in fp32 from the stored norm on both sides.  A block of zeros is stored as zeros.
+ * v, out: device fp32 [n_blocks * block_len]; q: device fp16 [n_blocks * block_len]; norm: device fp32
+ * [n_blocks] (||v||_inf of each block, written by compress, read by decompress).  block_len must be a
+ * multiple of 4, kappa finite and in (0, 65504]; values must be finite.  Enqueue-only; no context needed. */
+int emb_codec_compress(const float* v, uint64_t n_blocks, uint32_t block_len, float kappa, uint16_t* q, float* norm,
+                       void* hip_stream);
+int emb_codec_decompress(const uint16_t* q, const float* norm, uint64_t n_blocks, uint32_t block_len, float kappa,
+                         float* out, void* hip_stream);
+
 /* Bytes of device memory the context holds (tables, state, workspace). */
 uint64_t emb_device_bytes(emb_ctx* ctx);
 

@@ -79,6 +79,10 @@ def load_library() -> C.CDLL:
     L.emb_reset_stage_ms.argtypes = [vp]
     L.emb_device_bytes.argtypes = [vp]
     L.emb_device_bytes.restype = u64
+    L.emb_codec_compress.argtypes = [vp, u64, u32, C.c_float, vp, vp, vp]
+    L.emb_codec_decompress.argtypes = [vp, vp, u64, u32, C.c_float, vp, vp]
+    L.emb_codec_compress.restype = C.c_int
+    L.emb_codec_decompress.restype = C.c_int
     L.emb_last_error.argtypes = [vp]
     L.emb_last_error.restype = C.c_char_p
     for name in ("emb_create", "emb_destroy", "emb_lookup_pool", "emb_hash_rows", "emb_backward_update",
@@ -223,3 +227,28 @@ class EmbContext:
 
     def emb_device_bytes(self) -> int:
         return int(self.L.emb_device_bytes(self.h))
+
+
+def emb_codec_compress(v: torch.Tensor, block_len: int, kappa: float = 2.0 ** 15, stream=None):
+    """v: fp32 device tensor, numel a multiple of block_len -> (q fp16 [n_blocks, block_len], norm fp32 [n_blocks])."""
+    L = load_library()
+    assert v.is_contiguous() and v.dtype == torch.float32 and v.numel() % block_len == 0
+    n_blocks = v.numel() // block_len
+    q = torch.empty((n_blocks, block_len), dtype=torch.float16, device=v.device)
+    norm = torch.empty(max(n_blocks, 1), dtype=torch.float32, device=v.device)
+    rc = L.emb_codec_compress(v.data_ptr(), n_blocks, block_len, kappa, q.data_ptr(), norm.data_ptr(), _stream_ptr(stream))
+    if rc:
+        raise EmbError(rc, L.emb_last_error(None).decode())
+    return q, norm[:n_blocks]
+
+
+def emb_codec_decompress(q: torch.Tensor, norm: torch.Tensor, kappa: float = 2.0 ** 15, stream=None) -> torch.Tensor:
+    L = load_library()
+    assert q.is_contiguous() and q.dtype == torch.float16 and q.dim() == 2 and norm.dtype == torch.float32
+    n_blocks, block_len = q.shape
+    out = torch.empty((n_blocks, block_len), dtype=torch.float32, device=q.device)
+    rc = L.emb_codec_decompress(q.data_ptr(), norm.data_ptr(), n_blocks, block_len, kappa, out.data_ptr(),
+                                _stream_ptr(stream))
+    if rc:
+        raise EmbError(rc, L.emb_last_error(None).decode())
+    return out

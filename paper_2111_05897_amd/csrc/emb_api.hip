@@ -672,6 +672,30 @@ int emb_read_stage_ms(emb_ctx* ctx, float* ms, uint32_t* launches) { PEMB_GUARDE
 int emb_reset_stage_ms(emb_ctx* ctx) { PEMB_GUARDED(ctx, emb_reset_stage_ms_impl(ctx)) }
 #undef PEMB_GUARDED
 
+static int codec_args_ok(const void* a, const void* b, const void* c, uint64_t n_blocks, uint32_t block_len, float kappa) {
+  if (n_blocks == 0) return EMB_OK;
+  if (!a || !b || !c) return fail(nullptr, EMB_EINVAL, "codec: null buffer");
+  if (block_len == 0 || block_len % 4 != 0) return fail(nullptr, EMB_EINVAL, "codec: block_len must be a positive multiple of 4");
+  if (!(kappa > 0.f) || kappa > 65504.f) return fail(nullptr, EMB_EINVAL, "codec: kappa must be in (0, 65504]");
+  return EMB_OK;
+}
+
+int emb_codec_compress(const float* v, uint64_t n_blocks, uint32_t block_len, float kappa, uint16_t* q, float* norm,
+                       void* hip_stream) {
+  int rc = codec_args_ok(v, q, norm, n_blocks, block_len, kappa);
+  if (rc) return rc;
+  hipError_t e = launch_codec_compress(v, n_blocks, block_len, kappa, q, norm, (hipStream_t)hip_stream);
+  return e == hipSuccess ? EMB_OK : fail_hip(nullptr, "codec_compress", e);
+}
+
+int emb_codec_decompress(const uint16_t* q, const float* norm, uint64_t n_blocks, uint32_t block_len, float kappa,
+                         float* out, void* hip_stream) {
+  int rc = codec_args_ok(q, norm, out, n_blocks, block_len, kappa);
+  if (rc) return rc;
+  hipError_t e = launch_codec_decompress(q, norm, n_blocks, block_len, kappa, out, (hipStream_t)hip_stream);
+  return e == hipSuccess ? EMB_OK : fail_hip(nullptr, "codec_decompress", e);
+}
+
 uint64_t emb_device_bytes(emb_ctx* ctx) { return ctx ? ctx->device_bytes : 0; }
 
 const char* emb_last_error(emb_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }

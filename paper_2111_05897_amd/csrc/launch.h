@@ -108,4 +108,10 @@ hipError_t launch_tile_reduce_update(const TableView& t, const BackwardArgs& a, 
 hipError_t launch_classify_multi(const BackwardArgs& a, uint32_t* counters, uint32_t* long_list, hipStream_t stream);
 hipError_t launch_fixup(const TableView& t, const BackwardArgs& a, hipStream_t stream);
 
+// ---- codec.hip ----
+hipError_t launch_codec_compress(const float* v, uint64_t n_blocks, uint32_t block_len, float kappa, void* q_fp16,
+                                 float* norm, hipStream_t stream);
+hipError_t launch_codec_decompress(const void* q_fp16, const float* norm, uint64_t n_blocks, uint32_t block_len,
+                                   float kappa, float* out, hipStream_t stream);
+
 }  // namespace pemb
