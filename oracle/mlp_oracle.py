@@ -1,0 +1,63 @@
+"""CPU oracle of the dense step -- TEST INFRASTRUCTURE (numpy, fp64).
+
+Section 2.1: y^ = NN_{w_nn}(lookup_{w_emb}(x^ID), x^NID): the network takes the looked-up (pooled)
+embeddings concatenated with the non-ID features.  Algorithm 2: forward of the mini-batch, backward for
+F'^nn and F'^emb (the gradient of the loss w.r.t. the embedding activations, sent back to the embedding
+side), update w^nn <- w^nn - Omega^nn(F'^nn).  The network is a feed-forward ReLU net with one logit
+and the loss is binary cross-entropy on the logit; Omega^nn is plain SGD.  Readings where the paper is
+silent: the loss is the MEAN over the batch (Algorithm 2 writes a sum; `loss_mean=False` gives it);
+"bf16 MLP" means operands of every product are rounded to bf16 (inputs, weights, activations and the
+back-propagated deltas as they are stored) while sums are exact here (fp32 on the GPU); master weights
+and their update are fp32; the rounding is treated as the identity in the backward pass.
+"""
+import numpy as np
+
+
+def bf16(x):
+    """fp32 -> bf16 (round to nearest even) -> fp64, elementwise."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    r = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16) << 16
+    return r.astype(np.uint32).view(np.float32).astype(np.float64).reshape(np.shape(x))
+
+
+class MLP:
+    def __init__(self, weights, biases, lr, loss_mean=True, rounding=True):
+        """weights[l]: fp32 [in_l, out_l]; biases[l]: fp32 [out_l]; the last layer has out = 1."""
+        self.W = [np.array(w, dtype=np.float32) for w in weights]
+        self.b = [np.array(b, dtype=np.float32) for b in biases]
+        self.lr = np.float32(lr)
+        self.loss_mean = loss_mean
+        # storage rounding of every operand: through fp32 to bf16, or none at all (pure fp64, for the pins)
+        self.q = (lambda x: bf16(np.asarray(x, dtype=np.float32))) if rounding else (
+            lambda x: np.asarray(x, dtype=np.float64))
+
+    def step(self, pooled, dense, labels, update=True):
+        """One forward + backward (+ SGD update).  Returns (loss, d_pooled fp32 [B, P], grads) where grads is
+        the list of (dW, db) in fp64."""
+        q = self.q
+        B, P = pooled.shape
+        y = np.asarray(labels, dtype=np.float64).reshape(B)
+        h = [q(np.concatenate([pooled, dense], axis=1))]
+        L = len(self.W)
+        for l in range(L - 1):
+            a = h[-1] @ q(self.W[l]) + self.b[l].astype(np.float64)
+            h.append(q(np.maximum(a, 0.0)))
+        z = (h[-1] @ q(self.W[-1]) + self.b[-1].astype(np.float64)).reshape(B)
+        scale = 1.0 / B if self.loss_mean else 1.0
+        loss = scale * np.sum(np.logaddexp(0.0, z) - y * z)          # BCE with logits
+        dz = scale * (1.0 / (1.0 + np.exp(-z)) - y)                    # d loss / d z
+        grads = [None] * L
+        grads[L - 1] = (h[-1].T @ dz[:, None], np.array([dz.sum()]))
+        delta = q(dz[:, None] * q(self.W[-1]).T * (h[-1] > 0))   # [B, width of last hidden]
+        for l in range(L - 2, -1, -1):
+            grads[l] = (h[l].T @ delta, delta.sum(axis=0))
+            back = delta @ q(self.W[l]).T
+            if l > 0:
+                delta = q(back * (h[l] > 0))
+            else:
+                d_x = back                                             # the input has no ReLU in front of it
+        if update:
+            for l in range(L):
+                self.W[l] = (self.W[l].astype(np.float64) - float(self.lr) * grads[l][0]).astype(np.float32)
+                self.b[l] = (self.b[l].astype(np.float64) - float(self.lr) * grads[l][1]).astype(np.float32)
+        return loss, d_x[:, :P].astype(np.float32), grads
