@@ -168,6 +168,51 @@ int emb_codec_compress(const float* v, uint64_t n_blocks, uint32_t block_len, fl
 int emb_codec_decompress(const uint16_t* q, const float* norm, uint64_t n_blocks, uint32_t block_len, float kappa,
                          float* out, void* hip_stream);
 
+/* ---- optional dense step: the network NN_{w_nn} of section 2.1, trained as in Algorithm 2 --------------
+ * A feed-forward ReLU network with one logit: input [pooled | dense] of width widths[0] = pooled_width +
+ * dense_width, hidden widths widths[1..L-1], widths[L] = 1; loss = binary cross-entropy on the logit,
+ * averaged over the batch (loss_mean != 0) or summed as Algorithm 2 writes it (loss_mean == 0); Omega^nn =
+ * plain SGD with rate lr on fp32 master weights.  Every product takes bf16 operands (inputs, weights,
+ * stored activations and back-propagated deltas are rounded to bf16, nearest even) and accumulates in
+ * fp32 on the matrix cores.  widths[0..L-1] and the batch must be multiples of 64.
+ * mlp_create: weights[l] host fp32 [widths[l], widths[l+1]] row-major, biases[l] host fp32 [widths[l+1]];
+ *   copied; synchronous.
+ * mlp_step: one forward + backward + update (Algorithm 2) of a batch.  pooled: device fp32 [B, pooled_width]
+ *   (what emb_lookup_pool wrote), dense: device fp32 [B, dense_width], labels: device fp32 [B] in {0,1};
+ *   d_pooled: device fp32 [B, pooled_width], receives F'^emb, the gradient of the loss w.r.t. pooled, ready for
+ *   emb_backward_update; loss: device fp32 [1].  Enqueue-only on the given stream.
+ * mlp_read_weights: master weights and bias of a layer to the host (synchronous; either pointer may be NULL). */
+typedef struct mlp_ctx mlp_ctx;
+typedef struct {
+  uint32_t num_layers;      /* L >= 2 */
+  uint32_t pooled_width;
+  uint32_t dense_width;
+  uint32_t max_batch;
+  const uint32_t* widths;   /* host, [L + 1] */
+  float lr;
+  int32_t loss_mean;
+  int32_t device;
+  uint32_t reserved;        /* must be 0 */
+} mlp_config;
+int mlp_create(const mlp_config* cfg, const float* const* weights, const float* const* biases, mlp_ctx** out);
+int mlp_step(mlp_ctx* ctx, uint32_t batch, const float* pooled, const float* dense, const float* labels, float* d_pooled,
+             float* loss, void* hip_stream);
+int mlp_read_weights(mlp_ctx* ctx, uint32_t layer, float* w, float* b);
+/* Inspection of what the last mlp_step left behind (synchronous; for tests): what = 0 stored activation of
+ * `layer` (bf16 [B, widths[layer]]; layer 0 is the packed input), 1 back-propagated delta at the input of
+ * layer `layer` >= 1 (bf16 [B, widths[layer]]), 2 weight gradient (fp32 [widths[layer], widths[layer+1]]),
+ * 3 bias gradient (fp32 [widths[layer+1]]), 4 d loss / d logit (fp32 [B]).  `bytes` must be the exact size. */
+int mlp_read_state(mlp_ctx* ctx, int what, uint32_t layer, void* host, uint64_t bytes);
+int mlp_destroy(mlp_ctx* ctx);
+uint64_t mlp_device_bytes(mlp_ctx* ctx);
+/* The contraction the dense step is built from, on its own: C[M,N] = A[M,K] * Bt[N,K]^T with bf16 operands
+ * (device, row strides lda / ldb in elements, multiples of 8; K a multiple of 64) and fp32 accumulation.
+ * epilogue 0: C bf16 = relu(acc + bias[n]) (bias: device fp32 [N]); 1: C fp32 = acc; 2: C bf16 = acc where
+ * the bf16 matrix mask[M,N] (row stride ldm) is positive, else 0.  Enqueue-only. */
+int mlp_gemm_nt(int epilogue, const uint16_t* A, uint32_t lda, const uint16_t* Bt, uint32_t ldb, uint32_t M, uint32_t N,
+                uint32_t K, void* C, uint32_t ldc, const float* bias, const uint16_t* mask, uint32_t ldm, void* hip_stream);
+const char* mlp_last_error(mlp_ctx* ctx); /* ctx == NULL: the last failed mlp_create */
+
 /* Bytes of device memory the context holds (tables, state, workspace). */
 uint64_t emb_device_bytes(emb_ctx* ctx);
 

@@ -20,6 +20,36 @@ def bf16(x):
     return r.astype(np.uint32).view(np.float32).astype(np.float64).reshape(np.shape(x))
 
 
+# ---- the stages of one step, each from its own inputs (operands already in storage precision) ----
+def layer_forward(h_prev, W, b, q):
+    """Stored activation of the next layer: q(relu(h_prev W + b)); also returns the pre-activation."""
+    a = h_prev @ q(W) + np.asarray(b, dtype=np.float64)
+    return q(np.maximum(a, 0.0)), a
+
+
+def logit_loss(h_last, w_last, b_last, y, scale):
+    """Logit z = h_last w + b, loss = scale * sum BCE(z, y), dz = d loss / d z = scale * (sigmoid(z) - y)."""
+    z = (h_last @ w_last + np.asarray(b_last, dtype=np.float64)).reshape(-1)
+    loss = scale * np.sum(np.logaddexp(0.0, z) - y * z)
+    dz = scale * (0.5 * (1.0 + np.tanh(0.5 * z)) - y)
+    return z, loss, dz
+
+
+def delta_from_logit(dz, w_last, h_last, q):
+    """Delta at the input of the last layer: q(dz (x) w_last^T, kept where the stored activation is positive)."""
+    return q(dz[:, None] * w_last.reshape(1, -1) * (h_last > 0))
+
+
+def delta_back(delta, W, h_prev, q):
+    """Delta one layer down: q((delta W^T) kept where the stored activation h_prev is positive)."""
+    return q((delta @ q(W).T) * (h_prev > 0))
+
+
+def weight_grad(h_prev, delta):
+    """(dW, db) of the layer between h_prev and delta."""
+    return h_prev.T @ delta, delta.sum(axis=0)
+
+
 class MLP:
     def __init__(self, weights, biases, lr, loss_mean=True, rounding=True):
         """weights[l]: fp32 [in_l, out_l]; biases[l]: fp32 [out_l]; the last layer has out = 1."""
@@ -40,22 +70,18 @@ class MLP:
         h = [q(np.concatenate([pooled, dense], axis=1))]
         L = len(self.W)
         for l in range(L - 1):
-            a = h[-1] @ q(self.W[l]) + self.b[l].astype(np.float64)
-            h.append(q(np.maximum(a, 0.0)))
-        z = (h[-1] @ q(self.W[-1]) + self.b[-1].astype(np.float64)).reshape(B)
+            h.append(layer_forward(h[-1], self.W[l], self.b[l], q)[0])
         scale = 1.0 / B if self.loss_mean else 1.0
-        loss = scale * np.sum(np.logaddexp(0.0, z) - y * z)          # BCE with logits
-        dz = scale * (1.0 / (1.0 + np.exp(-z)) - y)                    # d loss / d z
+        _, loss, dz = logit_loss(h[-1], q(self.W[-1]), self.b[-1], y, scale)
         grads = [None] * L
         grads[L - 1] = (h[-1].T @ dz[:, None], np.array([dz.sum()]))
-        delta = q(dz[:, None] * q(self.W[-1]).T * (h[-1] > 0))   # [B, width of last hidden]
+        delta = delta_from_logit(dz, q(self.W[-1]), h[-1], q)      # [B, width of the last hidden layer]
         for l in range(L - 2, -1, -1):
-            grads[l] = (h[l].T @ delta, delta.sum(axis=0))
-            back = delta @ q(self.W[l]).T
+            grads[l] = weight_grad(h[l], delta)
             if l > 0:
-                delta = q(back * (h[l] > 0))
+                delta = delta_back(delta, self.W[l], h[l], q)
             else:
-                d_x = back                                             # the input has no ReLU in front of it
+                d_x = delta @ q(self.W[0]).T                        # the input has no ReLU in front of it
         if update:
             for l in range(L):
                 self.W[l] = (self.W[l].astype(np.float64) - float(self.lr) * grads[l][0]).astype(np.float32)

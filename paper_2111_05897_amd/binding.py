@@ -43,6 +43,12 @@ class emb_batch(C.Structure):
                 ("ids", C.c_void_p), ("offsets", C.c_void_p)]
 
 
+class mlp_config(C.Structure):
+    _fields_ = [("num_layers", C.c_uint32), ("pooled_width", C.c_uint32), ("dense_width", C.c_uint32),
+                ("max_batch", C.c_uint32), ("widths", C.POINTER(C.c_uint32)), ("lr", C.c_float),
+                ("loss_mean", C.c_int32), ("device", C.c_int32), ("reserved", C.c_uint32)]
+
+
 class EmbError(RuntimeError):
     def __init__(self, code: int, msg: str):
         super().__init__(f"{_STATUS.get(code, code)}: {msg}")
@@ -83,6 +89,18 @@ def load_library() -> C.CDLL:
     L.emb_codec_decompress.argtypes = [vp, vp, u64, u32, C.c_float, vp, vp]
     L.emb_codec_compress.restype = C.c_int
     L.emb_codec_decompress.restype = C.c_int
+    L.mlp_create.argtypes = [C.POINTER(mlp_config), vp, vp, C.POINTER(vp)]
+    L.mlp_step.argtypes = [vp, u32, vp, vp, vp, vp, vp, vp]
+    L.mlp_read_weights.argtypes = [vp, u32, vp, vp]
+    L.mlp_destroy.argtypes = [vp]
+    L.mlp_device_bytes.argtypes = [vp]
+    L.mlp_device_bytes.restype = u64
+    L.mlp_last_error.argtypes = [vp]
+    L.mlp_last_error.restype = C.c_char_p
+    L.mlp_gemm_nt.argtypes = [i32, vp, u32, vp, u32, u32, u32, u32, vp, u32, vp, vp, u32, vp]
+    L.mlp_read_state.argtypes = [vp, i32, u32, vp, u64]
+    for name in ("mlp_create", "mlp_step", "mlp_read_weights", "mlp_destroy", "mlp_gemm_nt", "mlp_read_state"):
+        getattr(L, name).restype = C.c_int
     L.emb_last_error.argtypes = [vp]
     L.emb_last_error.restype = C.c_char_p
     for name in ("emb_create", "emb_destroy", "emb_lookup_pool", "emb_hash_rows", "emb_backward_update",
@@ -252,3 +270,94 @@ def emb_codec_decompress(q: torch.Tensor, norm: torch.Tensor, kappa: float = 2.0
     if rc:
         raise EmbError(rc, L.emb_last_error(None).decode())
     return out
+
+
+class MlpContext:
+    """Owns one mlp_ctx (the optional dense step).  weights[l]: numpy fp32 [widths[l], widths[l+1]]."""
+
+    def __init__(self, widths, pooled_width, dense_width, max_batch, lr, weights, biases, loss_mean=True, device=0):
+        self.L = load_library()
+        self.widths = list(widths)
+        self.pooled_width, self.dense_width = pooled_width, dense_width
+        nl = len(widths) - 1
+        self._w = (C.c_uint32 * len(widths))(*widths)
+        ws = [np.ascontiguousarray(w, dtype=np.float32) for w in weights]
+        bs = [np.ascontiguousarray(b, dtype=np.float32) for b in biases]
+        assert len(ws) == nl and len(bs) == nl
+        for l in range(nl):
+            assert ws[l].shape == (widths[l], widths[l + 1]) and bs[l].shape == (widths[l + 1],)
+        wp = (C.c_void_p * nl)(*[w.ctypes.data for w in ws])
+        bp = (C.c_void_p * nl)(*[b.ctypes.data for b in bs])
+        cfg = mlp_config(nl, pooled_width, dense_width, max_batch, self._w, lr, 1 if loss_mean else 0, device, 0)
+        h = C.c_void_p()
+        rc = self.L.mlp_create(C.byref(cfg), wp, bp, C.byref(h))
+        if rc:
+            raise EmbError(rc, self.L.mlp_last_error(None).decode())
+        self.h = h
+
+    def _ck(self, rc):
+        if rc:
+            raise EmbError(rc, self.L.mlp_last_error(self.h).decode())
+
+    def mlp_step(self, pooled, dense, labels, d_pooled=None, stream=None):
+        B = pooled.shape[0]
+        assert pooled.is_contiguous() and pooled.dtype == torch.float32 and pooled.shape == (B, self.pooled_width)
+        assert dense.is_contiguous() and dense.dtype == torch.float32 and dense.shape == (B, self.dense_width)
+        assert labels.is_contiguous() and labels.dtype == torch.float32 and labels.shape == (B,)
+        if d_pooled is None:
+            d_pooled = torch.empty_like(pooled)
+        loss = torch.empty(1, dtype=torch.float32, device=pooled.device)
+        self._ck(self.L.mlp_step(self.h, B, pooled.data_ptr(), dense.data_ptr(), labels.data_ptr(), d_pooled.data_ptr(),
+                                 loss.data_ptr(), _stream_ptr(stream)))
+        return d_pooled, loss
+
+    def mlp_read_weights(self, layer):
+        w = np.empty((self.widths[layer], self.widths[layer + 1]), dtype=np.float32)
+        b = np.empty(self.widths[layer + 1], dtype=np.float32)
+        self._ck(self.L.mlp_read_weights(self.h, layer, w.ctypes.data, b.ctypes.data))
+        return w, b
+
+    def mlp_read_state(self, what, layer, batch):
+        """what: 'h' | 'delta' | 'dW' | 'db' | 'dz'.  bf16 states come back widened to fp32."""
+        kind = {"h": 0, "delta": 1, "dW": 2, "db": 3, "dz": 4}[what]
+        if kind <= 1:
+            raw = np.empty((batch, self.widths[layer]), dtype=np.uint16)
+        elif kind == 2:
+            raw = np.empty((self.widths[layer], self.widths[layer + 1]), dtype=np.float32)
+        elif kind == 3:
+            raw = np.empty(self.widths[layer + 1], dtype=np.float32)
+        else:
+            raw = np.empty(batch, dtype=np.float32)
+        self._ck(self.L.mlp_read_state(self.h, kind, layer, raw.ctypes.data, raw.nbytes))
+        if kind <= 1:
+            return (raw.astype(np.uint32) << 16).view(np.float32)
+        return raw
+
+    def mlp_device_bytes(self):
+        return int(self.L.mlp_device_bytes(self.h))
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.L.mlp_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def mlp_gemm_nt(epilogue, A, Bt, bias=None, mask=None, stream=None):
+    """C = A @ Bt.T for bf16 device tensors A [M, K], Bt [N, K]; see include/persia_emb.h for the epilogues."""
+    L = load_library()
+    assert A.dtype == torch.bfloat16 and Bt.dtype == torch.bfloat16 and A.is_contiguous() and Bt.is_contiguous()
+    M, K = A.shape
+    N = Bt.shape[0]
+    Cm = torch.empty((M, N), dtype=torch.float32 if epilogue == 1 else torch.bfloat16, device=A.device)
+    rc = L.mlp_gemm_nt(epilogue, A.data_ptr(), K, Bt.data_ptr(), K, M, N, K, Cm.data_ptr(), N,
+                       bias.data_ptr() if bias is not None else None, mask.data_ptr() if mask is not None else None,
+                       N, _stream_ptr(stream))
+    if rc:
+        raise EmbError(rc, L.mlp_last_error(None).decode())
+    return Cm

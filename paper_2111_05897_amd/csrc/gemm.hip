@@ -1,0 +1,201 @@
+// Dense contractions of the MLP step on the matrix cores: C[M,N] = A[M,K] * Bt[N,K]^T with bf16
+// operands (both K-contiguous) and fp32 accumulation, plus the bf16 transpose that brings every
+// operand of the step into that form.
+//
+// k_gemm_nt: a 256-thread workgroup computes a 128x128 tile of C; its 4 waves sit 2x2 and own 64x64
+// each, i.e. 2x2 MFMA tiles of v_mfma_f32_32x32x16_bf16 (lane l feeds row/column l%32 with the 8
+// consecutive k values starting at 8*(l/32)).  K is walked in steps of 64: the next A and Bt tiles are
+// fetched from global memory into registers while the current ones, staged in LDS (rows padded by 16
+// bytes against bank conflicts), feed the MFMAs.  Workgroups are numbered so that the ones running
+// together on an XCD cover a compact block of tiles and share their A and Bt strips in that XCD's L2.
+#include "device_utils.h"
+#include "launch.h"
+
+namespace pemb {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 128, BN = 128, BK = 64;
+constexpr int LDS_STRIDE = BK + 8;  // bf16 elements per staged row
+constexpr uint32_t kXcds = 8;
+constexpr uint32_t kGroupM = 8;     // m-tiles per raster group
+
+struct GemmArgs {
+  const bf16_t* A;   // [M, K], row stride lda
+  const bf16_t* Bt;  // [N, K], row stride ldb
+  uint32_t M, N, K, lda, ldb;
+  void* C;           // [M, N], row stride ldc (fp32 or bf16 by epilogue)
+  uint32_t ldc;
+  const float* bias;     // [N]            (EPI_BIAS_RELU_BF16)
+  const bf16_t* mask;    // [M, N], ldm    (EPI_MASK_BF16: keep where mask > 0)
+  uint32_t ldm;
+};
+
+__device__ __forceinline__ uint4 load16_or_zero(const bf16_t* p, bool ok) {
+  return ok ? *reinterpret_cast<const uint4*>(p) : make_uint4(0u, 0u, 0u, 0u);
+}
+
+template <int EPI>
+__global__ __launch_bounds__(kBlock) void k_gemm_nt(GemmArgs g) {
+  __shared__ __attribute__((aligned(16))) bf16_t As[BM * LDS_STRIDE];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[BN * LDS_STRIDE];
+  const uint32_t tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+  const uint32_t total = tiles_m * tiles_n;
+  // XCD-aware numbering: workgroup b runs on XCD b % 8; give each XCD a contiguous stretch of the tile order
+  const uint32_t per_xcd = (gridDim.x + kXcds - 1) / kXcds;
+  const uint32_t lid = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+  if (lid >= total) return;
+  // grouped raster: kGroupM m-tiles at a time, n fastest inside a group column
+  const uint32_t group_sz = kGroupM * tiles_n;
+  const uint32_t gidx = lid / group_sz;
+  const uint32_t first_m = gidx * kGroupM;
+  const uint32_t rows_in_group = (tiles_m - first_m < kGroupM) ? tiles_m - first_m : kGroupM;
+  const uint32_t in_group = lid - gidx * group_sz;
+  const uint32_t tile_m = first_m + in_group % rows_in_group;
+  const uint32_t tile_n = in_group / rows_in_group;
+  const uint32_t m0 = tile_m * BM, n0 = tile_n * BN;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  // global -> LDS mapping: 4 passes of 32 rows, 8 threads of 16 bytes per row
+  const int lrow = tid >> 3, lcol = (tid & 7) * 8;
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  uint4 ra[4], rb[4];
+  auto fetch = [&](uint32_t k0) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const uint32_t r = p * 32 + lrow;
+      ra[p] = load16_or_zero(g.A + (size_t)(m0 + r) * g.lda + k0 + lcol, m0 + r < g.M);
+      rb[p] = load16_or_zero(g.Bt + (size_t)(n0 + r) * g.ldb + k0 + lcol, n0 + r < g.N);
+    }
+  };
+  auto stage = [&]() {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const int r = p * 32 + lrow;
+      *reinterpret_cast<uint4*>(&As[r * LDS_STRIDE + lcol]) = ra[p];
+      *reinterpret_cast<uint4*>(&Bs[r * LDS_STRIDE + lcol]) = rb[p];
+    }
+  };
+
+  fetch(0);
+  for (uint32_t k0 = 0; k0 < g.K; k0 += BK) {
+    __syncthreads();  // everyone is done reading the previous tiles
+    stage();
+    __syncthreads();
+    if (k0 + BK < g.K) fetch(k0 + BK);  // in flight during the MFMAs below
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 16) {
+      bf16x8 af[2], bfr[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        af[i] = *reinterpret_cast<const bf16x8*>(&As[(wm * 64 + i * 32 + (lane & 31)) * LDS_STRIDE + kk + (lane >> 5) * 8]);
+        bfr[i] = *reinterpret_cast<const bf16x8*>(&Bs[(wn * 64 + i * 32 + (lane & 31)) * LDS_STRIDE + kk + (lane >> 5) * 8]);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+  }
+
+  // epilogue: accumulator element e of lane l is C[8*(e/4) + 4*(l/32) + e%4][l%32] of its 32x32 tile
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const uint32_t col = n0 + wn * 64 + j * 32 + (lane & 31);
+      if (col >= g.N) continue;
+      float bias = 0.f;
+      if constexpr (EPI == 0) bias = g.bias[col];
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const uint32_t row = m0 + wm * 64 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+        if (row >= g.M) continue;
+        float v = acc[i][j][e];
+        if constexpr (EPI == 0) {  // bias + ReLU -> bf16
+          v = fmaxf(v + bias, 0.f);
+          reinterpret_cast<bf16_t*>(g.C)[(size_t)row * g.ldc + col] = (bf16_t)f32_to_bf16(v);
+        } else if constexpr (EPI == 1) {  // fp32
+          reinterpret_cast<float*>(g.C)[(size_t)row * g.ldc + col] = v;
+        } else {  // keep where the stored activation is positive -> bf16
+          const bool on = (g.mask[(size_t)row * g.ldm + col] & 0x7FFFu) != 0 && !(g.mask[(size_t)row * g.ldm + col] & 0x8000u);
+          reinterpret_cast<bf16_t*>(g.C)[(size_t)row * g.ldc + col] = (bf16_t)f32_to_bf16(on ? v : 0.f);
+        }
+      }
+    }
+}
+
+// out[c][r] = in[r][c] for bf16 matrices, 64x64 tiles through LDS.
+__global__ __launch_bounds__(kBlock) void k_transpose_bf16(const bf16_t* __restrict__ in, uint32_t R, uint32_t Cc,
+                                                           uint32_t ld_in, bf16_t* __restrict__ out, uint32_t ld_out) {
+  __shared__ bf16_t t[64][66];
+  const uint32_t r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  for (int i = threadIdx.x; i < 64 * 64; i += kBlock) {
+    const uint32_t r = i / 64, c = i % 64;
+    t[r][c] = (r0 + r < R && c0 + c < Cc) ? in[(size_t)(r0 + r) * ld_in + c0 + c] : (bf16_t)0;
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < 64 * 64; i += kBlock) {
+    const uint32_t c = i / 64, r = i % 64;
+    if (r0 + r < R && c0 + c < Cc) out[(size_t)(c0 + c) * ld_out + r0 + r] = t[r][c];
+  }
+}
+
+template <int EPI>
+hipError_t launch_epi(const GemmArgs& g, hipStream_t stream) {
+  const uint32_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+  const uint32_t grid = (tiles + kXcds - 1) / kXcds * kXcds;
+  hipLaunchKernelGGL(k_gemm_nt<EPI>, dim3(grid), dim3(kBlock), 0, stream, g);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_gemm_nt(int epilogue, const void* A, uint32_t lda, const void* Bt, uint32_t ldb, uint32_t M, uint32_t N,
+                          uint32_t K, void* C, uint32_t ldc, const float* bias, const void* mask, uint32_t ldm,
+                          hipStream_t stream) {
+  if (M == 0 || N == 0) return hipSuccess;
+  if (K == 0 || K % BK != 0 || lda % 8 != 0 || ldb % 8 != 0) return hipErrorInvalidValue;  // 16-byte operand loads
+  if (!A || !Bt || !C || (epilogue == 0 && !bias) || (epilogue == 2 && !mask)) return hipErrorInvalidValue;
+  GemmArgs g;
+  g.A = reinterpret_cast<const bf16_t*>(A);
+  g.Bt = reinterpret_cast<const bf16_t*>(Bt);
+  g.M = M;
+  g.N = N;
+  g.K = K;
+  g.lda = lda;
+  g.ldb = ldb;
+  g.C = C;
+  g.ldc = ldc;
+  g.bias = bias;
+  g.mask = reinterpret_cast<const bf16_t*>(mask);
+  g.ldm = ldm;
+  switch (epilogue) {
+    case 0: return launch_epi<0>(g, stream);
+    case 1: return launch_epi<1>(g, stream);
+    case 2: return launch_epi<2>(g, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_transpose_bf16(const void* in, uint32_t R, uint32_t Cc, uint32_t ld_in, void* out, uint32_t ld_out,
+                                 hipStream_t stream) {
+  if (R == 0 || Cc == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_transpose_bf16, dim3((Cc + 63) / 64, (R + 63) / 64), dim3(kBlock), 0, stream,
+                     reinterpret_cast<const bf16_t*>(in), R, Cc, ld_in, reinterpret_cast<bf16_t*>(out), ld_out);
+  return hipGetLastError();
+}
+
+}  // namespace pemb

@@ -108,6 +108,16 @@ hipError_t launch_tile_reduce_update(const TableView& t, const BackwardArgs& a, 
 hipError_t launch_classify_multi(const BackwardArgs& a, uint32_t* counters, uint32_t* long_list, hipStream_t stream);
 hipError_t launch_fixup(const TableView& t, const BackwardArgs& a, hipStream_t stream);
 
+// ---- gemm.hip ----
+// C[M,N] = A[M,K] * Bt[N,K]^T, bf16 operands (row strides lda, ldb, multiples of 8), fp32 accumulation, K a
+// multiple of 64.  epilogue 0: C bf16 = relu(acc + bias[n]); 1: C fp32 = acc; 2: C bf16 = acc where the bf16
+// matrix `mask` (row stride ldm) is positive, else 0.
+hipError_t launch_gemm_nt(int epilogue, const void* A, uint32_t lda, const void* Bt, uint32_t ldb, uint32_t M, uint32_t N,
+                          uint32_t K, void* C, uint32_t ldc, const float* bias, const void* mask, uint32_t ldm,
+                          hipStream_t stream);
+hipError_t launch_transpose_bf16(const void* in, uint32_t R, uint32_t Cc, uint32_t ld_in, void* out, uint32_t ld_out,
+                                 hipStream_t stream);
+
 // ---- codec.hip ----
 hipError_t launch_codec_compress(const float* v, uint64_t n_blocks, uint32_t block_len, float kappa, void* q_fp16,
                                  float* norm, hipStream_t stream);
