@@ -79,6 +79,84 @@ def bench_codec(args, w, binding, torch, np) -> int:
     return 0
 
 
+def bench_hybrid(args, w, binding, torch, np, W) -> int:
+    """emb_lookup_pool -> mlp_step -> emb_backward_update(d_pooled from the MLP), one stream, synchronous."""
+    cfg = w.cfg
+    P = cfg.pooled_width
+    widths = [P + W.DENSE_FEATURES] + W.MLP_HIDDEN + [1]
+    nb = max(1, min(args.distinct_batches, args.steps, 2))
+    host_batches = [W.make_batch(w, s) for s in range(nb)]
+    batches = [binding.DeviceBatch(b.batch_size, b.ids, b.offsets) for b in host_batches]
+    feats = []
+    for s in range(nb):
+        d, y = W.make_dense_and_labels(w.seed, s, w.batch)
+        feats.append((torch.from_numpy(d).cuda(), torch.from_numpy(y).cuda()))
+    Ws, bs = W.make_mlp_params(widths, w.seed)
+    ctx = binding.EmbContext.from_config(cfg, max_batch=w.batch, max_ids=max(b.num_ids for b in batches))
+    mlp = binding.MlpContext(widths, P, W.DENSE_FEATURES, w.batch, 1e-3, Ws, bs, loss_mean=True)
+    pooled = torch.empty((w.batch, P), dtype=torch.float32, device="cuda")
+    d_pooled = torch.empty_like(pooled)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    t_emb_f = t_mlp = t_emb_b = 0.0
+    ids_done = 0
+    torch.cuda.synchronize()
+
+    def step(i, timed):
+        nonlocal t_emb_f, t_mlp, t_emb_b
+        b = batches[i % nb]
+        d, y = feats[i % nb]
+        ev[0].record()
+        ctx.emb_lookup_pool(b, pooled)
+        ev[1].record()
+        _, loss = mlp.mlp_step(pooled, d, y, d_pooled)
+        ev[2].record()
+        ctx.emb_backward_update(b, d_pooled)
+        ev[3].record()
+        if timed:
+            torch.cuda.synchronize()
+            t_emb_f += ev[0].elapsed_time(ev[1]); t_mlp += ev[1].elapsed_time(ev[2]); t_emb_b += ev[2].elapsed_time(ev[3])
+        return b.num_ids, loss
+
+    for i in range(args.warmup):
+        step(i, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        n, loss = step(args.warmup + i, False)
+        ids_done += n
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    for i in range(args.steps):
+        step(args.warmup + i, True)
+    B = w.batch
+    hidden = widths[1:-1]
+    flops = 0.0
+    prev = widths[0]
+    for j, hsz in enumerate(hidden):
+        flops += 2.0 * B * prev * hsz            # forward
+        flops += 2.0 * B * prev * hsz            # weight gradient
+        flops += 2.0 * B * (P if j == 0 else prev) * hsz   # input gradient (first layer: pooled columns only)
+        prev = hsz
+    flops += 3 * 2.0 * B * prev                  # the logit layer
+    mlp_ms = t_mlp / args.steps
+    tflops = flops / (mlp_ms * 1e-3) / 1e12
+    out = {
+        "metric": "embedding IDs/sec (lookup + dense MLP step + bwd + update), 1 GPU", "value": round(ids_done / elapsed, 1),
+        "unit": "IDs/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(elapsed * 1e3 / args.steps, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name + "_hybrid", "batch": B, "slots": cfg.num_slots, "mlp_widths": widths,
+                   "ids_per_step": round(ids_done / args.steps), "last_loss": round(float(loss.item()), 5)},
+        "part_ms_per_step": {"emb_lookup_pool": round(t_emb_f / args.steps, 4), "mlp_step": round(mlp_ms, 4),
+                             "emb_backward_update": round(t_emb_b / args.steps, 4)},
+        "roofline": {"bound": "mfma", "kernel": "mlp_step (all bf16 contractions, transposes and epilogues)",
+                     "achieved": round(tflops, 1), "peak": 2500.0, "unit": "TFLOP/s", "frac": round(tflops / 2500.0, 4),
+                     "traffic": None, "flop_per_step": flops},
+    }
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -90,6 +168,8 @@ def main() -> int:
                     help="staleness-1 schedule: lookup(t+1) on a second stream while update(t) runs on the first")
     ap.add_argument("--codec", action="store_true",
                     help="instead of the training step, time the scaled-fp16 value codec on this config's pooled shape")
+    ap.add_argument("--hybrid", action="store_true",
+                    help="full hybrid step: lookup -> dense MLP step (bf16 MFMA) -> embedding update with the MLP's gradient")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device-to-device copies (reference for rocprofv3 byte counters)")
@@ -109,6 +189,8 @@ def main() -> int:
     cfg = w.cfg
     if args.codec:
         return bench_codec(args, w, binding, torch, np)
+    if args.hybrid:
+        return bench_hybrid(args, w, binding, torch, np, W)
     T = len(cfg.tables)
     e_of = [2 if t.dtype == W.BF16 else 4 for t in cfg.tables]
     slot_table = np.array([s.table for s in cfg.slots])

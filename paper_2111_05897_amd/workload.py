@@ -276,3 +276,26 @@ def random_batch(seed: int, batch: int, num_slots: int, max_len: int, id_space: 
     n = int(offsets[-1])
     ids = np.floor(counter_uniform(seed, _TAG_ID, 0, 0, n) * id_space).astype(np.uint64)
     return Batch(batch, ids, offsets.astype(np.int32))
+
+
+# --------------------------------------------------------------------------- dense side (config 3)
+MLP_HIDDEN = [4096, 2048, 1024]
+DENSE_FEATURES = 512
+
+
+def make_mlp_params(widths, seed):
+    """Initial weights N(0, 2/fan_in) and zero biases for a ReLU net with layer widths `widths` (inputs to the
+    dense step, drawn here so that the GPU library and the oracle receive the same arrays)."""
+    rng = np.random.Generator(np.random.Philox(key=[seed % (1 << 64), 0xD15E]))
+    Ws = [(rng.standard_normal((i, o), dtype=np.float32) * np.float32(np.sqrt(2.0 / i))) for i, o in
+          zip(widths[:-1], widths[1:])]
+    bs = [np.zeros(o, dtype=np.float32) for o in widths[1:]]
+    return Ws, bs
+
+
+def make_dense_and_labels(seed, step, batch, dense_width=DENSE_FEATURES, positive_rate=0.05):
+    """Non-ID features N(0,1) fp32 [B, dense_width] and labels Bernoulli(positive_rate) fp32 [B]."""
+    rng = np.random.Generator(np.random.Philox(key=[seed % (1 << 64), 0xDE45E000 + step]))
+    dense = rng.standard_normal((batch, dense_width), dtype=np.float32)
+    labels = (rng.random(batch) < positive_rate).astype(np.float32)
+    return dense, labels
