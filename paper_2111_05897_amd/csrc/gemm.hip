@@ -2,8 +2,8 @@
 // operands (both K-contiguous) and fp32 accumulation, plus the bf16 transpose that brings every
 // operand of the step into that form.
 //
-// k_gemm_nt: a 256-thread workgroup computes a 128x128 tile of C; its 4 waves sit 2x2 and own 64x64
-// each, i.e. 2x2 MFMA tiles of v_mfma_f32_32x32x16_bf16 (lane l feeds row/column l%32 with the 8
+// k_gemm_nt: a 256-thread workgroup computes a 256x128 tile of C; its 4 waves sit 2x2 and own 128x64
+// each, i.e. 4x2 MFMA tiles of v_mfma_f32_32x32x16_bf16 (lane l feeds row/column l%32 with the 8
 // consecutive k values starting at 8*(l/32)).  K is walked in steps of 64: the next A and Bt tiles are
 // fetched from global memory into registers while the current ones, staged in LDS (rows padded by 16
 // bytes against bank conflicts), feed the MFMAs.  Workgroups are numbered so that the ones running
@@ -17,7 +17,11 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int BM = 128, BN = 128, BK = 64;
+constexpr int BK = 64;
+// Tiles of 32x32 per wave along M and N.  A wave tile of (32*WM)x(32*WN) reads (WM+WN) operand fragments
+// from LDS for WM*WN MFMAs, so larger wave tiles take LDS off the critical path: 4x2 measured faster than 2x2.
+constexpr int WM = 4, WN = 2;
+constexpr int BM = 2 * 32 * WM, BN = 2 * 32 * WN;
 constexpr int LDS_STRIDE = BK + 8;  // bf16 elements per staged row
 constexpr uint32_t kXcds = 8;
 constexpr uint32_t kGroupM = 8;     // m-tiles per raster group
@@ -38,7 +42,7 @@ __device__ __forceinline__ uint4 load16_or_zero(const bf16_t* p, bool ok) {
 }
 
 template <int EPI>
-__global__ __launch_bounds__(kBlock) void k_gemm_nt(GemmArgs g) {
+__global__ __launch_bounds__(kBlock, 2) void k_gemm_nt(GemmArgs g) {
   __shared__ __attribute__((aligned(16))) bf16_t As[BM * LDS_STRIDE];
   __shared__ __attribute__((aligned(16))) bf16_t Bs[BN * LDS_STRIDE];
   const uint32_t tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
@@ -62,30 +66,33 @@ __global__ __launch_bounds__(kBlock) void k_gemm_nt(GemmArgs g) {
   // global -> LDS mapping: 4 passes of 32 rows, 8 threads of 16 bytes per row
   const int lrow = tid >> 3, lcol = (tid & 7) * 8;
 
-  floatx16 acc[2][2];
+  floatx16 acc[WM][WN];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < WM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < WN; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  uint4 ra[4], rb[4];
+  constexpr int PA = BM / 32, PB = BN / 32;  // passes of 32 rows that bring a tile in
+  uint4 ra[PA], rb[PB];
   auto fetch = [&](uint32_t k0) {
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
+    for (int p = 0; p < PA; ++p) {
       const uint32_t r = p * 32 + lrow;
       ra[p] = load16_or_zero(g.A + (size_t)(m0 + r) * g.lda + k0 + lcol, m0 + r < g.M);
+    }
+#pragma unroll
+    for (int p = 0; p < PB; ++p) {
+      const uint32_t r = p * 32 + lrow;
       rb[p] = load16_or_zero(g.Bt + (size_t)(n0 + r) * g.ldb + k0 + lcol, n0 + r < g.N);
     }
   };
   auto stage = [&]() {
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const int r = p * 32 + lrow;
-      *reinterpret_cast<uint4*>(&As[r * LDS_STRIDE + lcol]) = ra[p];
-      *reinterpret_cast<uint4*>(&Bs[r * LDS_STRIDE + lcol]) = rb[p];
-    }
+    for (int p = 0; p < PA; ++p) *reinterpret_cast<uint4*>(&As[(p * 32 + lrow) * LDS_STRIDE + lcol]) = ra[p];
+#pragma unroll
+    for (int p = 0; p < PB; ++p) *reinterpret_cast<uint4*>(&Bs[(p * 32 + lrow) * LDS_STRIDE + lcol]) = rb[p];
   };
 
   fetch(0);
@@ -96,32 +103,33 @@ __global__ __launch_bounds__(kBlock) void k_gemm_nt(GemmArgs g) {
     if (k0 + BK < g.K) fetch(k0 + BK);  // in flight during the MFMAs below
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 16) {
-      bf16x8 af[2], bfr[2];
+      bf16x8 af[WM], bfr[WN];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        af[i] = *reinterpret_cast<const bf16x8*>(&As[(wm * 64 + i * 32 + (lane & 31)) * LDS_STRIDE + kk + (lane >> 5) * 8]);
-        bfr[i] = *reinterpret_cast<const bf16x8*>(&Bs[(wn * 64 + i * 32 + (lane & 31)) * LDS_STRIDE + kk + (lane >> 5) * 8]);
-      }
+      for (int i = 0; i < WM; ++i)
+        af[i] = *reinterpret_cast<const bf16x8*>(&As[(wm * 32 * WM + i * 32 + (lane & 31)) * LDS_STRIDE + kk + (lane >> 5) * 8]);
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int j = 0; j < WN; ++j)
+        bfr[j] = *reinterpret_cast<const bf16x8*>(&Bs[(wn * 32 * WN + j * 32 + (lane & 31)) * LDS_STRIDE + kk + (lane >> 5) * 8]);
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+      for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
   }
 
   // epilogue: accumulator element e of lane l is C[8*(e/4) + 4*(l/32) + e%4][l%32] of its 32x32 tile
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < WM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const uint32_t col = n0 + wn * 64 + j * 32 + (lane & 31);
+    for (int j = 0; j < WN; ++j) {
+      const uint32_t col = n0 + wn * 32 * WN + j * 32 + (lane & 31);
       if (col >= g.N) continue;
       float bias = 0.f;
       if constexpr (EPI == 0) bias = g.bias[col];
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const uint32_t row = m0 + wm * 64 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+        const uint32_t row = m0 + wm * 32 * WM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
         if (row >= g.M) continue;
         float v = acc[i][j][e];
         if constexpr (EPI == 0) {  // bias + ReLU -> bf16
