@@ -2,12 +2,11 @@
 // operands (both K-contiguous) and fp32 accumulation, plus the bf16 transpose that brings every
 // operand of the step into that form.
 //
-// k_gemm_nt: a 256-thread workgroup computes a 256x128 tile of C; its 4 waves sit 2x2 and own 128x64
+// k_gemm_nt: a 512-thread workgroup computes a 256x256 tile of C; its 8 waves sit 2x4 and own 128x64
 // each, i.e. 4x2 MFMA tiles of v_mfma_f32_32x32x16_bf16 (lane l feeds row/column l%32 with the 8
-// consecutive k values starting at 8*(l/32)).  K is walked in steps of 64: the next A and Bt tiles are
-// fetched from global memory into registers while the current ones, staged in LDS (rows padded by 16
-// bytes against bank conflicts), feed the MFMAs.  Workgroups are numbered so that the ones running
-// together on an XCD cover a compact block of tiles and share their A and Bt strips in that XCD's L2.
+// consecutive k values starting at 8*(l/32)).  K is walked in steps of 64 through two LDS stages (rows
+// padded by 16 bytes against bank conflicts).  Workgroups are numbered so that the ones running together on an XCD cover a
+// compact block of tiles and share their A and Bt strips in that XCD's L2.
 #include "device_utils.h"
 #include "launch.h"
 
@@ -18,11 +17,13 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int BK = 64;
-// Tiles of 32x32 per wave along M and N.  A wave tile of (32*WM)x(32*WN) reads (WM+WN) operand fragments
-// from LDS for WM*WN MFMAs, so larger wave tiles take LDS off the critical path: 4x2 measured faster than 2x2.
+// 512-thread workgroups: 8 waves sit 2 (M) x 4 (N); a wave owns WM x WN MFMA tiles of 32x32.
+constexpr int kGemmThreads = 512;
 constexpr int WM = 4, WN = 2;
-constexpr int BM = 2 * 32 * WM, BN = 2 * 32 * WN;
-constexpr int LDS_STRIDE = BK + 8;  // bf16 elements per staged row
+constexpr int BM = 2 * 32 * WM, BN = 4 * 32 * WN;  // 256 x 256
+constexpr int LDS_STRIDE = BK + 8;                  // bf16 elements per staged row (16 bytes of padding)
+constexpr int kStageElems = (BM + BN) * LDS_STRIDE; // one LDS stage: A tile then Bt tile
+constexpr size_t kGemmLdsBytes = 2 * (size_t)kStageElems * sizeof(bf16_t);  // two stages
 constexpr uint32_t kXcds = 8;
 constexpr uint32_t kGroupM = 8;     // m-tiles per raster group
 
@@ -32,8 +33,8 @@ struct GemmArgs {
   uint32_t M, N, K, lda, ldb;
   void* C;           // [M, N], row stride ldc (fp32 or bf16 by epilogue)
   uint32_t ldc;
-  const float* bias;     // [N]            (EPI_BIAS_RELU_BF16)
-  const bf16_t* mask;    // [M, N], ldm    (EPI_MASK_BF16: keep where mask > 0)
+  const float* bias;     // [N]            (epilogue 0)
+  const bf16_t* mask;    // [M, N], ldm    (epilogue 2: keep where mask > 0)
   uint32_t ldm;
 };
 
@@ -41,10 +42,12 @@ __device__ __forceinline__ uint4 load16_or_zero(const bf16_t* p, bool ok) {
   return ok ? *reinterpret_cast<const uint4*>(p) : make_uint4(0u, 0u, 0u, 0u);
 }
 
+// Software pipeline over the K tiles: tile i is multiplied out of LDS stage i%2 while tile i+1 travels from
+// global memory into registers; it is written to the other stage at the end of the iteration, so there is
+// one barrier per iteration.
 template <int EPI>
-__global__ __launch_bounds__(kBlock, 2) void k_gemm_nt(GemmArgs g) {
-  __shared__ __attribute__((aligned(16))) bf16_t As[BM * LDS_STRIDE];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[BN * LDS_STRIDE];
+__global__ __launch_bounds__(kGemmThreads, 2) void k_gemm_nt(GemmArgs g) {
+  extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
   const uint32_t tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   const uint32_t total = tiles_m * tiles_n;
   // XCD-aware numbering: workgroup b runs on XCD b % 8; give each XCD a contiguous stretch of the tile order
@@ -62,9 +65,10 @@ __global__ __launch_bounds__(kBlock, 2) void k_gemm_nt(GemmArgs g) {
   const uint32_t m0 = tile_m * BM, n0 = tile_n * BN;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  // global -> LDS mapping: 4 passes of 32 rows, 8 threads of 16 bytes per row
+  const int wm = wave >> 2, wn = wave & 3;
+  // global -> LDS mapping: passes of 64 rows, 8 threads of 16 bytes per row
   const int lrow = tid >> 3, lcol = (tid & 7) * 8;
+  constexpr int PA = BM / 64, PB = BN / 64;
 
   floatx16 acc[WM][WN];
 #pragma unroll
@@ -74,33 +78,30 @@ __global__ __launch_bounds__(kBlock, 2) void k_gemm_nt(GemmArgs g) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  constexpr int PA = BM / 32, PB = BN / 32;  // passes of 32 rows that bring a tile in
   uint4 ra[PA], rb[PB];
-  auto fetch = [&](uint32_t k0) {
+  auto fetch = [&](uint32_t k0, uint4 (&a)[PA], uint4 (&b)[PB]) {
 #pragma unroll
     for (int p = 0; p < PA; ++p) {
-      const uint32_t r = p * 32 + lrow;
-      ra[p] = load16_or_zero(g.A + (size_t)(m0 + r) * g.lda + k0 + lcol, m0 + r < g.M);
+      const uint32_t r = p * 64 + lrow;
+      a[p] = load16_or_zero(g.A + (size_t)(m0 + r) * g.lda + k0 + lcol, m0 + r < g.M);
     }
 #pragma unroll
     for (int p = 0; p < PB; ++p) {
-      const uint32_t r = p * 32 + lrow;
-      rb[p] = load16_or_zero(g.Bt + (size_t)(n0 + r) * g.ldb + k0 + lcol, n0 + r < g.N);
+      const uint32_t r = p * 64 + lrow;
+      b[p] = load16_or_zero(g.Bt + (size_t)(n0 + r) * g.ldb + k0 + lcol, n0 + r < g.N);
     }
   };
-  auto stage = [&]() {
+  auto stage = [&](int s, const uint4 (&a)[PA], const uint4 (&b)[PB]) {
+    bf16_t* As = lds + s * kStageElems;
+    bf16_t* Bs = As + BM * LDS_STRIDE;
 #pragma unroll
-    for (int p = 0; p < PA; ++p) *reinterpret_cast<uint4*>(&As[(p * 32 + lrow) * LDS_STRIDE + lcol]) = ra[p];
+    for (int p = 0; p < PA; ++p) *reinterpret_cast<uint4*>(&As[(p * 64 + lrow) * LDS_STRIDE + lcol]) = a[p];
 #pragma unroll
-    for (int p = 0; p < PB; ++p) *reinterpret_cast<uint4*>(&Bs[(p * 32 + lrow) * LDS_STRIDE + lcol]) = rb[p];
+    for (int p = 0; p < PB; ++p) *reinterpret_cast<uint4*>(&Bs[(p * 64 + lrow) * LDS_STRIDE + lcol]) = b[p];
   };
-
-  fetch(0);
-  for (uint32_t k0 = 0; k0 < g.K; k0 += BK) {
-    __syncthreads();  // everyone is done reading the previous tiles
-    stage();
-    __syncthreads();
-    if (k0 + BK < g.K) fetch(k0 + BK);  // in flight during the MFMAs below
+  auto compute = [&](int s) {
+    const bf16_t* As = lds + s * kStageElems;
+    const bf16_t* Bs = As + BM * LDS_STRIDE;
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 16) {
       bf16x8 af[WM], bfr[WN];
@@ -116,6 +117,19 @@ __global__ __launch_bounds__(kBlock, 2) void k_gemm_nt(GemmArgs g) {
         for (int j = 0; j < WN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
+  };
+
+  const uint32_t nk = g.K / BK;
+  fetch(0, ra, rb);
+  stage(0, ra, rb);
+  __syncthreads();
+  for (uint32_t i = 0; i < nk; ++i) {
+    const int cur = i & 1;
+    if (i + 1 < nk) fetch((i + 1) * BK, ra, rb);
+    compute(cur);
+    // the other stage was last read in iteration i-1, which every wave has left (barrier below)
+    if (i + 1 < nk) stage(cur ^ 1, ra, rb);
+    __syncthreads();
   }
 
   // epilogue: accumulator element e of lane l is C[8*(e/4) + 4*(l/32) + e%4][l%32] of its 32x32 tile
@@ -138,7 +152,8 @@ __global__ __launch_bounds__(kBlock, 2) void k_gemm_nt(GemmArgs g) {
         } else if constexpr (EPI == 1) {  // fp32
           reinterpret_cast<float*>(g.C)[(size_t)row * g.ldc + col] = v;
         } else {  // keep where the stored activation is positive -> bf16
-          const bool on = (g.mask[(size_t)row * g.ldm + col] & 0x7FFFu) != 0 && !(g.mask[(size_t)row * g.ldm + col] & 0x8000u);
+          const bf16_t mv = g.mask[(size_t)row * g.ldm + col];
+          const bool on = (mv & 0x7FFFu) != 0 && !(mv & 0x8000u);
           reinterpret_cast<bf16_t*>(g.C)[(size_t)row * g.ldc + col] = (bf16_t)f32_to_bf16(on ? v : 0.f);
         }
       }
@@ -163,9 +178,13 @@ __global__ __launch_bounds__(kBlock) void k_transpose_bf16(const bf16_t* __restr
 
 template <int EPI>
 hipError_t launch_epi(const GemmArgs& g, hipStream_t stream) {
+  // the two LDS stages need more than the 64 KB a kernel gets by default
+  static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_nt<EPI>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLdsBytes);
+  if (attr != hipSuccess) return attr;
   const uint32_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   const uint32_t grid = (tiles + kXcds - 1) / kXcds * kXcds;
-  hipLaunchKernelGGL(k_gemm_nt<EPI>, dim3(grid), dim3(kBlock), 0, stream, g);
+  hipLaunchKernelGGL(k_gemm_nt<EPI>, dim3(grid), dim3(kGemmThreads), kGemmLdsBytes, stream, g);
   return hipGetLastError();
 }
 
