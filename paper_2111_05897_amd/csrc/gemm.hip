@@ -10,6 +10,8 @@
 #include "device_utils.h"
 #include "launch.h"
 
+#include <type_traits>
+
 namespace pemb {
 namespace {
 
@@ -36,6 +38,7 @@ struct GemmArgs {
   const float* bias;     // [N]            (epilogue 0)
   const bf16_t* mask;    // [M, N], ldm    (epilogue 2: keep where mask > 0)
   uint32_t ldm;
+  uint32_t vec_out;      // 1: C (and mask) rows can be written 16 bytes at a time
 };
 
 __device__ __forceinline__ uint4 load16_or_zero(const bf16_t* p, bool ok) {
@@ -133,6 +136,61 @@ __global__ __launch_bounds__(kGemmThreads, 2) void k_gemm_nt(GemmArgs g) {
   }
 
   // epilogue: accumulator element e of lane l is C[8*(e/4) + 4*(l/32) + e%4][l%32] of its 32x32 tile
+  if (g.vec_out) {
+    // Each wave passes its 32-row strips (32*WN columns wide) through a private LDS patch and writes whole
+    // rows, 16 bytes per lane; the K loop ended with a barrier, so the stages are free.  A wave's LDS
+    // accesses complete in order, so the patch needs no workgroup barrier.
+    using out_t = typename std::conditional<EPI == 1, float, bf16_t>::type;
+    constexpr int PW = 32 * WN;                       // patch width in elements
+    constexpr int VEC = 16 / (int)sizeof(out_t);      // elements per lane on the way out
+    constexpr int PS = PW + VEC;                      // padded patch stride
+    constexpr int LPR = PW / VEC, RPP = kWave / LPR;  // lanes per row, rows per pass
+    out_t* patch = reinterpret_cast<out_t*>(lds) + wave * 32 * PS;
+    const uint32_t cbase = n0 + wn * PW;
+#pragma unroll
+    for (int i = 0; i < WM; ++i) {
+#pragma unroll
+      for (int j = 0; j < WN; ++j) {
+        const int cl = j * 32 + (lane & 31);
+        float bias = 0.f;
+        if constexpr (EPI == 0) bias = (cbase + cl < g.N) ? g.bias[cbase + cl] : 0.f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int r = 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+          float v = acc[i][j][e];
+          if constexpr (EPI == 0) v = fmaxf(v + bias, 0.f);
+          if constexpr (EPI == 1) patch[r * PS + cl] = v;
+          else patch[r * PS + cl] = (bf16_t)f32_to_bf16(v);
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+      for (int pass = 0; pass < 32 / RPP; ++pass) {
+        const int r = pass * RPP + lane / LPR, c = (lane % LPR) * VEC;
+        const uint32_t row = m0 + wm * 32 * WM + i * 32 + r, col = cbase + c;
+        uint4 v = *reinterpret_cast<const uint4*>(&patch[r * PS + c]);
+        if (row < g.M && col < g.N) {  // N is a multiple of VEC here, so the whole vector is inside
+          if constexpr (EPI == 2) {    // keep where the stored activation is positive
+            const uint4 mv = *reinterpret_cast<const uint4*>(g.mask + (size_t)row * g.ldm + col);
+            auto keep = [](uint32_t val, uint32_t m) {
+              const uint32_t lo = m & 0xFFFFu, hi = m >> 16;
+              const uint32_t klo = ((lo & 0x7FFFu) != 0 && !(lo & 0x8000u)) ? 0x0000FFFFu : 0u;
+              const uint32_t khi = ((hi & 0x7FFFu) != 0 && !(hi & 0x8000u)) ? 0xFFFF0000u : 0u;
+              return val & (klo | khi);
+            };
+            v.x = keep(v.x, mv.x); v.y = keep(v.y, mv.y); v.z = keep(v.z, mv.z); v.w = keep(v.w, mv.w);
+          }
+          *reinterpret_cast<uint4*>(reinterpret_cast<out_t*>(g.C) + (size_t)row * g.ldc + col) = v;
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < WM; ++i)
 #pragma unroll
@@ -209,6 +267,9 @@ hipError_t launch_gemm_nt(int epilogue, const void* A, uint32_t lda, const void*
   g.bias = bias;
   g.mask = reinterpret_cast<const bf16_t*>(mask);
   g.ldm = ldm;
+  auto vec16 = [](const void* p, uint32_t ld) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0 && ld % 8 == 0; };
+  // fp32 output already writes 128 contiguous bytes per row from the accumulator layout
+  g.vec_out = (epilogue != 1 && N % 8 == 0 && vec16(C, ldc) && (epilogue != 2 || vec16(mask, ldm))) ? 1u : 0u;
   switch (epilogue) {
     case 0: return launch_epi<0>(g, stream);
     case 1: return launch_epi<1>(g, stream);

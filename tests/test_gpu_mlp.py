@@ -25,7 +25,7 @@ def _close(got, want, rtol=2e-2, floor=2e-3):
 
 
 @pytest.mark.parametrize("M,N,K", [(128, 128, 64), (64, 32, 128), (300, 200, 192), (129, 257, 64), (1, 1, 64),
-                                   (512, 9920 // 8, 256)])
+                                   (512, 9920 // 8, 256), (700, 520, 128), (257, 1033, 64)])
 def test_gemm_nt_matches_fp64_product(B, M, N, K):
     import torch
     rng = np.random.default_rng(M * 7 + N)
