@@ -39,15 +39,10 @@ struct GemmArgs {
   const bf16_t* mask;    // [M, N], ldm    (epilogue 2: keep where mask > 0)
   uint32_t ldm;
   uint32_t vec_out;      // 1: C (and mask) rows can be written 16 bytes at a time
+  bf16_t* Ct;            // optional second copy of a bf16 C, transposed: [N, M], row stride ldct (needs vec_out)
+  uint32_t ldct;
 };
 
-__device__ __forceinline__ uint4 load16_or_zero(const bf16_t* p, bool ok) {
-  return ok ? *reinterpret_cast<const uint4*>(p) : make_uint4(0u, 0u, 0u, 0u);
-}
-
-// Software pipeline over the K tiles: tile i is multiplied out of LDS stage i%2 while tile i+1 travels from
-// global memory into registers; it is written to the other stage at the end of the iteration, so there is
-// one barrier per iteration.
 template <int EPI>
 __global__ __launch_bounds__(kGemmThreads, 2) void k_gemm_nt(GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
@@ -81,26 +76,32 @@ __global__ __launch_bounds__(kGemmThreads, 2) void k_gemm_nt(GemmArgs g) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  uint4 ra[PA], rb[PB];
-  auto fetch = [&](uint32_t k0, uint4 (&a)[PA], uint4 (&b)[PB]) {
+  // Rows past the end of A or Bt are replaced by the last valid row (their products are never stored), so
+  // the loads need no predicate: a uniform base that advances with k plus one 32-bit offset per load.
+  const char* baseA = reinterpret_cast<const char*>(g.A + (size_t)m0 * g.lda);
+  const char* baseB = reinterpret_cast<const char*>(g.Bt + (size_t)n0 * g.ldb);
+  uint32_t offA[PA], offB[PB];
 #pragma unroll
-    for (int p = 0; p < PA; ++p) {
-      const uint32_t r = p * 64 + lrow;
-      a[p] = load16_or_zero(g.A + (size_t)(m0 + r) * g.lda + k0 + lcol, m0 + r < g.M);
-    }
+  for (int p = 0; p < PA; ++p) offA[p] = (min((uint32_t)(p * 64 + lrow), g.M - 1 - m0) * g.lda + lcol) * 2u;
 #pragma unroll
-    for (int p = 0; p < PB; ++p) {
-      const uint32_t r = p * 64 + lrow;
-      b[p] = load16_or_zero(g.Bt + (size_t)(n0 + r) * g.ldb + k0 + lcol, n0 + r < g.N);
-    }
+  for (int p = 0; p < PB; ++p) offB[p] = (min((uint32_t)(p * 64 + lrow), g.N - 1 - n0) * g.ldb + lcol) * 2u;
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 ra[PA], rb[PB], ra2[PA], rb2[PB];
+  auto fetch = [&](uint32_t k0, u32x4 (&a)[PA], u32x4 (&b)[PB]) {
+    const char* pa = baseA + (size_t)k0 * 2;
+    const char* pb = baseB + (size_t)k0 * 2;
+#pragma unroll
+    for (int p = 0; p < PA; ++p) a[p] = *reinterpret_cast<const u32x4*>(pa + offA[p]);
+#pragma unroll
+    for (int p = 0; p < PB; ++p) b[p] = *reinterpret_cast<const u32x4*>(pb + offB[p]);
   };
-  auto stage = [&](int s, const uint4 (&a)[PA], const uint4 (&b)[PB]) {
+  auto stage = [&](int s, const u32x4 (&a)[PA], const u32x4 (&b)[PB]) {
     bf16_t* As = lds + s * kStageElems;
     bf16_t* Bs = As + BM * LDS_STRIDE;
 #pragma unroll
-    for (int p = 0; p < PA; ++p) *reinterpret_cast<uint4*>(&As[(p * 64 + lrow) * LDS_STRIDE + lcol]) = a[p];
+    for (int p = 0; p < PA; ++p) *reinterpret_cast<u32x4*>(&As[(p * 64 + lrow) * LDS_STRIDE + lcol]) = a[p];
 #pragma unroll
-    for (int p = 0; p < PB; ++p) *reinterpret_cast<uint4*>(&Bs[(p * 64 + lrow) * LDS_STRIDE + lcol]) = b[p];
+    for (int p = 0; p < PB; ++p) *reinterpret_cast<u32x4*>(&Bs[(p * 64 + lrow) * LDS_STRIDE + lcol]) = b[p];
   };
   auto compute = [&](int s) {
     const bf16_t* As = lds + s * kStageElems;
@@ -125,13 +126,22 @@ __global__ __launch_bounds__(kGemmThreads, 2) void k_gemm_nt(GemmArgs g) {
   const uint32_t nk = g.K / BK;
   fetch(0, ra, rb);
   stage(0, ra, rb);
+  if (nk > 1) fetch(BK, ra, rb);
   __syncthreads();
+  // While tile i is multiplied out of LDS stage i%2, tile i+1 waits in registers (ra, rb; it goes to the
+  // other stage at the end of the iteration) and tile i+2 is on its way from global memory (ra2, rb2): every
+  // load has two iterations to arrive, and there is one barrier per iteration.
   for (uint32_t i = 0; i < nk; ++i) {
     const int cur = i & 1;
-    if (i + 1 < nk) fetch((i + 1) * BK, ra, rb);
+    if (i + 2 < nk) fetch((i + 2) * BK, ra2, rb2);
     compute(cur);
-    // the other stage was last read in iteration i-1, which every wave has left (barrier below)
-    if (i + 1 < nk) stage(cur ^ 1, ra, rb);
+    if (i + 1 < nk) stage(cur ^ 1, ra, rb);  // that stage was last read in iteration i-1, behind a barrier
+    if (i + 2 < nk) {
+#pragma unroll
+      for (int p = 0; p < PA; ++p) ra[p] = ra2[p];
+#pragma unroll
+      for (int p = 0; p < PB; ++p) rb[p] = rb2[p];
+    }
     __syncthreads();
   }
 
@@ -183,6 +193,30 @@ __global__ __launch_bounds__(kGemmThreads, 2) void k_gemm_nt(GemmArgs g) {
             v.x = keep(v.x, mv.x); v.y = keep(v.y, mv.y); v.z = keep(v.z, mv.z); v.w = keep(v.w, mv.w);
           }
           *reinterpret_cast<uint4*>(reinterpret_cast<out_t*>(g.C) + (size_t)row * g.ldc + col) = v;
+        }
+        if constexpr (EPI == 2) {  // the transposed copy below wants the masked values
+          if (g.Ct) *reinterpret_cast<uint4*>(&patch[r * PS + c]) = v;
+        }
+      }
+      if constexpr (EPI != 1) {
+        if (g.Ct) {
+          static_assert(EPI == 1 || PW == kWave, "one patch column per lane");
+          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+          __builtin_amdgcn_wave_barrier();
+          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+          const uint32_t col = cbase + lane;
+#pragma unroll
+          for (int p8 = 0; p8 < 4; ++p8) {  // 8 consecutive rows of column `lane` -> 16 bytes of Ct's row
+            uint32_t w4[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const uint32_t lo = patch[(p8 * 8 + 2 * q) * PS + lane], hi = patch[(p8 * 8 + 2 * q + 1) * PS + lane];
+              w4[q] = lo | (hi << 16);
+            }
+            const uint32_t row0 = m0 + wm * 32 * WM + i * 32 + p8 * 8;
+            if (col < g.N && row0 < g.M)  // M is a multiple of 8 here
+              *reinterpret_cast<uint4*>(g.Ct + (size_t)col * g.ldct + row0) = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+          }
         }
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -250,7 +284,7 @@ hipError_t launch_epi(const GemmArgs& g, hipStream_t stream) {
 
 hipError_t launch_gemm_nt(int epilogue, const void* A, uint32_t lda, const void* Bt, uint32_t ldb, uint32_t M, uint32_t N,
                           uint32_t K, void* C, uint32_t ldc, const float* bias, const void* mask, uint32_t ldm,
-                          hipStream_t stream) {
+                          hipStream_t stream, void* Ct, uint32_t ldct) {
   if (M == 0 || N == 0) return hipSuccess;
   if (K == 0 || K % BK != 0 || lda % 8 != 0 || ldb % 8 != 0) return hipErrorInvalidValue;  // 16-byte operand loads
   if (!A || !Bt || !C || (epilogue == 0 && !bias) || (epilogue == 2 && !mask)) return hipErrorInvalidValue;
@@ -270,12 +304,19 @@ hipError_t launch_gemm_nt(int epilogue, const void* A, uint32_t lda, const void*
   auto vec16 = [](const void* p, uint32_t ld) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0 && ld % 8 == 0; };
   // fp32 output already writes 128 contiguous bytes per row from the accumulator layout
   g.vec_out = (epilogue != 1 && N % 8 == 0 && vec16(C, ldc) && (epilogue != 2 || vec16(mask, ldm))) ? 1u : 0u;
+  if (Ct && epilogue == 1) return hipErrorInvalidValue;  // the transposed copy is bf16
+  const bool fused_t = Ct && g.vec_out && M % 8 == 0 && vec16(Ct, ldct);
+  g.Ct = fused_t ? reinterpret_cast<bf16_t*>(Ct) : nullptr;
+  g.ldct = ldct;
+  hipError_t e;
   switch (epilogue) {
-    case 0: return launch_epi<0>(g, stream);
-    case 1: return launch_epi<1>(g, stream);
-    case 2: return launch_epi<2>(g, stream);
+    case 0: e = launch_epi<0>(g, stream); break;
+    case 1: e = launch_epi<1>(g, stream); break;
+    case 2: e = launch_epi<2>(g, stream); break;
     default: return hipErrorInvalidValue;
   }
+  if (e == hipSuccess && Ct && !fused_t) e = launch_transpose_bf16(C, M, N, ldc, Ct, ldct, stream);
+  return e;
 }
 
 hipError_t launch_transpose_bf16(const void* in, uint32_t R, uint32_t Cc, uint32_t ld_in, void* out, uint32_t ld_out,

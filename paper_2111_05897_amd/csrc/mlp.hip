@@ -19,16 +19,28 @@ namespace {
 
 thread_local std::string g_mlp_create_error;
 
-// x[b, :] = bf16([pooled[b, :] | dense[b, :]])
+// x[b, :] = bf16([pooled[b, :] | dense[b, :]]) and xt = x transposed ([P + Dn, B]); 64x64 tiles through LDS.
 __global__ __launch_bounds__(kBlock) void k_pack_input(const float* __restrict__ pooled, uint32_t P,
                                                        const float* __restrict__ dense, uint32_t Dn, uint32_t B,
-                                                       bf16_t* __restrict__ x) {
+                                                       bf16_t* __restrict__ x, bf16_t* __restrict__ xt) {
+  __shared__ bf16_t t[64][66];
   const uint32_t K0 = P + Dn;
-  const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i >= (uint64_t)B * K0) return;
-  const uint32_t b = (uint32_t)(i / K0), c = (uint32_t)(i - (uint64_t)b * K0);
-  const float v = c < P ? pooled[(size_t)b * P + c] : dense[(size_t)b * Dn + (c - P)];
-  x[i] = (bf16_t)f32_to_bf16(v);
+  const uint32_t b0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  for (int i = threadIdx.x; i < 64 * 64; i += kBlock) {
+    const uint32_t r = i / 64, cc = i % 64;
+    const uint32_t b = b0 + r, c = c0 + cc;
+    bf16_t v = 0;
+    if (b < B && c < K0) {
+      v = (bf16_t)f32_to_bf16(c < P ? pooled[(size_t)b * P + c] : dense[(size_t)b * Dn + (c - P)]);
+      x[(size_t)b * K0 + c] = v;
+    }
+    t[r][cc] = v;
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < 64 * 64; i += kBlock) {
+    const uint32_t cc = i / 64, r = i % 64;
+    if (b0 + r < B && c0 + cc < K0) xt[(size_t)(c0 + cc) * B + b0 + r] = t[r][cc];
+  }
 }
 
 // One wave per sample: z = h[b, :] . w + bias; dz = scale * (sigmoid(z) - y); loss term;
@@ -298,13 +310,14 @@ int mlp_step_impl(mlp_ctx* c, uint32_t B, const float* pooled, const float* dens
   c->last_batch = B;
   // forward
   {
-    const uint64_t n = (uint64_t)B * w[0];
-    hipLaunchKernelGGL(k_pack_input, dim3((uint32_t)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, pooled, c->P, dense,
-                       c->Dn, B, c->h[0]);
+    hipLaunchKernelGGL(k_pack_input, dim3((w[0] + 63) / 64, (B + 63) / 64), dim3(kBlock), 0, s, pooled, c->P, dense,
+                       c->Dn, B, c->h[0], c->ht[0]);
     CKM(hipGetLastError(), "pack_input");
   }
-  for (uint32_t l = 0; l + 1 < L; ++l)  // h[l+1] = relu(h[l] W[l] + b[l])
-    CKM(launch_gemm_nt(0, c->h[l], w[l], c->Wt[l], w[l], B, w[l + 1], w[l], c->h[l + 1], w[l + 1], c->bias[l], nullptr, 0, s),
+  // h[l+1] = relu(h[l] W[l] + b[l]); the weight gradients below want h[1..L-2] transposed as well
+  for (uint32_t l = 0; l + 1 < L; ++l)
+    CKM(launch_gemm_nt(0, c->h[l], w[l], c->Wt[l], w[l], B, w[l + 1], w[l], c->h[l + 1], w[l + 1], c->bias[l], nullptr, 0, s,
+                       l + 2 < L ? c->ht[l + 1] : nullptr, B),
         "gemm(forward)");
   const uint32_t H = w[L - 1];
   const float scale = c->loss_mean ? 1.0f / (float)B : 1.0f;
@@ -321,14 +334,15 @@ int mlp_step_impl(mlp_ctx* c, uint32_t B, const float* pooled, const float* dens
   for (uint32_t l = L - 1; l >= 1; --l) {
     // delta[l]: [B, w[l]] is the gradient w.r.t. the pre-activation of h[l]; it feeds layer l-1's weights
     CKM(colsum(c, c->delta[l], B, w[l], nullptr, c->db[l - 1], s), "db");
-    CKM(launch_transpose_bf16(c->h[l - 1], B, w[l - 1], w[l - 1], c->ht[l - 1], B, s), "transpose(h)");
-    CKM(launch_transpose_bf16(c->delta[l], B, w[l], w[l], c->deltat[l], B, s), "transpose(delta)");
+    // ht[l-1] came with the forward pass and deltat[l] with the GEMM that made delta[l]; the last layer's
+    // delta comes from the loss kernel
+    if (l == L - 1) CKM(launch_transpose_bf16(c->delta[l], B, w[l], w[l], c->deltat[l], B, s), "transpose(delta)");
     // dW[l-1] [w[l-1], w[l]] = h[l-1]^T delta[l]
     CKM(launch_gemm_nt(1, c->ht[l - 1], B, c->deltat[l], B, w[l - 1], w[l], B, c->dW[l - 1], w[l], nullptr, nullptr, 0, s),
         "gemm(dW)");
     if (l >= 2) {  // delta[l-1] = (delta[l] W[l-1]^T) masked by h[l-1] > 0
       CKM(launch_gemm_nt(2, c->delta[l], w[l], c->W[l - 1], w[l], B, w[l - 1], w[l], c->delta[l - 1], w[l - 1], nullptr,
-                         c->h[l - 1], w[l - 1], s),
+                         c->h[l - 1], w[l - 1], s, c->deltat[l - 1], B),
           "gemm(delta)");
     } else {  // gradient of the pooled embedding activations: the first P input columns, fp32
       CKM(launch_gemm_nt(1, c->delta[1], w[1], c->W[0], w[1], B, c->P, w[1], d_pooled, c->P, nullptr, nullptr, 0, s),
