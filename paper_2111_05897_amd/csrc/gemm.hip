@@ -10,6 +10,7 @@
 #include "device_utils.h"
 #include "launch.h"
 
+#include <algorithm>
 #include <type_traits>
 
 namespace pemb {
@@ -39,6 +40,8 @@ struct GemmArgs {
   const bf16_t* mask;    // [M, N], ldm    (epilogue 2: keep where mask > 0)
   uint32_t ldm;
   uint32_t vec_out;      // 1: C (and mask) rows can be written 16 bytes at a time
+  uint32_t k_tiles_per_split;  // blockIdx.y takes this many K tiles and writes the fp32 partial product
+  uint64_t part_stride;        // number blockIdx.y, part_stride elements apart (split-K, epilogue 1 only)
   bf16_t* Ct;            // optional second copy of a bf16 C, transposed: [N, M], row stride ldct (needs vec_out)
   uint32_t ldct;
 };
@@ -78,8 +81,9 @@ __global__ __launch_bounds__(kGemmThreads, 2) void k_gemm_nt(GemmArgs g) {
 
   // Rows past the end of A or Bt are replaced by the last valid row (their products are never stored), so
   // the loads need no predicate: a uniform base that advances with k plus one 32-bit offset per load.
-  const char* baseA = reinterpret_cast<const char*>(g.A + (size_t)m0 * g.lda);
-  const char* baseB = reinterpret_cast<const char*>(g.Bt + (size_t)n0 * g.ldb);
+  const uint32_t kt0 = blockIdx.y * g.k_tiles_per_split;  // first K tile of this split
+  const char* baseA = reinterpret_cast<const char*>(g.A + (size_t)m0 * g.lda + (size_t)kt0 * BK);
+  const char* baseB = reinterpret_cast<const char*>(g.Bt + (size_t)n0 * g.ldb + (size_t)kt0 * BK);
   uint32_t offA[PA], offB[PB];
 #pragma unroll
   for (int p = 0; p < PA; ++p) offA[p] = (min((uint32_t)(p * 64 + lrow), g.M - 1 - m0) * g.lda + lcol) * 2u;
@@ -123,7 +127,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void k_gemm_nt(GemmArgs g) {
     }
   };
 
-  const uint32_t nk = g.K / BK;
+  const uint32_t nk = min(g.K / BK - kt0, g.k_tiles_per_split);
   fetch(0, ra, rb);
   stage(0, ra, rb);
   if (nk > 1) fetch(BK, ra, rb);
@@ -242,7 +246,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void k_gemm_nt(GemmArgs g) {
           v = fmaxf(v + bias, 0.f);
           reinterpret_cast<bf16_t*>(g.C)[(size_t)row * g.ldc + col] = (bf16_t)f32_to_bf16(v);
         } else if constexpr (EPI == 1) {  // fp32
-          reinterpret_cast<float*>(g.C)[(size_t)row * g.ldc + col] = v;
+          reinterpret_cast<float*>(g.C)[blockIdx.y * g.part_stride + (size_t)row * g.ldc + col] = v;
         } else {  // keep where the stored activation is positive -> bf16
           const bf16_t mv = g.mask[(size_t)row * g.ldm + col];
           const bool on = (mv & 0x7FFFu) != 0 && !(mv & 0x8000u);
@@ -276,15 +280,39 @@ hipError_t launch_epi(const GemmArgs& g, hipStream_t stream) {
   if (attr != hipSuccess) return attr;
   const uint32_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   const uint32_t grid = (tiles + kXcds - 1) / kXcds * kXcds;
-  hipLaunchKernelGGL(k_gemm_nt<EPI>, dim3(grid), dim3(kGemmThreads), kGemmLdsBytes, stream, g);
+  const uint32_t splits = (g.K / BK + g.k_tiles_per_split - 1) / g.k_tiles_per_split;
+  hipLaunchKernelGGL(k_gemm_nt<EPI>, dim3(grid, splits), dim3(kGemmThreads), kGemmLdsBytes, stream, g);
   return hipGetLastError();
+}
+
+// C[r][c] = sum over s of parts[s][r][c], in the order of s.
+__global__ __launch_bounds__(kBlock) void k_sum_splits(const float* __restrict__ parts, uint32_t splits, uint32_t M,
+                                                       uint32_t N, float* __restrict__ C, uint32_t ldc) {
+  const uint64_t n = (uint64_t)M * N;
+  for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kBlock) {
+    float acc = parts[i];
+    for (uint32_t sp = 1; sp < splits; ++sp) acc += parts[sp * n + i];
+    C[(i / N) * ldc + i % N] = acc;
+  }
 }
 
 }  // namespace
 
+// A product with few output tiles and a long K leaves most compute units idle: such a product is cut along K
+// into this many partial products (1 = no split), summed afterwards in a fixed order.
+uint32_t gemm_splits(uint32_t M, uint32_t N, uint32_t K) {
+  const uint32_t tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+  const uint32_t nk = K / BK;
+  if (tiles == 0 || tiles * 2 > 256) return 1;
+  uint32_t s = 256 / tiles;
+  if (s > nk / 4) s = nk / 4;  // at least four K tiles per split
+  if (s > 16) s = 16;
+  return s < 2 ? 1 : s;
+}
+
 hipError_t launch_gemm_nt(int epilogue, const void* A, uint32_t lda, const void* Bt, uint32_t ldb, uint32_t M, uint32_t N,
                           uint32_t K, void* C, uint32_t ldc, const float* bias, const void* mask, uint32_t ldm,
-                          hipStream_t stream, void* Ct, uint32_t ldct) {
+                          hipStream_t stream, void* Ct, uint32_t ldct, float* split_ws, uint64_t split_ws_elems) {
   if (M == 0 || N == 0) return hipSuccess;
   if (K == 0 || K % BK != 0 || lda % 8 != 0 || ldb % 8 != 0) return hipErrorInvalidValue;  // 16-byte operand loads
   if (!A || !Bt || !C || (epilogue == 0 && !bias) || (epilogue == 2 && !mask)) return hipErrorInvalidValue;
@@ -305,6 +333,21 @@ hipError_t launch_gemm_nt(int epilogue, const void* A, uint32_t lda, const void*
   // fp32 output already writes 128 contiguous bytes per row from the accumulator layout
   g.vec_out = (epilogue != 1 && N % 8 == 0 && vec16(C, ldc) && (epilogue != 2 || vec16(mask, ldm))) ? 1u : 0u;
   if (Ct && epilogue == 1) return hipErrorInvalidValue;  // the transposed copy is bf16
+  g.k_tiles_per_split = K / BK;
+  g.part_stride = 0;
+  uint32_t splits = 1;
+  if (epilogue == 1 && split_ws) {
+    splits = gemm_splits(M, N, K);
+    const uint64_t fit = split_ws_elems / ((uint64_t)M * N);
+    if (splits > fit) splits = (uint32_t)fit;
+    if (splits >= 2) {
+      g.k_tiles_per_split = (K / BK + splits - 1) / splits;
+      splits = (K / BK + g.k_tiles_per_split - 1) / g.k_tiles_per_split;  // no empty split
+      g.C = split_ws;
+      g.ldc = N;
+      g.part_stride = (uint64_t)M * N;
+    }
+  }
   const bool fused_t = Ct && g.vec_out && M % 8 == 0 && vec16(Ct, ldct);
   g.Ct = fused_t ? reinterpret_cast<bf16_t*>(Ct) : nullptr;
   g.ldct = ldct;
@@ -314,6 +357,13 @@ hipError_t launch_gemm_nt(int epilogue, const void* A, uint32_t lda, const void*
     case 1: e = launch_epi<1>(g, stream); break;
     case 2: e = launch_epi<2>(g, stream); break;
     default: return hipErrorInvalidValue;
+  }
+  if (e == hipSuccess && splits >= 2) {
+    const uint64_t n = (uint64_t)M * N;
+    const uint32_t blocks = (uint32_t)std::min<uint64_t>((n + kBlock - 1) / kBlock, 4096);
+    hipLaunchKernelGGL(k_sum_splits, dim3(blocks), dim3(kBlock), 0, stream, split_ws, splits, M, N,
+                       reinterpret_cast<float*>(C), ldc);
+    e = hipGetLastError();
   }
   if (e == hipSuccess && Ct && !fused_t) e = launch_transpose_bf16(C, M, N, ldc, Ct, ldct, stream);
   return e;

@@ -112,10 +112,14 @@ hipError_t launch_fixup(const TableView& t, const BackwardArgs& a, hipStream_t s
 // C[M,N] = A[M,K] * Bt[N,K]^T, bf16 operands (row strides lda, ldb, multiples of 8), fp32 accumulation, K a
 // multiple of 64.  epilogue 0: C bf16 = relu(acc + bias[n]); 1: C fp32 = acc; 2: C bf16 = acc where the bf16
 // matrix `mask` (row stride ldm) is positive, else 0.  Ct (optional, bf16 epilogues only) receives C
-// transposed, [N, M] with row stride ldct.
+// transposed, [N, M] with row stride ldct.  split_ws (optional, epilogue 1 only): fp32 scratch of
+// split_ws_elems elements; with it a product of few output tiles and long K is cut along K into up to
+// gemm_splits(M, N, K) partial products of M*N elements each, summed in a fixed order.
+uint32_t gemm_splits(uint32_t M, uint32_t N, uint32_t K);
 hipError_t launch_gemm_nt(int epilogue, const void* A, uint32_t lda, const void* Bt, uint32_t ldb, uint32_t M, uint32_t N,
                           uint32_t K, void* C, uint32_t ldc, const float* bias, const void* mask, uint32_t ldm,
-                          hipStream_t stream, void* Ct = nullptr, uint32_t ldct = 0);
+                          hipStream_t stream, void* Ct = nullptr, uint32_t ldct = 0, float* split_ws = nullptr,
+                          uint64_t split_ws_elems = 0);
 hipError_t launch_transpose_bf16(const void* in, uint32_t R, uint32_t Cc, uint32_t ld_in, void* out, uint32_t ld_out,
                                  hipStream_t stream);
 

@@ -168,6 +168,8 @@ struct mlp_ctx {
   // activations for max_batch
   std::vector<bf16_t*> h, ht, delta, deltat;  // h[l]: [B, widths[l]] (h[0] = packed input), ht: transposed; delta[l] for l = 1..L-1
   float *dz = nullptr, *loss_parts = nullptr, *col_parts = nullptr;
+  float* split_ws = nullptr;  // partial weight-gradient products (split along the batch dimension)
+  uint64_t split_ws_elems = 0;
   uint32_t last_batch = 0;
   std::vector<void*> allocs;
   uint64_t device_bytes = 0;
@@ -272,6 +274,13 @@ int mlp_create_impl(const mlp_config* cfg, const float* const* weights, const fl
     }
     if (n_in > max_w) max_w = (uint32_t)n_in;
   }
+  // scratch for the weight-gradient products that are cut along the batch dimension
+  c->split_ws_elems = 0;
+  for (uint32_t l = 0; l + 1 < L; ++l) {
+    const uint64_t need = (uint64_t)gemm_splits(c->widths[l], c->widths[l + 1], (uint32_t)B) * c->widths[l] * c->widths[l + 1];
+    if (gemm_splits(c->widths[l], c->widths[l + 1], (uint32_t)B) >= 2 && need > c->split_ws_elems) c->split_ws_elems = need;
+  }
+  if (c->split_ws_elems) CK(malloc_dev(c, &c->split_ws, c->split_ws_elems), "hipMalloc(split-K scratch)");
   CK(malloc_dev(c, &c->dz, B), "hipMalloc(dz)");
   CK(malloc_dev(c, &c->loss_parts, (B + kWavesPerBlock - 1) / kWavesPerBlock), "hipMalloc(loss parts)");
   CK(malloc_dev(c, &c->col_parts, (uint64_t)kColChunks * max_w), "hipMalloc(column sums)");
@@ -338,7 +347,8 @@ int mlp_step_impl(mlp_ctx* c, uint32_t B, const float* pooled, const float* dens
     // delta comes from the loss kernel
     if (l == L - 1) CKM(launch_transpose_bf16(c->delta[l], B, w[l], w[l], c->deltat[l], B, s), "transpose(delta)");
     // dW[l-1] [w[l-1], w[l]] = h[l-1]^T delta[l]
-    CKM(launch_gemm_nt(1, c->ht[l - 1], B, c->deltat[l], B, w[l - 1], w[l], B, c->dW[l - 1], w[l], nullptr, nullptr, 0, s),
+    CKM(launch_gemm_nt(1, c->ht[l - 1], B, c->deltat[l], B, w[l - 1], w[l], B, c->dW[l - 1], w[l], nullptr, nullptr, 0, s,
+                       nullptr, 0, c->split_ws, c->split_ws_elems),
         "gemm(dW)");
     if (l >= 2) {  // delta[l-1] = (delta[l] W[l-1]^T) masked by h[l-1] > 0
       CKM(launch_gemm_nt(2, c->delta[l], w[l], c->W[l - 1], w[l], B, w[l - 1], w[l], c->delta[l - 1], w[l - 1], nullptr,
