@@ -213,6 +213,40 @@ int mlp_gemm_nt(int epilogue, const uint16_t* A, uint32_t lda, const uint16_t* B
                 uint32_t K, void* C, uint32_t ldc, const float* bias, const uint16_t* mask, uint32_t ldm, void* hip_stream);
 const char* mlp_last_error(mlp_ctx* ctx); /* ctx == NULL: the last failed mlp_create */
 
+/* ---- hybrid step loop (section 3.2: the embedding layer is trained asynchronously, the dense network
+ * synchronously; section 5: the staleness of the embedding parameters is bounded by tau) ------------------
+ * hyb_submit hands over batch t = 0, 1, 2, ...: its lookup (Algorithm 1, forward task) is enqueued at once,
+ * and batch t - tau -- whose pooled activations have been waiting since its own submission, like a sample in
+ * the embedding worker's buffer -- gets its dense step (Algorithm 2) and its embedding put + optimizer
+ * (Algorithm 1, backward task).  Events fix the order so that the lookup of batch t sees the updates of the
+ * batches 0 .. t - tau - 1 and of no others (tau = 0 is fully synchronous training); the lookup of batch t
+ * runs on a second stream beside the dense step of batch t - tau.  The results are those of the same calls
+ * made one after the other in the order L(0)..L(tau), train(0), L(tau+1), train(1), ...
+ * hyb_create: emb and mlp must live on one device and agree on the pooled width; they stay owned by the
+ *   caller, must outlive the loop, and must not be used elsewhere between hyb_submit and hyb_sync.  Allocates
+ *   tau + 1 sets of input copies and pooled activations.
+ * hyb_submit: batch->ids / offsets, dense [B, dense_width], labels [B]: device buffers, copied by work
+ *   enqueued in this call; they may be overwritten after hyb_wait_inputs (or hyb_sync) returns.  Enqueue-only.
+ * hyb_drain: trains the batches that have been looked up but not trained (the last tau), in order.
+ * hyb_sync: waits for everything enqueued.  hyb_counts: batches submitted / trained (enqueued) so far.
+ * hyb_read_losses: losses[i] = loss of batch first + i as mlp_step reported it (synchronous; host array;
+ *   the most recent 65536 trained batches are kept). */
+typedef struct hyb_ctx hyb_ctx;
+int hyb_create(emb_ctx* emb, mlp_ctx* mlp, uint32_t tau, hyb_ctx** out);
+int hyb_submit(hyb_ctx* ctx, const emb_batch* batch, const float* dense, const float* labels);
+int hyb_drain(hyb_ctx* ctx);
+int hyb_sync(hyb_ctx* ctx);
+int hyb_wait_inputs(hyb_ctx* ctx);
+int hyb_counts(hyb_ctx* ctx, uint64_t* submitted, uint64_t* trained);
+int hyb_read_losses(hyb_ctx* ctx, uint64_t first, uint64_t count, float* losses);
+int hyb_destroy(hyb_ctx* ctx); /* synchronous; does not destroy emb or mlp */
+const char* hyb_last_error(hyb_ctx* ctx); /* ctx == NULL: the last failed hyb_create */
+
+/* Shapes and limits a context was created with (any pointer may be NULL). */
+int emb_describe(emb_ctx* ctx, uint32_t* num_slots, uint32_t* pooled_width, uint32_t* max_batch, uint64_t* max_ids,
+                 int32_t* device);
+int mlp_describe(mlp_ctx* ctx, uint32_t* pooled_width, uint32_t* dense_width, uint32_t* max_batch, int32_t* device);
+
 /* Bytes of device memory the context holds (tables, state, workspace). */
 uint64_t emb_device_bytes(emb_ctx* ctx);
 

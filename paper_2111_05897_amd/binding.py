@@ -101,6 +101,21 @@ def load_library() -> C.CDLL:
     L.mlp_read_state.argtypes = [vp, i32, u32, vp, u64]
     for name in ("mlp_create", "mlp_step", "mlp_read_weights", "mlp_destroy", "mlp_gemm_nt", "mlp_read_state"):
         getattr(L, name).restype = C.c_int
+    L.hyb_create.argtypes = [vp, vp, u32, C.POINTER(vp)]
+    L.hyb_submit.argtypes = [vp, C.POINTER(emb_batch), vp, vp]
+    L.hyb_drain.argtypes = [vp]
+    L.hyb_sync.argtypes = [vp]
+    L.hyb_wait_inputs.argtypes = [vp]
+    L.hyb_counts.argtypes = [vp, C.POINTER(u64), C.POINTER(u64)]
+    L.hyb_read_losses.argtypes = [vp, u64, u64, vp]
+    L.hyb_destroy.argtypes = [vp]
+    L.hyb_last_error.argtypes = [vp]
+    L.hyb_last_error.restype = C.c_char_p
+    L.emb_describe.argtypes = [vp, C.POINTER(u32), C.POINTER(u32), C.POINTER(u32), C.POINTER(u64), C.POINTER(i32)]
+    L.mlp_describe.argtypes = [vp, C.POINTER(u32), C.POINTER(u32), C.POINTER(u32), C.POINTER(i32)]
+    for name in ("hyb_create", "hyb_submit", "hyb_drain", "hyb_sync", "hyb_wait_inputs", "hyb_counts", "hyb_read_losses",
+                 "hyb_destroy", "emb_describe", "mlp_describe"):
+        getattr(L, name).restype = C.c_int
     L.emb_last_error.argtypes = [vp]
     L.emb_last_error.restype = C.c_char_p
     for name in ("emb_create", "emb_destroy", "emb_lookup_pool", "emb_hash_rows", "emb_backward_update",
@@ -361,3 +376,58 @@ def mlp_gemm_nt(epilogue, A, Bt, bias=None, mask=None, stream=None):
     if rc:
         raise EmbError(rc, L.mlp_last_error(None).decode())
     return Cm
+
+
+class HybridLoop:
+    """Owns one hyb_ctx: the step loop with staleness tau over an EmbContext and an MlpContext (both stay owned by
+    the caller and must outlive the loop).  Method names mirror the C entry points."""
+
+    def __init__(self, emb: "EmbContext", mlp: "MlpContext", tau: int):
+        self.L = load_library()
+        self.emb, self.mlp, self.tau = emb, mlp, int(tau)
+        h = C.c_void_p()
+        rc = self.L.hyb_create(emb.h, mlp.h, self.tau, C.byref(h))
+        if rc:
+            raise EmbError(rc, self.L.hyb_last_error(None).decode())
+        self.h = h
+
+    def _ck(self, rc):
+        if rc:
+            raise EmbError(rc, self.L.hyb_last_error(self.h).decode())
+
+    def hyb_submit(self, batch: "DeviceBatch", dense, labels):
+        B = batch.batch_size
+        assert labels.is_contiguous() and labels.dtype == torch.float32 and labels.shape == (B,)
+        assert dense is None or (dense.is_contiguous() and dense.dtype == torch.float32 and dense.shape[0] == B)
+        self._ck(self.L.hyb_submit(self.h, C.byref(batch.c), dense.data_ptr() if dense is not None else None,
+                                   labels.data_ptr()))
+
+    def hyb_drain(self):
+        self._ck(self.L.hyb_drain(self.h))
+
+    def hyb_sync(self):
+        self._ck(self.L.hyb_sync(self.h))
+
+    def hyb_wait_inputs(self):
+        self._ck(self.L.hyb_wait_inputs(self.h))
+
+    def hyb_counts(self):
+        a, b = C.c_uint64(), C.c_uint64()
+        self._ck(self.L.hyb_counts(self.h, C.byref(a), C.byref(b)))
+        return a.value, b.value
+
+    def hyb_read_losses(self, first, count):
+        out = np.empty(count, dtype=np.float32)
+        self._ck(self.L.hyb_read_losses(self.h, first, count, out.ctypes.data))
+        return out
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.L.hyb_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

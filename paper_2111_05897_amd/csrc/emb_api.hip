@@ -697,6 +697,16 @@ int emb_codec_decompress(const uint16_t* q, const float* norm, uint64_t n_blocks
 }
 
 uint64_t emb_device_bytes(emb_ctx* ctx) { return ctx ? ctx->device_bytes : 0; }
+int emb_describe(emb_ctx* ctx, uint32_t* num_slots, uint32_t* pooled_width, uint32_t* max_batch, uint64_t* max_ids,
+                 int32_t* device) {
+  if (!ctx) return fail(nullptr, EMB_EINVAL, "null context");
+  if (num_slots) *num_slots = ctx->S;
+  if (pooled_width) *pooled_width = ctx->width;
+  if (max_batch) *max_batch = ctx->max_batch;
+  if (max_ids) *max_ids = ctx->max_ids;
+  if (device) *device = ctx->device;
+  return EMB_OK;
+}
 
 const char* emb_last_error(emb_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
 

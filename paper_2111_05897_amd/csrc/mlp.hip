@@ -460,6 +460,14 @@ int mlp_destroy(mlp_ctx* ctx) {
   return EMB_OK;
 }
 uint64_t mlp_device_bytes(mlp_ctx* ctx) { return ctx ? ctx->device_bytes : 0; }
+int mlp_describe(mlp_ctx* ctx, uint32_t* pooled_width, uint32_t* dense_width, uint32_t* max_batch, int32_t* device) {
+  if (!ctx) return mfail(nullptr, EMB_EINVAL, "null context");
+  if (pooled_width) *pooled_width = ctx->P;
+  if (dense_width) *dense_width = ctx->Dn;
+  if (max_batch) *max_batch = ctx->max_batch;
+  if (device) *device = ctx->device;
+  return EMB_OK;
+}
 int mlp_gemm_nt(int epilogue, const uint16_t* A, uint32_t lda, const uint16_t* Bt, uint32_t ldb, uint32_t M, uint32_t N,
                 uint32_t K, void* C, uint32_t ldc, const float* bias, const uint16_t* mask, uint32_t ldm, void* hip_stream) {
   hipError_t e = launch_gemm_nt(epilogue, A, lda, Bt, ldb, M, N, K, C, ldc, bias, mask, ldm, (hipStream_t)hip_stream);
