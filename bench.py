@@ -120,12 +120,31 @@ def bench_hybrid(args, w, binding, torch, np, W) -> int:
     for i in range(args.warmup):
         step(i, False)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        n, loss = step(args.warmup + i, False)
-        ids_done += n
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    if args.tau is None:
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            n, loss = step(args.warmup + i, False)
+            ids_done += n
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+    else:
+        # the library's step loop: lookups run tau batches ahead of the dense step, on a second stream; the timed
+        # region starts with tau lookups in flight and ends with tau in flight, so it holds `steps` whole steps
+        loop = binding.HybridLoop(ctx, mlp, args.tau)
+        for i in range(args.tau + args.warmup):
+            loop.hyb_submit(batches[i % nb], *feats[i % nb])
+        loop.hyb_sync()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            j = args.tau + args.warmup + i
+            loop.hyb_submit(batches[j % nb], *feats[j % nb])
+            ids_done += batches[(j - args.tau) % nb].num_ids
+        loop.hyb_sync()
+        elapsed = time.perf_counter() - t0
+        loop.hyb_drain()
+        n_trained = loop.hyb_counts()[1]
+        loss = torch.tensor(loop.hyb_read_losses(n_trained - 1, 1))
+        loop.close()
     for i in range(args.steps):
         step(args.warmup + i, True)
     B = w.batch
@@ -145,7 +164,7 @@ def bench_hybrid(args, w, binding, torch, np, W) -> int:
         "unit": "IDs/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(elapsed * 1e3 / args.steps, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": w.name + "_hybrid", "batch": B, "slots": cfg.num_slots, "mlp_widths": widths,
+        "config": {"workload": w.name + "_hybrid", "schedule": "sync" if args.tau is None else f"staleness-{args.tau} loop", "batch": B, "slots": cfg.num_slots, "mlp_widths": widths,
                    "ids_per_step": round(ids_done / args.steps), "last_loss": round(float(loss.item()), 5)},
         "part_ms_per_step": {"emb_lookup_pool": round(t_emb_f / args.steps, 4), "mlp_step": round(mlp_ms, 4),
                              "emb_backward_update": round(t_emb_b / args.steps, 4)},
@@ -170,6 +189,8 @@ def main() -> int:
                     help="instead of the training step, time the scaled-fp16 value codec on this config's pooled shape")
     ap.add_argument("--hybrid", action="store_true",
                     help="full hybrid step: lookup -> dense MLP step (bf16 MFMA) -> embedding update with the MLP's gradient")
+    ap.add_argument("--tau", type=int, default=None,
+                    help="with --hybrid: run the library's step loop with this staleness (lookups tau batches ahead, second stream)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device-to-device copies (reference for rocprofv3 byte counters)")

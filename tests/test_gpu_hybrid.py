@@ -168,3 +168,19 @@ def test_loop_validation(B):
     loop.hyb_drain()                                              # nothing to do
     loop.hyb_sync()
     loop.close()
+
+
+def test_small_staleness_trains_like_synchronous(B):
+    """The qualitative claim of section 5 / Table 2 on the synthetic click task: the student learns (the
+    progressive-validation loss falls well below the base-rate entropy) and a staleness of a few batches
+    leaves the loss it reaches within 2 % of fully synchronous training."""
+    from paper_2111_05897_amd import staleness_study as SS
+    task = SS.Task(3)
+    out = {}
+    for tau in (0, 4):
+        losses, bayes, base = SS.run(tau, 240, batch_size=2048, seed=3, task=task)
+        assert np.isfinite(losses).all()
+        out[tau] = SS.summarize(tau, losses, bayes, base, 40)
+    assert out[0]["loss_last"] < 0.93 * out[0]["base_rate_entropy"], out
+    assert out[0]["loss_last"] > out[0]["teacher_entropy"], out
+    assert abs(out[4]["loss_last"] - out[0]["loss_last"]) <= 0.02 * out[0]["loss_last"], out
