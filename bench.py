@@ -181,7 +181,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="index into BASELINE.json configs (single-table ones)")
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 0..4 (2 = the headline workload: 100 slots, 2^26 rows, fp32 D=64)")
     ap.add_argument("--distinct-batches", type=int, default=4, help="synthetic batches generated and cycled")
     ap.add_argument("--overlap", action="store_true",
                     help="staleness-1 schedule: lookup(t+1) on a second stream while update(t) runs on the first")
