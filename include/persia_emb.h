@@ -242,6 +242,26 @@ int hyb_read_losses(hyb_ctx* ctx, uint64_t first, uint64_t count, float* losses)
 int hyb_destroy(hyb_ctx* ctx); /* synchronous; does not destroy emb or mlp */
 const char* hyb_last_error(hyb_ctx* ctx); /* ctx == NULL: the last failed hyb_create */
 
+/* ---- tables larger than device memory (section 4.2.2: the parameter server holds the embedding parameters
+ * in an LRU cache -- an array list plus a hash map whose links are indices) --------------------------------
+ * emb_create_cached is emb_create with cache_rows[t] (host, [num_tables]): 0, or a value >= rows, keeps table
+ * t wholly in device memory; otherwise the table (rows and optimizer state) lives in pinned host memory and
+ * cache_rows[t] slots of device memory hold the rows in use.  Every emb_lookup_pool and emb_backward_update
+ * first brings the batch's rows in; a missing row replaces the least recently used slot (recency = the last
+ * call that touched the row; ties, and everything idle for 1022 calls or more, in slot order), whose row is
+ * written back to the host table first.  Results are those of a resident table, bit for bit.  Rule:
+ * cache_rows[t] >= min(rows, max_ids), so that any batch fits at once.  emb_read_rows / emb_write_rows see a
+ * row wherever it currently is.  Calls on such a context must not overlap (the cache is shared state), and in
+ * it emb_lookup_pool builds the index form too (so emb_read_dedup then describes the looked-up batch).
+ * emb_cache_stats: stats[0] rows requested (unique per call), [1] of those not in the cache, [2] rows written
+ *   back, [3] calls that found fewer replaceable slots than missing rows (0 under the rule above); synchronous.
+ * emb_cache_where: where_host[r] = slot of row r or -1 (host, [rows]; synchronous; for tests).
+ * emb_cache_flush: writes every cached row back to the host table (the cache stays valid); enqueue-only. */
+int emb_create_cached(const emb_config* cfg, const uint64_t* cache_rows, emb_ctx** out);
+int emb_cache_stats(emb_ctx* ctx, uint32_t table, uint64_t* stats);
+int emb_cache_where(emb_ctx* ctx, uint32_t table, int32_t* where_host);
+int emb_cache_flush(emb_ctx* ctx, void* hip_stream);
+
 /* Shapes and limits a context was created with (any pointer may be NULL). */
 int emb_describe(emb_ctx* ctx, uint32_t* num_slots, uint32_t* pooled_width, uint32_t* max_batch, uint64_t* max_ids,
                  int32_t* device);

@@ -69,6 +69,12 @@ def load_library() -> C.CDLL:
     vp, u32, u64, i32 = C.c_void_p, C.c_uint32, C.c_uint64, C.c_int
     L.emb_create.argtypes = [C.POINTER(emb_config), C.POINTER(vp)]
     L.emb_destroy.argtypes = [vp]
+    L.emb_create_cached.argtypes = [C.POINTER(emb_config), vp, C.POINTER(vp)]
+    L.emb_cache_stats.argtypes = [vp, u32, vp]
+    L.emb_cache_where.argtypes = [vp, u32, vp]
+    L.emb_cache_flush.argtypes = [vp, vp]
+    for name in ("emb_create_cached", "emb_cache_stats", "emb_cache_where", "emb_cache_flush"):
+        getattr(L, name).restype = C.c_int
     L.emb_lookup_pool.argtypes = [vp, C.POINTER(emb_batch), vp, vp]
     L.emb_hash_rows.argtypes = [vp, C.POINTER(emb_batch), vp, vp]
     L.emb_backward_update.argtypes = [vp, C.POINTER(emb_batch), vp, vp]
@@ -151,7 +157,9 @@ class EmbContext:
 
     def __init__(self, tables: Sequence[Tuple[int, int, int]], slots: Sequence[Tuple[int, int]], hash_kind: int,
                  opt: int, lr: float, eps: float, acc_init: float, init_seed: int, init_lo: float, init_hi: float,
-                 max_batch: int, max_ids: int, device: int = 0):
+                 max_batch: int, max_ids: int, device: int = 0, cache_rows: Optional[Sequence[int]] = None):
+        """cache_rows (optional, one entry per table): device-memory slots of a table kept in host memory behind
+        the LRU cache (emb_create_cached); 0 keeps the table resident."""
         self.L = load_library()
         self.tables = [tuple(t) for t in tables]
         self.slots = [tuple(s) for s in slots]
@@ -161,7 +169,12 @@ class EmbContext:
         cfg = emb_config(len(tables), len(slots), self._t, self._s, hash_kind, opt, lr, eps, acc_init, init_lo, init_hi,
                          device, init_seed, max_ids, max_batch, 0)
         h = C.c_void_p()
-        rc = self.L.emb_create(C.byref(cfg), C.byref(h))
+        if cache_rows is None:
+            rc = self.L.emb_create(C.byref(cfg), C.byref(h))
+        else:
+            assert len(cache_rows) == len(tables)
+            cr = (C.c_uint64 * len(tables))(*[int(c) for c in cache_rows])
+            rc = self.L.emb_create_cached(C.byref(cfg), cr, C.byref(h))
         if rc:
             raise EmbError(rc, self.L.emb_last_error(None).decode())
         self.h = h
@@ -169,11 +182,11 @@ class EmbContext:
         self.width = sum(self.tables[t][1] for t, _ in slots)
 
     @classmethod
-    def from_config(cls, cfg, max_batch: int, max_ids: int, device: int = 0):
+    def from_config(cls, cfg, max_batch: int, max_ids: int, device: int = 0, cache_rows=None):
         """cfg: workload.EmbConfig (duck-typed)."""
         return cls([(t.rows, t.dim, t.dtype) for t in cfg.tables], [(s.table, s.salt) for s in cfg.slots],
                    cfg.hash_kind, cfg.opt, cfg.lr, cfg.eps, cfg.acc_init, cfg.init_seed, cfg.init_lo, cfg.init_hi,
-                   max_batch, max_ids, device)
+                   max_batch, max_ids, device, cache_rows=cache_rows)
 
     def _ck(self, rc: int):
         if rc:
@@ -239,6 +252,19 @@ class EmbContext:
             acc = np.ascontiguousarray(acc, dtype=np.float32)
             ap = acc.ctypes.data
         self._ck(self.L.emb_write_rows(self.h, table, rows.ctypes.data, len(rows), w.ctypes.data, ap))
+
+    def emb_cache_stats(self, table: int) -> dict:
+        st = (C.c_uint64 * 4)()
+        self._ck(self.L.emb_cache_stats(self.h, table, st))
+        return {"requested": st[0], "misses": st[1], "written_back": st[2], "overflows": st[3]}
+
+    def emb_cache_where(self, table: int) -> np.ndarray:
+        out = np.empty(self.tables[table][0], dtype=np.int32)
+        self._ck(self.L.emb_cache_where(self.h, table, out.ctypes.data))
+        return out
+
+    def emb_cache_flush(self, stream=None) -> None:
+        self._ck(self.L.emb_cache_flush(self.h, _stream_ptr(stream)))
 
     def emb_table_ptr(self, table: int) -> Tuple[int, int]:
         w, a = C.c_void_p(), C.c_void_p()

@@ -62,6 +62,14 @@ struct emb_ctx {
   uint32_t *counters = nullptr, *ranges = nullptr;
   float* partials = nullptr;
   uint32_t *tile_key[2] = {nullptr, nullptr}, *tile_val[2] = {nullptr, nullptr};
+  // tables kept in host memory behind an LRU cache (emb_create_cached); lru[t].C == 0: table t is resident
+  std::vector<LruView> lru;
+  std::vector<uint64_t*> lru_stats;   // device [4] per cached table
+  LruScratch lru_scratch{};
+  uint32_t* unique_slots = nullptr;   // unique keys with rows replaced by cache slots
+  uint32_t lru_step = 0;              // one step per admission (every lookup and every update is a use)
+  bool any_cached = false;
+  std::vector<void*> host_allocs;
   // last backward
   int sorted_buf = 0;
   uint64_t last_n = 0;
@@ -111,9 +119,24 @@ hipError_t dev_upload(emb_ctx* ctx, T** p, const std::vector<T>& v) {
   return e;
 }
 
+// Pinned host memory the device can address; *dev receives the device-side pointer.
+template <typename T>
+hipError_t host_alloc(emb_ctx* ctx, T** dev, uint64_t count) {
+  void *h = nullptr, *d = nullptr;
+  hipError_t e = hipHostMalloc(&h, (count ? count : 1) * sizeof(T), hipHostMallocMapped);
+  if (e != hipSuccess) return e;
+  ctx->host_allocs.push_back(h);
+  e = hipHostGetDevicePointer(&d, h, 0);
+  if (e != hipSuccess) return e;
+  *dev = reinterpret_cast<T*>(d);
+  return hipSuccess;
+}
+
 void free_all(emb_ctx* ctx) {
   for (void* p : ctx->allocs) (void)hipFree(p);
   ctx->allocs.clear();
+  for (void* p : ctx->host_allocs) (void)hipHostFree(p);
+  ctx->host_allocs.clear();
   for (auto& r : ctx->recs) {
     (void)hipEventDestroy(r.e0);
     (void)hipEventDestroy(r.e1);
@@ -193,7 +216,7 @@ int bit_length(uint64_t v) {
 
 extern "C" {
 
-static int emb_create_impl(const emb_config* cfg, emb_ctx** out) {
+static int emb_create_impl(const emb_config* cfg, const uint64_t* cache_rows, emb_ctx** out) {
   if (!cfg || !out) return fail(nullptr, EMB_EINVAL, "null argument");
   if (cfg->num_tables == 0 || cfg->num_tables > 1023 || !cfg->tables)
     return fail(nullptr, EMB_EINVAL, "num_tables must be in 1..1023");
@@ -223,6 +246,11 @@ static int emb_create_impl(const emb_config* cfg, emb_ctx** out) {
     total_rows += d.rows;
     if (total_rows >= (1ull << 31)) return fail(nullptr, EMB_EINVAL, "sum of table rows must be < 2^31");
     if (d.dim > max_dim) max_dim = d.dim;
+    if (cache_rows && cache_rows[t] != 0 && cache_rows[t] < d.rows) {
+      // a batch's rows must all fit at once, whatever was cached before
+      const uint64_t need = d.rows < cfg->max_ids ? d.rows : cfg->max_ids;
+      if (cache_rows[t] < need) return fail(nullptr, EMB_EINVAL, "cache_rows must be at least min(rows, max_ids)");
+    }
   }
   for (uint32_t s = 0; s < cfg->num_slots; ++s) {
     if (cfg->slots[s].table >= cfg->num_tables) return fail(nullptr, EMB_EINVAL, "slot refers to a missing table");
@@ -269,6 +297,8 @@ static int emb_create_impl(const emb_config* cfg, emb_ctx** out) {
   std::vector<uint32_t> s_kb(ctx->S), s_col(ctx->S);
   ctx->tables.resize(cfg->num_tables);
   ctx->key_base_host.resize(cfg->num_tables);
+  ctx->lru.assign(cfg->num_tables, LruView{});
+  ctx->lru_stats.assign(cfg->num_tables, nullptr);
   uint32_t kb = 0;
   for (uint32_t t = 0; t < cfg->num_tables; ++t) {
     const emb_table_desc& d = cfg->tables[t];
@@ -281,7 +311,9 @@ static int emb_create_impl(const emb_config* cfg, emb_ctx** out) {
     tv.key_base = kb;
     ctx->key_base_host[t] = kb;
     kb += (uint32_t)d.rows;
-    const uint64_t elems = d.rows * d.dim;
+    const bool cached = cache_rows && cache_rows[t] != 0 && cache_rows[t] < d.rows;
+    const uint64_t held = cached ? cache_rows[t] : d.rows;  // rows in device memory
+    const uint64_t elems = held * d.dim;
     if (d.dtype == EMB_BF16) {
       bf16_t* p = nullptr;
       CK(dev_alloc(ctx, &p, elems), "hipMalloc(table)");
@@ -291,7 +323,37 @@ static int emb_create_impl(const emb_config* cfg, emb_ctx** out) {
       CK(dev_alloc(ctx, &p, elems), "hipMalloc(table)");
       tv.w = p;
     }
-    CK(dev_alloc(ctx, &tv.acc, d.rows), "hipMalloc(optimizer state)");
+    CK(dev_alloc(ctx, &tv.acc, held), "hipMalloc(optimizer state)");
+    LruView& lv = ctx->lru[t];
+    if (cached) {
+      ctx->any_cached = true;
+      if (d.dtype == EMB_BF16) {
+        bf16_t* p = nullptr;
+        CK(host_alloc(ctx, &p, d.rows * d.dim), "hipHostMalloc(table)");
+        tv.back_w = p;
+      } else {
+        float* p = nullptr;
+        CK(host_alloc(ctx, &p, d.rows * d.dim), "hipHostMalloc(table)");
+        tv.back_w = p;
+      }
+      CK(host_alloc(ctx, &tv.back_acc, d.rows), "hipHostMalloc(optimizer state)");
+      lv.C = (uint32_t)held;
+      lv.dim = d.dim;
+      lv.dtype = d.dtype;
+      lv.key_base = tv.key_base;
+      lv.rows = d.rows;
+      lv.cache_w = tv.w;
+      lv.cache_acc = tv.acc;
+      lv.back_w = tv.back_w;
+      lv.back_acc = tv.back_acc;
+      CK(dev_alloc(ctx, &lv.where, d.rows), "hipMalloc(row -> slot map)");
+      CK(dev_alloc(ctx, &lv.slot_row, held), "hipMalloc(slot rows)");
+      CK(dev_alloc(ctx, &lv.stamp, held), "hipMalloc(slot stamps)");
+      tv.where = lv.where;
+      CK(launch_lru_init(lv, nullptr), "lru_init");
+      CK(dev_alloc(ctx, &ctx->lru_stats[t], 4), "hipMalloc(cache statistics)");
+      CK(hipMemset(ctx->lru_stats[t], 0, 4 * sizeof(uint64_t)), "hipMemset(cache statistics)");
+    }
     std::vector<uint32_t> list;
     for (uint32_t s = 0; s < ctx->S; ++s)
       if (cfg->slots[s].table == t) list.push_back(s);
@@ -302,7 +364,14 @@ static int emb_create_impl(const emb_config* cfg, emb_ctx** out) {
     const uint64_t table_key = mix64(cfg->init_seed + (uint64_t)(t + 1) * 0x9E3779B97F4A7C15ull);
     const float scale = (cfg->init_hi - cfg->init_lo) * 5.9604644775390625e-08f;
     const float mid = (cfg->init_hi + cfg->init_lo) * 0.5f;
-    CK(launch_init_table(tv, table_key, scale, mid, cfg->acc_init, nullptr), "init_table");
+    if (cached) {  // the whole table is initialised where it lives: in host memory
+      TableView whole = tv;
+      whole.w = tv.back_w;
+      whole.acc = tv.back_acc;
+      CK(launch_init_table(whole, table_key, scale, mid, cfg->acc_init, nullptr), "init_table");
+    } else {
+      CK(launch_init_table(tv, table_key, scale, mid, cfg->acc_init, nullptr), "init_table");
+    }
   }
   uint32_t col = 0;
   for (uint32_t s = 0; s < ctx->S; ++s) {
@@ -353,6 +422,19 @@ static int emb_create_impl(const emb_config* cfg, emb_ctx** out) {
     CK(dev_alloc(ctx, &ctx->tile_val[i], ntiles), "hipMalloc(tile order)");
   }
 
+  if (ctx->any_cached) {
+    uint64_t max_c = 0;
+    for (const LruView& v : ctx->lru) max_c = v.C > max_c ? v.C : max_c;
+    const uint64_t big = max_c > cap ? max_c : cap;
+    CK(dev_alloc(ctx, &ctx->lru_scratch.blk_counts, big / 2048 + 2), "hipMalloc(cache scan counts)");
+    CK(dev_alloc(ctx, &ctx->lru_scratch.miss_list, cap), "hipMalloc(cache miss list)");
+    CK(dev_alloc(ctx, &ctx->lru_scratch.victims, cap), "hipMalloc(cache victim list)");
+    CK(dev_alloc(ctx, &ctx->lru_scratch.age_hist, kAgeMax + 1), "hipMalloc(cache age histogram)");
+    CK(dev_alloc(ctx, &ctx->lru_scratch.plan, 8), "hipMalloc(cache plan)");
+    CK(dev_alloc(ctx, &ctx->lru_scratch.evicted, 1), "hipMalloc(cache eviction counter)");
+    CK(hipMemset(ctx->lru_scratch.evicted, 0, sizeof(uint32_t)), "hipMemset(cache eviction counter)");
+    CK(dev_alloc(ctx, &ctx->unique_slots, cap), "hipMalloc(unique slots)");
+  }
   CK(hipDeviceSynchronize(), "table initialisation");
 #undef CK
   guard.c = nullptr;
@@ -375,47 +457,14 @@ int emb_destroy(emb_ctx* ctx) {
     if (_e != hipSuccess) return fail_hip(ctx, what, _e);    \
   } while (0)
 
-static int emb_lookup_pool_impl(emb_ctx* ctx, const emb_batch* batch, float* pooled, void* hip_stream) {
-  int rc = check_batch(ctx, batch);
-  if (rc) return rc;
-  if (batch->batch_size == 0) return EMB_OK;
-  if (!pooled) return fail(ctx, EMB_EINVAL, "null pooled output");
-  hipStream_t stream = (hipStream_t)hip_stream;
-  CKH(hipSetDevice(ctx->device), "hipSetDevice");
-  for (const TableView& tv : ctx->tables) {
-    StageTimer tm(ctx, ST_GATHER_POOL, stream);
-    CKH(launch_gather_pool(tv, ctx->slots, batch->ids, batch->offsets, batch->batch_size, ctx->S, ctx->width,
-                           ctx->mix, pooled, stream),
-        "gather_pool");
-  }
-  return EMB_OK;
-}
-
-static int emb_hash_rows_impl(emb_ctx* ctx, const emb_batch* batch, uint32_t* rows_out, void* hip_stream) {
-  int rc = check_batch(ctx, batch);
-  if (rc) return rc;
-  if (batch->num_ids == 0) return EMB_OK;
-  if (!rows_out) return fail(ctx, EMB_EINVAL, "null rows output");
-  hipStream_t stream = (hipStream_t)hip_stream;
-  CKH(hipSetDevice(ctx->device), "hipSetDevice");
-  CKH(launch_build_keys(ctx->slots, batch->ids, batch->offsets, batch->batch_size, ctx->S, ctx->mix, 1, rows_out,
-                        nullptr, stream),
-      "hash_rows");
-  return EMB_OK;
-}
-
-static int emb_backward_update_impl(emb_ctx* ctx, const emb_batch* batch, const float* d_pooled, void* hip_stream) {
-  int rc = check_batch(ctx, batch);
-  if (rc) return rc;
-  if (!workspace_complete(ctx)) return fail(ctx, EMB_ESTATE, "workspace is incomplete (a buffer is null)");
-  if (batch->batch_size && !d_pooled) return fail(ctx, EMB_EINVAL, "null d_pooled");
-  hipStream_t stream = (hipStream_t)hip_stream;
-  CKH(hipSetDevice(ctx->device), "hipSetDevice");
+// The index form of the batch (section 4.2.3): keys built, sorted (stable LSD radix) and run-length encoded.
+// Leaves the sorted pairs in keys/bags[ctx->sorted_buf] and unique_keys / seg_off / counters filled.
+static int run_dedup(emb_ctx* ctx, const emb_batch* batch, hipStream_t stream) {
   const uint32_t n = (uint32_t)batch->num_ids;
   ctx->last_n = n;
   ctx->have_dedup = true;
   ctx->sorted_buf = 0;
-  if (n == 0) {  // nothing to update; leave an empty index form behind
+  if (n == 0) {  // leave an empty index form behind
     CKH(launch_unique(ctx->keys[0], 0, ctx->blk_heads, ctx->blk_multi, ctx->unique_keys, ctx->seg_off,
                       ctx->multi_list, ctx->counters, stream),
         "unique");
@@ -454,8 +503,92 @@ static int emb_backward_update_impl(emb_ctx* ctx, const emb_batch* batch, const 
                       ctx->multi_list, ctx->counters, stream),
         "unique");
   }
+  return EMB_OK;
+}
+
+// Makes every row of the batch just deduplicated resident in its table's cache (one LRU step per call).
+static int admit_batch(emb_ctx* ctx, hipStream_t stream) {
+  if (!ctx->any_cached || ctx->last_n == 0) return EMB_OK;
+  ++ctx->lru_step;
+  for (size_t t = 0; t < ctx->lru.size(); ++t) {
+    if (ctx->lru[t].C == 0) continue;
+    LruScratch sc = ctx->lru_scratch;
+    sc.stats = ctx->lru_stats[t];
+    CKH(launch_lru_admit(ctx->lru[t], sc, ctx->unique_keys, ctx->counters, (uint32_t)ctx->last_n, ctx->lru_step, stream),
+        "lru_admit");
+  }
+  return EMB_OK;
+}
+
+static int emb_lookup_pool_impl(emb_ctx* ctx, const emb_batch* batch, float* pooled, void* hip_stream) {
+  int rc = check_batch(ctx, batch);
+  if (rc) return rc;
+  if (batch->batch_size == 0) return EMB_OK;
+  if (!pooled) return fail(ctx, EMB_EINVAL, "null pooled output");
+  hipStream_t stream = (hipStream_t)hip_stream;
+  CKH(hipSetDevice(ctx->device), "hipSetDevice");
+  if (ctx->any_cached) {  // the rows must be in the cache before they are gathered
+    if (!workspace_complete(ctx)) return fail(ctx, EMB_ESTATE, "workspace is incomplete (a buffer is null)");
+    if ((rc = run_dedup(ctx, batch, stream)) != EMB_OK) return rc;
+    if ((rc = admit_batch(ctx, stream)) != EMB_OK) return rc;
+  }
+  for (const TableView& tv : ctx->tables) {
+    StageTimer tm(ctx, ST_GATHER_POOL, stream);
+    CKH(launch_gather_pool(tv, ctx->slots, batch->ids, batch->offsets, batch->batch_size, ctx->S, ctx->width,
+                           ctx->mix, pooled, stream),
+        "gather_pool");
+  }
+  return EMB_OK;
+}
+
+static int emb_hash_rows_impl(emb_ctx* ctx, const emb_batch* batch, uint32_t* rows_out, void* hip_stream) {
+  int rc = check_batch(ctx, batch);
+  if (rc) return rc;
+  if (batch->num_ids == 0) return EMB_OK;
+  if (!rows_out) return fail(ctx, EMB_EINVAL, "null rows output");
+  hipStream_t stream = (hipStream_t)hip_stream;
+  CKH(hipSetDevice(ctx->device), "hipSetDevice");
+  CKH(launch_build_keys(ctx->slots, batch->ids, batch->offsets, batch->batch_size, ctx->S, ctx->mix, 1, rows_out,
+                        nullptr, stream),
+      "hash_rows");
+  return EMB_OK;
+}
+
+static int emb_backward_update_impl(emb_ctx* ctx, const emb_batch* batch, const float* d_pooled, void* hip_stream) {
+  int rc = check_batch(ctx, batch);
+  if (rc) return rc;
+  if (!workspace_complete(ctx)) return fail(ctx, EMB_ESTATE, "workspace is incomplete (a buffer is null)");
+  if (batch->batch_size && !d_pooled) return fail(ctx, EMB_EINVAL, "null d_pooled");
+  hipStream_t stream = (hipStream_t)hip_stream;
+  CKH(hipSetDevice(ctx->device), "hipSetDevice");
+  const uint32_t n = (uint32_t)batch->num_ids;
+  if ((rc = run_dedup(ctx, batch, stream)) != EMB_OK) return rc;
+  if (n == 0) return EMB_OK;  // nothing to update
+  const int src = ctx->sorted_buf;
+  const bool multi_table = ctx->tables.size() > 1;
+  if (multi_table)  // each table's stretch of the sorted list (found before any key is rewritten below)
+    CKH(launch_table_ranges(ctx->keys[src], n, ctx->key_base_dev, (uint32_t)ctx->tables.size(), ctx->ranges, stream),
+        "table_ranges");
+  const uint32_t* sorted_keys = ctx->keys[src];
+  const uint32_t* unique_keys = ctx->unique_keys;
+  if (ctx->any_cached) {
+    // rows that were evicted since the lookup come back; then the kernels below address cache slots: they
+    // only compare neighbouring keys for equality, and key_base + slot stays inside the table's key range
+    if ((rc = admit_batch(ctx, stream)) != EMB_OK) return rc;
+    uint32_t* tk = ctx->keys[src ^ 1];
+    CKH(hipMemcpyAsync(tk, ctx->keys[src], (size_t)n * sizeof(uint32_t), hipMemcpyDeviceToDevice, stream), "copy(keys)");
+    CKH(hipMemcpyAsync(ctx->unique_slots, ctx->unique_keys, (size_t)n * sizeof(uint32_t), hipMemcpyDeviceToDevice, stream),
+        "copy(unique keys)");
+    for (size_t t = 0; t < ctx->lru.size(); ++t) {
+      if (ctx->lru[t].C == 0) continue;
+      CKH(launch_lru_translate(ctx->lru[t], tk, multi_table ? ctx->ranges + t : nullptr, nullptr, n, stream), "lru_translate");
+      CKH(launch_lru_translate(ctx->lru[t], ctx->unique_slots, nullptr, ctx->counters, n, stream), "lru_translate");
+    }
+    sorted_keys = tk;
+    unique_keys = ctx->unique_slots;
+  }
   BackwardArgs a{};
-  a.keys = ctx->keys[src];
+  a.keys = sorted_keys;
   a.bags = ctx->bags[src];
   a.n = n;
   a.d_pooled = d_pooled;
@@ -470,7 +603,7 @@ static int emb_backward_update_impl(emb_ctx* ctx, const emb_batch* batch, const 
   a.opt = ctx->opt;
   a.lr = ctx->lr;
   a.eps = ctx->eps;
-  a.unique_keys = ctx->unique_keys;
+  a.unique_keys = unique_keys;
   a.seg_off = ctx->seg_off;
   a.counters = ctx->counters;
   a.multi_list = ctx->multi_list;
@@ -484,10 +617,6 @@ static int emb_backward_update_impl(emb_ctx* ctx, const emb_batch* batch, const 
                           ctx->tile_val, ctx->hist, ctx->total, &a.tile_perm, stream),
         "tile_order");
   }
-  const bool multi_table = ctx->tables.size() > 1;
-  if (multi_table)
-    CKH(launch_table_ranges(a.keys, n, ctx->key_base_dev, (uint32_t)ctx->tables.size(), ctx->ranges, stream),
-        "table_ranges");
   for (size_t t = 0; t < ctx->tables.size(); ++t) {
     StageTimer tm(ctx, ST_REDUCE_UPDATE, stream);
     a.range = multi_table ? ctx->ranges + t : nullptr;
@@ -596,8 +725,38 @@ static int emb_write_rows_impl(emb_ctx* ctx, uint32_t table, const uint64_t* row
 int emb_table_ptr(emb_ctx* ctx, uint32_t table, void** w_dev, float** acc_dev) {
   if (!ctx) return fail(nullptr, EMB_EINVAL, "null context");
   if (table >= ctx->tables.size()) return fail(ctx, EMB_EINVAL, "no such table");
+  if (ctx->lru[table].C) return fail(ctx, EMB_ESTATE, "the table is kept in host memory behind a cache: no flat device array");
   if (w_dev) *w_dev = ctx->tables[table].w;
   if (acc_dev) *acc_dev = ctx->tables[table].acc;
+  return EMB_OK;
+}
+
+static int emb_cache_stats_impl(emb_ctx* ctx, uint32_t table, uint64_t* stats) {
+  if (!ctx) return fail(nullptr, EMB_EINVAL, "null context");
+  if (table >= ctx->tables.size() || !stats) return fail(ctx, EMB_EINVAL, "no such table, or null output");
+  if (ctx->lru[table].C == 0) return fail(ctx, EMB_ESTATE, "the table is resident, it has no cache");
+  CKH(hipSetDevice(ctx->device), "hipSetDevice");
+  CKH(hipDeviceSynchronize(), "hipDeviceSynchronize");
+  CKH(hipMemcpy(stats, ctx->lru_stats[table], 4 * sizeof(uint64_t), hipMemcpyDeviceToHost), "hipMemcpy(cache statistics)");
+  return EMB_OK;
+}
+
+static int emb_cache_where_impl(emb_ctx* ctx, uint32_t table, int32_t* where_host) {
+  if (!ctx) return fail(nullptr, EMB_EINVAL, "null context");
+  if (table >= ctx->tables.size() || !where_host) return fail(ctx, EMB_EINVAL, "no such table, or null output");
+  if (ctx->lru[table].C == 0) return fail(ctx, EMB_ESTATE, "the table is resident, it has no cache");
+  CKH(hipSetDevice(ctx->device), "hipSetDevice");
+  CKH(hipDeviceSynchronize(), "hipDeviceSynchronize");
+  CKH(hipMemcpy(where_host, ctx->lru[table].where, ctx->lru[table].rows * sizeof(int32_t), hipMemcpyDeviceToHost),
+      "hipMemcpy(row -> slot map)");
+  return EMB_OK;
+}
+
+static int emb_cache_flush_impl(emb_ctx* ctx, void* hip_stream) {
+  if (!ctx) return fail(nullptr, EMB_EINVAL, "null context");
+  CKH(hipSetDevice(ctx->device), "hipSetDevice");
+  for (const LruView& v : ctx->lru)
+    if (v.C) CKH(launch_lru_flush(v, (hipStream_t)hip_stream), "lru_flush");
   return EMB_OK;
 }
 
@@ -660,7 +819,11 @@ static int emb_reset_stage_ms_impl(emb_ctx* ctx) {
     return fail(ctx_expr, EMB_ESTATE, "unexpected exception inside the library");  \
   }
 
-int emb_create(const emb_config* cfg, emb_ctx** out) { PEMB_GUARDED(nullptr, emb_create_impl(cfg, out)) }
+int emb_create(const emb_config* cfg, emb_ctx** out) { PEMB_GUARDED(nullptr, emb_create_impl(cfg, nullptr, out)) }
+int emb_create_cached(const emb_config* cfg, const uint64_t* cache_rows, emb_ctx** out) { PEMB_GUARDED(nullptr, emb_create_impl(cfg, cache_rows, out)) }
+int emb_cache_stats(emb_ctx* ctx, uint32_t table, uint64_t* stats) { PEMB_GUARDED(ctx, emb_cache_stats_impl(ctx, table, stats)) }
+int emb_cache_where(emb_ctx* ctx, uint32_t table, int32_t* where_host) { PEMB_GUARDED(ctx, emb_cache_where_impl(ctx, table, where_host)) }
+int emb_cache_flush(emb_ctx* ctx, void* hip_stream) { PEMB_GUARDED(ctx, emb_cache_flush_impl(ctx, hip_stream)) }
 int emb_lookup_pool(emb_ctx* ctx, const emb_batch* batch, float* pooled, void* hip_stream) { PEMB_GUARDED(ctx, emb_lookup_pool_impl(ctx, batch, pooled, hip_stream)) }
 int emb_hash_rows(emb_ctx* ctx, const emb_batch* batch, uint32_t* rows_out, void* hip_stream) { PEMB_GUARDED(ctx, emb_hash_rows_impl(ctx, batch, rows_out, hip_stream)) }
 int emb_backward_update(emb_ctx* ctx, const emb_batch* batch, const float* d_pooled, void* hip_stream) { PEMB_GUARDED(ctx, emb_backward_update_impl(ctx, batch, d_pooled, hip_stream)) }

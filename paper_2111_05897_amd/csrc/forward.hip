@@ -15,6 +15,7 @@ struct GatherArgs {
   const uint64_t* ids;
   const int32_t* offsets;
   const void* w;
+  const int32_t* where;        // null, or row -> cache slot for a table kept behind the LRU cache
   uint64_t rows, mask;
   const uint32_t* slot_list;   // slots reading this table
   const uint64_t* slot_salt;   // indexed by slot
@@ -86,7 +87,12 @@ __global__ __launch_bounds__(kBlock) void k_gather_pool(GatherArgs a) {
 #pragma unroll
     for (int q = 0; q < IPL; ++q) {
       const int idx = cbase + q * LANES + lane;
-      myrow[q] = idx < end ? hash_row(ids[idx], salt, a.rows, a.mask, a.mix) : 0u;
+      uint32_t r = idx < end ? hash_row(ids[idx], salt, a.rows, a.mask, a.mix) : 0u;
+      if (a.where) {  // table behind the LRU cache: the row's slot (every row of the batch was admitted)
+        const int32_t slot = idx < end ? a.where[r] : 0;
+        r = slot >= 0 ? (uint32_t)slot : 0u;
+      }
+      myrow[q] = r;
     }
 #pragma unroll
     for (int j0 = 0; j0 < CH; j0 += RIF) {
@@ -165,6 +171,7 @@ hipError_t launch_gather_pool(const TableView& t, const SlotArrays& sl, const ui
   a.ids = ids;
   a.offsets = offsets;
   a.w = t.w;
+  a.where = t.where;
   a.rows = t.rows;
   a.mask = t.mask;
   a.slot_list = t.slot_list;

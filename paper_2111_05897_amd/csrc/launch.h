@@ -24,7 +24,48 @@ struct TableView {
   uint32_t key_base;  // first global row index of the table (sort keys are key_base + row)
   uint32_t n_slots;   // slots reading this table
   const uint32_t* slot_list;  // device, [n_slots] slot indices, ascending
+  // A table kept in host memory behind an LRU cache (else all null): w / acc above are then the cache's slot
+  // arrays, where[row] is the slot holding a row or -1, back_w / back_acc the whole table in host memory.
+  const int32_t* where;
+  void* back_w;
+  float* back_acc;
 };
+
+// ---- lru.hip: least-recently-used cache in HBM over a table in pinned host memory ----
+constexpr uint32_t kAgeMax = 1023;            // recency is exact up to kAgeMax - 2 steps back; kAgeMax = an empty slot
+constexpr uint32_t kEmptySlot = 0xFFFFFFFFu;  // slot_row value of a slot that holds nothing
+struct LruView {
+  int32_t* where;       // [rows] slot of a row, or -1
+  uint32_t* slot_row;   // [C] row held by a slot, or kEmptySlot
+  uint32_t* stamp;      // [C] step number of the slot's last use
+  void* cache_w;        // [C, dim]
+  float* cache_acc;     // [C]
+  void* back_w;         // [rows, dim], host memory mapped into the device
+  float* back_acc;      // [rows]
+  uint32_t C, dim;
+  int32_t dtype;
+  uint32_t key_base;
+  uint64_t rows;
+};
+struct LruScratch {       // shared by the cached tables of a context, used by one admission at a time
+  uint32_t* blk_counts;   // [max(C, max_unique) / 2048 + 1]
+  uint32_t* miss_list;    // [max_unique] rows to bring in, ascending
+  uint32_t* victims;      // [max_unique] slots to replace
+  uint32_t* age_hist;     // [kAgeMax + 1]
+  uint32_t* plan;         // [8]
+  uint32_t* evicted;      // [1]
+  uint64_t* stats;        // [4] of the table being admitted: rows seen, misses, evictions, overflows
+};
+hipError_t launch_lru_init(const LruView& v, hipStream_t stream);
+// Makes every row of unique_keys[0 .. counters[0]) that belongs to the table resident: hits are stamped with
+// `step`, misses replace the least recently used slots (written back to the host table first).
+hipError_t launch_lru_admit(const LruView& v, const LruScratch& s, const uint32_t* unique_keys, const uint32_t* counters,
+                            uint32_t max_unique, uint32_t step, hipStream_t stream);
+// keys[i] = key_base + slot of the row, for the table's elements in [range[0], range[1]) (range null: in
+// [0, count[0]) or, with count null too, in [0, n_max)).
+hipError_t launch_lru_translate(const LruView& v, uint32_t* keys, const uint32_t* range, const uint32_t* count,
+                                uint32_t n_max, hipStream_t stream);
+hipError_t launch_lru_flush(const LruView& v, hipStream_t stream);
 
 // Per-slot arrays, device, [S] each.
 struct SlotArrays {

@@ -25,15 +25,24 @@ __global__ __launch_bounds__(kBlock) void k_fill_f32(float* __restrict__ p, uint
   for (; i < n; i += stride) p[i] = v;
 }
 
+// For a table behind the LRU cache (`where` not null) a row is in its cache slot if it has one, else in the
+// host table.
 template <typename T>
 __global__ __launch_bounds__(kBlock) void k_read_rows(const T* __restrict__ w, const float* __restrict__ acc,
                                                       uint32_t dim, const uint64_t* __restrict__ rows, uint64_t n,
-                                                      float* __restrict__ w_out, float* __restrict__ acc_out) {
+                                                      float* __restrict__ w_out, float* __restrict__ acc_out,
+                                                      const int32_t* __restrict__ where, const T* __restrict__ back_w,
+                                                      const float* __restrict__ back_acc) {
   uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= n * dim) return;
   uint64_t r = i / dim;
   uint32_t d = (uint32_t)(i - r * dim);
   uint64_t row = rows[r];
+  if (where) {
+    const int32_t slot = where[row];
+    if (slot >= 0) row = (uint64_t)slot;
+    else w = back_w, acc = back_acc;
+  }
   if (w_out) {
     if constexpr (sizeof(T) == 2) w_out[i] = bf16_to_f32(w[row * dim + d]);
     else w_out[i] = w[row * dim + d];
@@ -45,12 +54,19 @@ template <typename T>
 __global__ __launch_bounds__(kBlock) void k_write_rows(T* __restrict__ w, float* __restrict__ acc, uint32_t dim,
                                                        const uint64_t* __restrict__ rows, uint64_t n,
                                                        const float* __restrict__ w_in,
-                                                       const float* __restrict__ acc_in) {
+                                                       const float* __restrict__ acc_in,
+                                                       const int32_t* __restrict__ where, T* __restrict__ back_w,
+                                                       float* __restrict__ back_acc) {
   uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i >= n * dim) return;
   uint64_t r = i / dim;
   uint32_t d = (uint32_t)(i - r * dim);
   uint64_t row = rows[r];
+  if (where) {
+    const int32_t slot = where[row];
+    if (slot >= 0) row = (uint64_t)slot;
+    else w = back_w, acc = back_acc;
+  }
   if (w_in) {
     if constexpr (sizeof(T) == 2) w[row * dim + d] = (bf16_t)f32_to_bf16(w_in[i]);
     else w[row * dim + d] = w_in[i];
@@ -88,11 +104,11 @@ hipError_t launch_read_rows(const TableView& t, const uint64_t* rows_dev, uint64
   if (n == 0) return hipSuccess;
   const uint32_t grid = (uint32_t)((n * t.dim + kBlock - 1) / kBlock);
   if (t.dtype == 1)
-    hipLaunchKernelGGL(k_read_rows<bf16_t>, dim3(grid), dim3(kBlock), 0, stream, (const bf16_t*)t.w, t.acc, t.dim,
-                       rows_dev, n, w_out, acc_out);
+    hipLaunchKernelGGL(k_read_rows<bf16_t>, dim3(grid), dim3(kBlock), 0, stream, (const bf16_t*)t.w, (const float*)t.acc,
+                       t.dim, rows_dev, n, w_out, acc_out, t.where, (const bf16_t*)t.back_w, (const float*)t.back_acc);
   else
-    hipLaunchKernelGGL(k_read_rows<float>, dim3(grid), dim3(kBlock), 0, stream, (const float*)t.w, t.acc, t.dim,
-                       rows_dev, n, w_out, acc_out);
+    hipLaunchKernelGGL(k_read_rows<float>, dim3(grid), dim3(kBlock), 0, stream, (const float*)t.w, (const float*)t.acc,
+                       t.dim, rows_dev, n, w_out, acc_out, t.where, (const float*)t.back_w, (const float*)t.back_acc);
   return hipGetLastError();
 }
 
@@ -102,10 +118,10 @@ hipError_t launch_write_rows(const TableView& t, const uint64_t* rows_dev, uint6
   const uint32_t grid = (uint32_t)((n * t.dim + kBlock - 1) / kBlock);
   if (t.dtype == 1)
     hipLaunchKernelGGL(k_write_rows<bf16_t>, dim3(grid), dim3(kBlock), 0, stream, (bf16_t*)t.w, t.acc, t.dim,
-                       rows_dev, n, w_in, acc_in);
+                       rows_dev, n, w_in, acc_in, t.where, (bf16_t*)t.back_w, t.back_acc);
   else
     hipLaunchKernelGGL(k_write_rows<float>, dim3(grid), dim3(kBlock), 0, stream, (float*)t.w, t.acc, t.dim, rows_dev,
-                       n, w_in, acc_in);
+                       n, w_in, acc_in, t.where, (float*)t.back_w, t.back_acc);
   return hipGetLastError();
 }
 

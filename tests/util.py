@@ -66,7 +66,8 @@ def sync_rows(ctx, orc, cfg, keys):
             ctx.emb_write_rows(t, r, ow, oa)
 
 
-def run_steps(binding, workload_mod, oracle_mod, w, steps=1, dense=None, batches=None, grads=None, check_hash=True):
+def run_steps(binding, workload_mod, oracle_mod, w, steps=1, dense=None, batches=None, grads=None, check_hash=True,
+              cache_rows=None):
     """Runs `steps` forward+backward steps of workload w on both sides and compares everything."""
     cfg = w.cfg
     if batches is None:
@@ -78,7 +79,7 @@ def run_steps(binding, workload_mod, oracle_mod, w, steps=1, dense=None, batches
     if dense is None:
         dense = sum(t.rows * t.dim for t in cfg.tables) <= (1 << 24)
     orc = oracle_mod.Oracle.from_config(cfg, dense=dense)
-    ctx = binding.EmbContext.from_config(cfg, max_batch=max(max_b, 1), max_ids=max_ids)
+    ctx = binding.EmbContext.from_config(cfg, max_batch=max(max_b, 1), max_ids=max_ids, cache_rows=cache_rows)
     import torch
     touched = []
     for b, dp in zip(batches, grads):
