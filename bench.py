@@ -191,6 +191,8 @@ def main() -> int:
                     help="full hybrid step: lookup -> dense MLP step (bf16 MFMA) -> embedding update with the MLP's gradient")
     ap.add_argument("--tau", type=int, default=None,
                     help="with --hybrid: run the library's step loop with this staleness (lookups tau batches ahead, second stream)")
+    ap.add_argument("--cache-frac", type=float, default=None,
+                    help="keep the tables in pinned host memory with this fraction of their rows cached in HBM (LRU)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device-to-device copies (reference for rocprofv3 byte counters)")
@@ -224,7 +226,13 @@ def main() -> int:
     for s in range(nb):
         gen.manual_seed(w.seed * 1000 + s)
         grads.append(torch.randn((w.batch, cfg.pooled_width), generator=gen, device="cuda", dtype=torch.float32))
-    ctx = binding.EmbContext.from_config(cfg, max_batch=w.batch, max_ids=max(b.num_ids for b in batches))
+    max_ids = max(b.num_ids for b in batches)
+    cache_rows = None
+    if args.cache_frac is not None:
+        # tables in pinned host memory, this fraction of their rows cached in HBM (at least one batch's worst case)
+        cache_rows = [max(min(t.rows, max_ids), int(args.cache_frac * t.rows)) for t in cfg.tables]
+        cache_rows = [c if c < t.rows else 0 for c, t in zip(cache_rows, cfg.tables)]
+    ctx = binding.EmbContext.from_config(cfg, max_batch=w.batch, max_ids=max_ids, cache_rows=cache_rows)
     pooled = torch.empty((w.batch, cfg.pooled_width), dtype=torch.float32, device="cuda")
     torch.cuda.synchronize()
     setup_s = time.time() - t0
@@ -286,6 +294,17 @@ def main() -> int:
         elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
     ids_per_s = ids_done / elapsed
+    cache_report = None
+    if cache_rows is not None and any(cache_rows):
+        cache_report = []
+        for t, c in enumerate(cache_rows):
+            if c:
+                st = ctx.emb_cache_stats(t)
+                row_bytes = cfg.tables[t].dim * e_of[t] + 4
+                cache_report.append({"table": t, "cache_rows": c, "rows": cfg.tables[t].rows, **st,
+                                     "hit_rate": round(1.0 - st["misses"] / max(st["requested"], 1), 4),
+                                     "host_link_bytes_per_step": round((st["misses"] + st["written_back"]) * row_bytes /
+                                                                       (args.warmup + args.steps))})
 
     # per-kernel timing pass (HIP events on the launch stream, inside the library)
     ctx.emb_set_profiling(True)
@@ -342,6 +361,8 @@ def main() -> int:
         "setup_s": round(setup_s, 1),
         "roofline": roofline,
     }
+    if cache_report is not None:
+        out["config"]["tables_in_host_memory"] = cache_report
 
     if not args.no_cpu_baseline:
         from oracle import oracle as O   # the checker, timed as a baseline only
