@@ -7,8 +7,9 @@ namespace pemb {
 
 // Occurrences per tile of the segmented reduce: one lane-group walks this many sorted occurrences.
 constexpr uint32_t kTile = 32;
-// Radix sort geometry: a block ranks and scatters tiles of 256 threads x 8 keys.
-constexpr uint32_t kSortTile = 2048;
+// Radix sort geometry: a block ranks and scatters tiles of 256 threads x 16 pairs (runs of one digit are
+// then long enough to be written as whole cache lines).
+constexpr uint32_t kSortTile = 4096;
 constexpr uint32_t kSortMaxBlocks = 2048;
 constexpr int kSortMaxBits = 9;                 // widest digit a pass may use (512 bins)
 constexpr uint32_t kUniqueTile = 2048;

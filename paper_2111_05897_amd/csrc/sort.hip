@@ -13,8 +13,10 @@
 namespace pemb {
 namespace {
 
-constexpr int kItems = 8;  // keys per thread per tile
-static_assert(kSortTile == kBlock * kItems, "tile geometry");
+constexpr int kItems = 8;  // keys per thread of a unique-kernel tile
+static_assert(kUniqueTile == kBlock * kItems, "tile geometry");
+constexpr int kSortItems = kSortTile / kBlock;  // pairs per thread of a scatter tile
+static_assert(kSortTile == kBlock * kSortItems, "tile geometry");
 
 constexpr int kHistThreads = 1024;  // the histogram is latency-bound: more waves per chunk than the scatter uses
 
@@ -140,17 +142,17 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(const uint32_t* __rest
     for (int i = tid; i < kWavesPerBlock * NB; i += kBlock) (&s_cnt[0][0])[i] = 0;
     __syncthreads();
 
-    uint32_t key[kItems], pay[kItems], lrank[kItems];
+    uint32_t key[kSortItems], pay[kSortItems], lrank[kSortItems];
 #pragma unroll
-    for (int k = 0; k < kItems; ++k) {
-      const uint32_t off = wave * (kWave * kItems) + k * kWave + lane;  // position inside the tile
+    for (int k = 0; k < kSortItems; ++k) {
+      const uint32_t off = wave * (kWave * kSortItems) + k * kWave + lane;  // position inside the tile
       const bool valid = off < tile_cnt;
       key[k] = valid ? kin[tile_base + off] : 0xFFFFFFFFu;
       pay[k] = valid ? pin[tile_base + off] : 0u;
     }
 #pragma unroll
-    for (int k = 0; k < kItems; ++k) {
-      const uint32_t off = wave * (kWave * kItems) + k * kWave + lane;
+    for (int k = 0; k < kSortItems; ++k) {
+      const uint32_t off = wave * (kWave * kSortItems) + k * kWave + lane;
       const bool valid = off < tile_cnt;
       const uint32_t d = (key[k] >> shift) & (NB - 1);
       uint64_t peers = __ballot(valid);
@@ -201,8 +203,8 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(const uint32_t* __rest
     __syncthreads();
 
 #pragma unroll
-    for (int k = 0; k < kItems; ++k) {
-      const uint32_t off = wave * (kWave * kItems) + k * kWave + lane;
+    for (int k = 0; k < kSortItems; ++k) {
+      const uint32_t off = wave * (kWave * kSortItems) + k * kWave + lane;
       if (off < tile_cnt) {
         const uint32_t d = (key[k] >> shift) & (NB - 1);
         const uint32_t pos = s_cnt[wave][d] + lrank[k];
