@@ -150,3 +150,42 @@ def test_cache_validation(B):
     with pytest.raises(B.EmbError):
         ctx.emb_cache_stats(0)
     ctx.close()
+
+
+@pytest.mark.parametrize("tau", [0, 2])
+def test_hybrid_loop_over_a_cached_table(B, tau):
+    """The staleness loop (lookups ahead of updates, second stream) driving a table behind the cache: losses,
+    network weights and every embedding row equal those of the same loop over a resident table, bit for bit."""
+    import torch
+    rows, dim, S, dense_w, bsz = 1 << 15, 16, 4, 64, 128
+    widths = [S * dim + dense_w, 128, 64, 1]
+    a = _args([(rows, dim, 0)], [0] * S, 1)
+    max_ids = bsz * S * 5
+    Ws, bs = W.make_mlp_params(widths, 21)
+    out = []
+    for cache in (None, [max_ids]):
+        emb = B.EmbContext(max_batch=bsz, max_ids=max_ids, cache_rows=cache, **a)
+        mlp = B.MlpContext(widths, S * dim, dense_w, bsz, 0.1, Ws, bs, loss_mean=True)
+        loop = B.HybridLoop(emb, mlp, tau)
+        keep = []
+        for t in range(10):
+            b = W.random_batch(3000 + t, bsz, S, 5, 20000)
+            d, y = W.make_dense_and_labels(5, t, bsz, dense_w, positive_rate=0.3)
+            item = (B.DeviceBatch(b.batch_size, b.ids, b.offsets), torch.from_numpy(d).cuda(), torch.from_numpy(y).cuda())
+            keep.append(item)
+            loop.hyb_submit(*item)
+        loop.hyb_drain()
+        losses = loop.hyb_read_losses(0, 10)
+        w_, acc = emb.emb_read_rows(0, np.arange(rows))
+        out.append((losses, w_, acc, [mlp.mlp_read_weights(l)[0] for l in range(3)]))
+        if cache:
+            st = emb.emb_cache_stats(0)
+            assert st["written_back"] > 0 and st["overflows"] == 0
+        loop.close()
+        mlp.close()
+        emb.close()
+    np.testing.assert_array_equal(out[0][0], out[1][0])
+    np.testing.assert_array_equal(out[0][1], out[1][1])
+    np.testing.assert_array_equal(out[0][2], out[1][2])
+    for x, y in zip(out[0][3], out[1][3]):
+        np.testing.assert_array_equal(x, y)
