@@ -79,6 +79,41 @@ def bench_codec(args, w, binding, torch, np) -> int:
     return 0
 
 
+def bench_indexed_forward(args, w, binding, torch, np, W) -> int:
+    """The forward two ways on one batch: gather per bag (emb_lookup_pool) and from the index form, each unique
+    row read once (emb_lookup_pool_indexed; the index form is built beforehand, outside the timed region, as if
+    the batch had arrived compressed)."""
+    cfg = w.cfg
+    hb = W.make_batch(w, 0)
+    b = binding.DeviceBatch(hb.batch_size, hb.ids, hb.offsets)
+    ctx = binding.EmbContext.from_config(cfg, max_batch=w.batch, max_ids=b.num_ids)
+    pooled = torch.empty((w.batch, cfg.pooled_width), dtype=torch.float32, device="cuda")
+    ctx.emb_backward_update(b, torch.zeros_like(pooled))       # zero gradient: builds the index form, changes no row
+    keys, seg_off, seg_bags = ctx.emb_read_dedup()
+    dk = torch.from_numpy(keys.view(np.int64)).cuda()
+    do = torch.from_numpy(seg_off.view(np.int32)).cuda()
+    dbg = torch.from_numpy(seg_bags.view(np.int32)).cuda()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    for _ in range(args.warmup):
+        ctx.emb_lookup_pool(b, pooled)
+        ctx.emb_lookup_pool_indexed(w.batch, dk, do, dbg, pooled)
+    torch.cuda.synchronize()
+    ev[0].record()
+    for _ in range(args.steps):
+        ctx.emb_lookup_pool(b, pooled)
+    ev[1].record()
+    for _ in range(args.steps):
+        ctx.emb_lookup_pool_indexed(w.batch, dk, do, dbg, pooled)
+    ev[2].record()
+    torch.cuda.synchronize()
+    t_g, t_i = ev[0].elapsed_time(ev[1]) / args.steps, ev[1].elapsed_time(ev[2]) / args.steps
+    print(json.dumps({"metric": "forward, ms per batch", "workload": w.name, "ids": b.num_ids, "unique_rows": int(len(keys)),
+                      "gather_per_bag_ms": round(t_g, 4), "from_index_form_ms": round(t_i, 4), "steps": args.steps,
+                      "n_gpus": 1, "data": "synthetic"}))
+    ctx.close()
+    return 0
+
+
 def bench_hybrid(args, w, binding, torch, np, W) -> int:
     """emb_lookup_pool -> mlp_step -> emb_backward_update(d_pooled from the MLP), one stream, synchronous."""
     cfg = w.cfg
@@ -189,6 +224,8 @@ def main() -> int:
                     help="instead of the training step, time the scaled-fp16 value codec on this config's pooled shape")
     ap.add_argument("--hybrid", action="store_true",
                     help="full hybrid step: lookup -> dense MLP step (bf16 MFMA) -> embedding update with the MLP's gradient")
+    ap.add_argument("--indexed-forward", action="store_true",
+                    help="instead of the training step, time the forward per bag against the forward from the index form")
     ap.add_argument("--tau", type=int, default=None,
                     help="with --hybrid: run the library's step loop with this staleness (lookups tau batches ahead, second stream)")
     ap.add_argument("--cache-frac", type=float, default=None,
@@ -214,6 +251,8 @@ def main() -> int:
         return bench_codec(args, w, binding, torch, np)
     if args.hybrid:
         return bench_hybrid(args, w, binding, torch, np, W)
+    if args.indexed_forward:
+        return bench_indexed_forward(args, w, binding, torch, np, W)
     T = len(cfg.tables)
     e_of = [2 if t.dtype == W.BF16 else 4 for t in cfg.tables]
     slot_table = np.array([s.table for s in cfg.slots])

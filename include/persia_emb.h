@@ -118,6 +118,16 @@ int emb_destroy(emb_ctx* ctx); /* synchronous; frees everything the context owns
  * counted with multiplicity, empty bags give zeros.  pooled: device, fp32 [B, W], written whole. */
 int emb_lookup_pool(emb_ctx* ctx, const emb_batch* batch, float* pooled, void* hip_stream);
 
+/* The forward from the index form (section 4.2.3: a batch compressed losslessly as its unique keys, each with
+ * the list of places that hold it) -- the same pooled activations as emb_lookup_pool, from what
+ * emb_read_dedup describes: keys[u] = (table << 32) | row ascending (device, [num_unique]), seg_off (device,
+ * [num_unique + 1], seg_off[0] = 0, seg_off[num_unique] = num_ids), seg_bags (device, [num_ids], bag = sample *
+ * num_slots + slot).  Each unique row is read once and added to its bags' pooled rows with fp32 atomics, so
+ * a bag's sum forms in no fixed order: equal to emb_lookup_pool within the fp32 tolerance, not bit for bit.
+ * pooled: device fp32 [batch_size, W], written whole.  Not available for tables behind a cache. */
+int emb_lookup_pool_indexed(emb_ctx* ctx, uint32_t batch_size, uint64_t num_unique, uint64_t num_ids, const uint64_t* keys,
+                            const uint32_t* seg_off, const uint32_t* seg_bags, float* pooled, void* hip_stream);
+
 /* The hash step alone (section 4.2.2: the global hashing function that locates a parameter):
  * rows_out[i] = row of ids[i] in the table of its slot.  rows_out: device, uint32 [N]. */
 int emb_hash_rows(emb_ctx* ctx, const emb_batch* batch, uint32_t* rows_out, void* hip_stream);

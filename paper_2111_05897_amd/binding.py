@@ -77,6 +77,8 @@ def load_library() -> C.CDLL:
         getattr(L, name).restype = C.c_int
     L.emb_lookup_pool.argtypes = [vp, C.POINTER(emb_batch), vp, vp]
     L.emb_hash_rows.argtypes = [vp, C.POINTER(emb_batch), vp, vp]
+    L.emb_lookup_pool_indexed.argtypes = [vp, u32, u64, u64, vp, vp, vp, vp, vp]
+    L.emb_lookup_pool_indexed.restype = C.c_int
     L.emb_backward_update.argtypes = [vp, C.POINTER(emb_batch), vp, vp]
     L.emb_dedup_sizes.argtypes = [vp, C.POINTER(u64), C.POINTER(u64)]
     L.emb_read_dedup.argtypes = [vp, vp, vp, vp]
@@ -210,6 +212,21 @@ class EmbContext:
         assert pooled.is_contiguous() and pooled.dtype == torch.float32
         assert pooled.shape == (batch.batch_size, self.width)
         self._ck(self.L.emb_lookup_pool(self.h, C.byref(batch.c), pooled.data_ptr(), _stream_ptr(stream)))
+        return pooled
+
+    def emb_lookup_pool_indexed(self, batch_size: int, keys: torch.Tensor, seg_off: torch.Tensor, seg_bags: torch.Tensor,
+                                pooled: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+        """keys: int64 bits of (table << 32) | row [U]; seg_off: int32 bits of uint32 [U+1]; seg_bags: int32 [N]."""
+        if pooled is None:
+            pooled = torch.empty((batch_size, self.width), dtype=torch.float32, device=seg_off.device)
+        assert pooled.is_contiguous() and pooled.dtype == torch.float32 and pooled.shape == (batch_size, self.width)
+        assert keys.dtype == torch.int64 and seg_off.dtype == torch.int32 and seg_bags.dtype == torch.int32
+        assert keys.is_contiguous() and seg_off.is_contiguous() and seg_bags.is_contiguous()
+        U, N = keys.numel(), seg_bags.numel()
+        assert seg_off.numel() == U + 1
+        self._ck(self.L.emb_lookup_pool_indexed(self.h, batch_size, U, N, keys.data_ptr() if U else None,
+                                                seg_off.data_ptr(), seg_bags.data_ptr() if N else None,
+                                                pooled.data_ptr(), _stream_ptr(stream)))
         return pooled
 
     def emb_hash_rows(self, batch: DeviceBatch, stream=None) -> torch.Tensor:

@@ -541,6 +541,27 @@ static int emb_lookup_pool_impl(emb_ctx* ctx, const emb_batch* batch, float* poo
   return EMB_OK;
 }
 
+static int emb_lookup_pool_indexed_impl(emb_ctx* ctx, uint32_t batch_size, uint64_t num_unique, uint64_t num_ids,
+                                        const uint64_t* keys, const uint32_t* seg_off, const uint32_t* seg_bags,
+                                        float* pooled, void* hip_stream) {
+  if (!ctx) return fail(nullptr, EMB_EINVAL, "null context");
+  if (batch_size > ctx->max_batch) return fail(ctx, EMB_EINVAL, "batch_size exceeds max_batch");
+  if (num_ids > ctx->max_ids || num_unique > num_ids) return fail(ctx, EMB_EINVAL, "num_unique <= num_ids <= max_ids violated");
+  if (batch_size == 0) return EMB_OK;
+  if (!pooled || (num_ids && (!keys || !seg_off || !seg_bags))) return fail(ctx, EMB_EINVAL, "null buffer");
+  if (ctx->any_cached) return fail(ctx, EMB_ESTATE, "not available for tables kept behind a cache");
+  hipStream_t stream = (hipStream_t)hip_stream;
+  CKH(hipSetDevice(ctx->device), "hipSetDevice");
+  CKH(launch_zero_f32(pooled, (uint64_t)batch_size * ctx->width, stream), "zero(pooled)");
+  for (size_t t = 0; t < ctx->tables.size(); ++t) {
+    StageTimer tm(ctx, ST_GATHER_POOL, stream);
+    CKH(launch_indexed_pool(ctx->tables[t], (uint32_t)t, ctx->slots, keys, seg_off, seg_bags, (uint32_t)num_unique,
+                            (uint32_t)num_ids, batch_size, ctx->S, ctx->width, pooled, stream),
+        "indexed_pool");
+  }
+  return EMB_OK;
+}
+
 static int emb_hash_rows_impl(emb_ctx* ctx, const emb_batch* batch, uint32_t* rows_out, void* hip_stream) {
   int rc = check_batch(ctx, batch);
   if (rc) return rc;
@@ -825,6 +846,10 @@ int emb_cache_stats(emb_ctx* ctx, uint32_t table, uint64_t* stats) { PEMB_GUARDE
 int emb_cache_where(emb_ctx* ctx, uint32_t table, int32_t* where_host) { PEMB_GUARDED(ctx, emb_cache_where_impl(ctx, table, where_host)) }
 int emb_cache_flush(emb_ctx* ctx, void* hip_stream) { PEMB_GUARDED(ctx, emb_cache_flush_impl(ctx, hip_stream)) }
 int emb_lookup_pool(emb_ctx* ctx, const emb_batch* batch, float* pooled, void* hip_stream) { PEMB_GUARDED(ctx, emb_lookup_pool_impl(ctx, batch, pooled, hip_stream)) }
+int emb_lookup_pool_indexed(emb_ctx* ctx, uint32_t batch_size, uint64_t num_unique, uint64_t num_ids, const uint64_t* keys,
+                            const uint32_t* seg_off, const uint32_t* seg_bags, float* pooled, void* hip_stream) {
+  PEMB_GUARDED(ctx, emb_lookup_pool_indexed_impl(ctx, batch_size, num_unique, num_ids, keys, seg_off, seg_bags, pooled, hip_stream))
+}
 int emb_hash_rows(emb_ctx* ctx, const emb_batch* batch, uint32_t* rows_out, void* hip_stream) { PEMB_GUARDED(ctx, emb_hash_rows_impl(ctx, batch, rows_out, hip_stream)) }
 int emb_backward_update(emb_ctx* ctx, const emb_batch* batch, const float* d_pooled, void* hip_stream) { PEMB_GUARDED(ctx, emb_backward_update_impl(ctx, batch, d_pooled, hip_stream)) }
 int emb_dedup_sizes(emb_ctx* ctx, uint64_t* num_unique, uint64_t* num_ids) { PEMB_GUARDED(ctx, emb_dedup_sizes_impl(ctx, num_unique, num_ids)) }

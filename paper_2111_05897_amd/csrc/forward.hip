@@ -162,7 +162,139 @@ hipError_t dispatch_dim(uint32_t dim, const GatherArgs& a, hipStream_t stream) {
   }
 }
 
+// ---- forward from the index form (section 4.2.3: the batch arrives as unique keys, each with the list of
+// bags that hold it) ----
+// A group of LANES lanes walks a tile of kTile entries of the bag list.  The table row of the unique key the
+// entries belong to is read once per (tile, key) and added into the pooled rows of the listed bags with
+// hardware fp32 atomics: a bag's sum then forms in no fixed order (fp32 rounding may differ from run to run,
+// inside the forward's tolerance), which is the price of reading each row once.  pooled must start at zero.
+struct IndexedArgs {
+  const uint64_t* keys;      // [U] (table << 32) | row, ascending
+  const uint32_t* seg_off;   // [U + 1]
+  const uint32_t* seg_bags;  // [N]
+  uint32_t U, N;
+  const void* w;
+  const int32_t* where;
+  uint32_t table;
+  uint64_t rows;
+  const uint32_t* slot_col;
+  uint32_t S, width, n_bags;
+  float* pooled;
+};
+
+template <typename T, int D>
+__global__ __launch_bounds__(kBlock) void k_indexed_pool(IndexedArgs a) {
+  constexpr int VEC = 16 / (int)sizeof(T);
+  constexpr int LANES = D / VEC;
+  constexpr int GPB = kBlock / LANES;
+  const uint32_t tile = blockIdx.x * GPB + threadIdx.x / LANES;
+  const int lane = threadIdx.x % LANES;
+  const uint64_t p0 = (uint64_t)tile * kTile;
+  if (p0 >= a.N) return;
+  const uint32_t p1 = (a.N - p0 < kTile) ? a.N : (uint32_t)p0 + kTile;
+  // the unique key entry p0 belongs to: the last u with seg_off[u] <= p0 (seg_off[U] = N > p0)
+  uint32_t lo = 0, hi = a.U;
+  while (hi - lo > 1) {
+    const uint32_t mid = lo + (hi - lo) / 2;
+    if (a.seg_off[mid] <= p0) lo = mid;
+    else hi = mid;
+  }
+  uint32_t u = lo, u_end = a.seg_off[u + 1];
+  const T* __restrict__ base = reinterpret_cast<const T*>(a.w) + lane * VEC;
+  bool mine = false, loaded = false;
+  float r[VEC];
+  for (uint32_t p = (uint32_t)p0; p < p1; ++p) {
+    while (p >= u_end) {  // next key (empty segments are skipped)
+      if (u + 1 >= a.U) return;  // seg_off does not reach N: a malformed index form must not run off the arrays
+      ++u;
+      u_end = a.seg_off[u + 1];
+      loaded = false;
+    }
+    if (!loaded) {
+      const uint64_t key = a.keys[u];
+      mine = (uint32_t)(key >> 32) == a.table && (key & 0xFFFFFFFFull) < a.rows;
+      if (mine) {
+        uint32_t row = (uint32_t)key;
+        if (a.where) {
+          const int32_t slot = a.where[row];
+          row = slot >= 0 ? (uint32_t)slot : 0u;
+        }
+        Raw16<T> raw;
+        raw.load(base + (size_t)row * D);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) r[e] = 0.f;
+        raw.add_to(r);
+      }
+      loaded = true;
+    }
+    if (mine) {
+      const uint32_t bag = a.seg_bags[p];
+      if (bag >= a.n_bags) continue;  // malformed input: no such bag
+      const uint32_t b = bag / a.S, s = bag - b * a.S;
+      float* out = a.pooled + (size_t)b * a.width + a.slot_col[s] + lane * VEC;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) unsafeAtomicAdd(out + e, r[e]);
+    }
+  }
+}
+
+template <typename T, int D>
+hipError_t launch_ip(const IndexedArgs& a, hipStream_t stream) {
+  constexpr int LANES = D / (16 / (int)sizeof(T));
+  constexpr int GPB = kBlock / LANES;
+  const uint64_t tiles = ((uint64_t)a.N + kTile - 1) / kTile;
+  hipLaunchKernelGGL((k_indexed_pool<T, D>), dim3((uint32_t)((tiles + GPB - 1) / GPB)), dim3(kBlock), 0, stream, a);
+  return hipGetLastError();
+}
+template <typename T>
+hipError_t dispatch_ip(uint32_t dim, const IndexedArgs& a, hipStream_t stream) {
+  switch (dim) {
+    case 8: return launch_ip<T, 8>(a, stream);
+    case 16: return launch_ip<T, 16>(a, stream);
+    case 32: return launch_ip<T, 32>(a, stream);
+    case 64: return launch_ip<T, 64>(a, stream);
+    case 128: return launch_ip<T, 128>(a, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void k_zero_f32(float4* __restrict__ p, uint64_t n4) {
+  for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n4; i += (uint64_t)gridDim.x * kBlock)
+    p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
 }  // namespace
+
+hipError_t launch_zero_f32(float* p, uint64_t n, hipStream_t stream) {  // n a multiple of 4, p 16-byte aligned
+  if (n == 0) return hipSuccess;
+  const uint64_t n4 = n / 4;
+  const uint64_t blocks = (n4 + kBlock - 1) / kBlock;
+  hipLaunchKernelGGL(k_zero_f32, dim3((uint32_t)(blocks > 16384 ? 16384 : blocks)), dim3(kBlock), 0, stream,
+                     reinterpret_cast<float4*>(p), n4);
+  return hipGetLastError();
+}
+
+hipError_t launch_indexed_pool(const TableView& t, uint32_t table, const SlotArrays& sl, const uint64_t* keys,
+                               const uint32_t* seg_off, const uint32_t* seg_bags, uint32_t U, uint32_t N, uint32_t B,
+                               uint32_t S, uint32_t width, float* pooled, hipStream_t stream) {
+  if (N == 0 || U == 0 || t.n_slots == 0) return hipSuccess;
+  IndexedArgs a;
+  a.keys = keys;
+  a.seg_off = seg_off;
+  a.seg_bags = seg_bags;
+  a.U = U;
+  a.N = N;
+  a.w = t.w;
+  a.where = t.where;
+  a.table = table;
+  a.rows = t.rows;
+  a.slot_col = sl.col;
+  a.S = S;
+  a.width = width;
+  a.n_bags = B * S;
+  a.pooled = pooled;
+  return t.dtype == 1 ? dispatch_ip<bf16_t>(t.dim, a, stream) : dispatch_ip<float>(t.dim, a, stream);
+}
 
 hipError_t launch_gather_pool(const TableView& t, const SlotArrays& sl, const uint64_t* ids, const int32_t* offsets,
                               uint32_t B, uint32_t S, uint32_t width, int mix, float* pooled, hipStream_t stream) {

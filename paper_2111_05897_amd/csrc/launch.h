@@ -88,6 +88,12 @@ hipError_t launch_write_rows(const TableView& t, const uint64_t* rows_dev, uint6
 // ---- forward.hip ----
 hipError_t launch_gather_pool(const TableView& t, const SlotArrays& sl, const uint64_t* ids, const int32_t* offsets,
                               uint32_t B, uint32_t S, uint32_t width, int mix, float* pooled, hipStream_t stream);
+// The forward from the index form: pooled (zeroed first, launch_zero_f32) += row of keys[u] for every bag of
+// seg_bags[seg_off[u] .. seg_off[u+1]), for the keys of table `table`; fp32 hardware atomics.
+hipError_t launch_zero_f32(float* p, uint64_t n, hipStream_t stream);
+hipError_t launch_indexed_pool(const TableView& t, uint32_t table, const SlotArrays& sl, const uint64_t* keys,
+                               const uint32_t* seg_off, const uint32_t* seg_bags, uint32_t U, uint32_t N, uint32_t B,
+                               uint32_t S, uint32_t width, float* pooled, hipStream_t stream);
 // keys_out[i] = key_base(slot) + row (or the bare row when bare_rows != 0); bags_out may be null.
 hipError_t launch_build_keys(const SlotArrays& sl, const uint64_t* ids, const int32_t* offsets, uint32_t B,
                              uint32_t S, int mix, int bare_rows, uint32_t* keys_out, uint32_t* bags_out,
