@@ -349,6 +349,7 @@ def main() -> int:
     ctx.emb_set_profiling(True)
     ctx.emb_reset_stage_ms()
     N_t, U_t, Um_t = np.zeros(T), np.zeros(T), np.zeros(T)
+    tile = int(binding.load_library().emb_tile_entries())   # segments crossing a tile edge are finished by the fix-up
     N_sum = 0
     for i in range(args.steps):
         N_sum += step(args.warmup + i)
@@ -356,7 +357,7 @@ def main() -> int:
         s, en = seg_off[:-1].astype(np.int64), seg_off[1:].astype(np.int64)
         kt = (keys >> np.uint64(32)).astype(np.int64)
         U_t += np.bincount(kt, minlength=T)
-        Um_t += np.bincount(kt[s // 32 != (en - 1) // 32], minlength=T)
+        Um_t += np.bincount(kt[s // tile != (en - 1) // tile], minlength=T)
         N_t += np.bincount(kt, weights=(en - s), minlength=T)
     stages = ctx.emb_read_stage_ms()
     ctx.emb_set_profiling(False)

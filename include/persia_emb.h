@@ -162,6 +162,7 @@ int emb_table_ptr(emb_ctx* ctx, uint32_t table, void** w_dev, float** acc_dev);
  * Stage names: emb_stage_name(i) for 0 <= i < emb_stage_count(). */
 int emb_set_profiling(emb_ctx* ctx, int enabled);
 int emb_stage_count(void);
+uint32_t emb_tile_entries(void); /* entries of the sorted occurrence list one lane-group reduces (for byte accounting) */
 const char* emb_stage_name(int stage);
 int emb_read_stage_ms(emb_ctx* ctx, float* ms, uint32_t* launches); /* host arrays [emb_stage_count()] */
 int emb_reset_stage_ms(emb_ctx* ctx);

@@ -87,6 +87,8 @@ def load_library() -> C.CDLL:
     L.emb_table_ptr.argtypes = [vp, u32, C.POINTER(vp), C.POINTER(vp)]
     L.emb_set_profiling.argtypes = [vp, i32]
     L.emb_stage_count.argtypes = []
+    L.emb_tile_entries.argtypes = []
+    L.emb_tile_entries.restype = u32
     L.emb_stage_name.argtypes = [i32]
     L.emb_stage_name.restype = C.c_char_p
     L.emb_read_stage_ms.argtypes = [vp, vp, vp]

@@ -788,6 +788,7 @@ int emb_set_profiling(emb_ctx* ctx, int enabled) {
 }
 
 int emb_stage_count(void) { return ST_COUNT; }
+uint32_t emb_tile_entries(void) { return kTile; }
 
 const char* emb_stage_name(int stage) { return (stage >= 0 && stage < ST_COUNT) ? kStageNames[stage] : ""; }
 

@@ -6,7 +6,7 @@
 namespace pemb {
 
 // Occurrences per tile of the segmented reduce: one lane-group walks this many sorted occurrences.
-constexpr uint32_t kTile = 32;
+constexpr uint32_t kTile = 64;
 // Radix sort geometry: a block ranks and scatters tiles of 256 threads x 16 pairs (runs of one digit are
 // then long enough to be written as whole cache lines).
 constexpr uint32_t kSortTile = 4096;
