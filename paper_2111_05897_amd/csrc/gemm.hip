@@ -4,9 +4,11 @@
 //
 // k_gemm_nt: a 512-thread workgroup computes a 256x256 tile of C; its 8 waves sit 2x4 and own 128x64
 // each, i.e. 4x2 MFMA tiles of v_mfma_f32_32x32x16_bf16 (lane l feeds row/column l%32 with the 8
-// consecutive k values starting at 8*(l/32)).  K is walked in steps of 64 through two LDS stages (rows
-// padded by 16 bytes against bank conflicts).  Workgroups are numbered so that the ones running together on an XCD cover a
-// compact block of tiles and share their A and Bt strips in that XCD's L2.
+// consecutive k values starting at 8*(l/32)).  K is walked in steps of 32 through a ring of four LDS
+// stages that global_load_lds_dwordx4 fills directly (no staging registers), three tiles ahead of the
+// products; rows are unpadded and XOR-swizzled against bank conflicts.  Workgroups are numbered so that
+// the ones running together on an XCD cover a compact block of tiles and share their A and Bt strips in
+// that XCD's L2.
 #include "device_utils.h"
 #include "launch.h"
 
@@ -19,14 +21,16 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int BK = 64;
+constexpr int BK = 32;              // K elements per LDS stage
+constexpr int kKUnit = 64;          // K must be a multiple of this; splits along K are counted in these units
+constexpr int kStages = 4;          // ring of LDS stages: tile i is multiplied while tiles i+1..i+3 arrive
 // 512-thread workgroups: 8 waves sit 2 (M) x 4 (N); a wave owns WM x WN MFMA tiles of 32x32.
 constexpr int kGemmThreads = 512;
 constexpr int WM = 4, WN = 2;
 constexpr int BM = 2 * 32 * WM, BN = 4 * 32 * WN;  // 256 x 256
-constexpr int LDS_STRIDE = BK + 8;                  // bf16 elements per staged row (16 bytes of padding)
-constexpr int kStageElems = (BM + BN) * LDS_STRIDE; // one LDS stage: A tile then Bt tile
-constexpr size_t kGemmLdsBytes = 2 * (size_t)kStageElems * sizeof(bf16_t);  // two stages
+constexpr int kRowBytes = BK * 2;                   // a staged row: 64 bytes = 4 chunks of 16, no padding
+constexpr int kStageBytes = (BM + BN) * kRowBytes;  // one LDS stage: A tile then Bt tile
+constexpr size_t kGemmLdsBytes = (size_t)kStages * kStageBytes;
 constexpr uint32_t kXcds = 8;
 constexpr uint32_t kGroupM = 8;     // m-tiles per raster group
 
@@ -67,10 +71,6 @@ __global__ __launch_bounds__(kGemmThreads, 2) void k_gemm_nt(GemmArgs g) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 2, wn = wave & 3;
-  // global -> LDS mapping: passes of 64 rows, 8 threads of 16 bytes per row
-  const int lrow = tid >> 3, lcol = (tid & 7) * 8;
-  constexpr int PA = BM / 64, PB = BN / 64;
-
   floatx16 acc[WM][WN];
 #pragma unroll
   for (int i = 0; i < WM; ++i)
@@ -79,46 +79,58 @@ __global__ __launch_bounds__(kGemmThreads, 2) void k_gemm_nt(GemmArgs g) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  // Rows past the end of A or Bt are replaced by the last valid row (their products are never stored), so
-  // the loads need no predicate: a uniform base that advances with k plus one 32-bit offset per load.
-  const uint32_t kt0 = blockIdx.y * g.k_tiles_per_split;  // first K tile of this split
-  const char* baseA = reinterpret_cast<const char*>(g.A + (size_t)m0 * g.lda + (size_t)kt0 * BK);
-  const char* baseB = reinterpret_cast<const char*>(g.Bt + (size_t)n0 * g.ldb + (size_t)kt0 * BK);
-  uint32_t offA[PA], offB[PB];
+  // Global -> LDS without passing through registers (global_load_lds_dwordx4): one wave instruction moves 64
+  // x 16 bytes to 1 KB of consecutive LDS, i.e. 16 staged rows; lane l lands on row l/4, chunk position l%4.
+  // Rows are not padded; instead chunk c of row r is kept at position c ^ ((r >> 2) & 3), which makes the
+  // fragment reads below (32 rows, one chunk each) hit every bank once.  The lane chooses the global chunk
+  // that belongs at its position.  Rows past the end of A or Bt are replaced by the last valid row (their
+  // products are never stored), so no load needs a predicate.
+  constexpr int kGroupsA = BM / 16, kGroupsB = BN / 16;            // 16-row groups per operand tile
+  constexpr int kWaves = kGemmThreads / kWave;
+  static_assert(kGroupsA % kWaves == 0 && kGroupsB % kWaves == 0, "whole wave instructions per stage");
+  constexpr int LA = kGroupsA / kWaves, LB = kGroupsB / kWaves;     // loads per thread and stage
+  const uint32_t kt0 = blockIdx.y * g.k_tiles_per_split;            // first K unit of this split
+  const int uwave = __builtin_amdgcn_readfirstlane(wave);
+  const uint32_t chunk = (uint32_t)((lane & 3) ^ ((lane >> 4) & 3));
+  const char* srcA[LA];
+  const char* srcB[LB];
 #pragma unroll
-  for (int p = 0; p < PA; ++p) offA[p] = (min((uint32_t)(p * 64 + lrow), g.M - 1 - m0) * g.lda + lcol) * 2u;
+  for (int j = 0; j < LA; ++j) {
+    const uint32_t r = min((uint32_t)((j * kWaves + wave) * 16 + (lane >> 2)), g.M - 1 - m0);
+    srcA[j] = reinterpret_cast<const char*>(g.A + (size_t)(m0 + r) * g.lda + (size_t)kt0 * kKUnit + chunk * 8);
+  }
 #pragma unroll
-  for (int p = 0; p < PB; ++p) offB[p] = (min((uint32_t)(p * 64 + lrow), g.N - 1 - n0) * g.ldb + lcol) * 2u;
-  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-  u32x4 ra[PA], rb[PB], ra2[PA], rb2[PB];
-  auto fetch = [&](uint32_t k0, u32x4 (&a)[PA], u32x4 (&b)[PB]) {
-    const char* pa = baseA + (size_t)k0 * 2;
-    const char* pb = baseB + (size_t)k0 * 2;
+  for (int j = 0; j < LB; ++j) {
+    const uint32_t r = min((uint32_t)((j * kWaves + wave) * 16 + (lane >> 2)), g.N - 1 - n0);
+    srcB[j] = reinterpret_cast<const char*>(g.Bt + (size_t)(n0 + r) * g.ldb + (size_t)kt0 * kKUnit + chunk * 8);
+  }
+  char* lds_bytes = reinterpret_cast<char*>(lds);
+  auto request = [&](uint32_t tile, int stage) {  // tile: index of the 32-wide K tile inside this split
+    char* dst = lds_bytes + stage * kStageBytes;
 #pragma unroll
-    for (int p = 0; p < PA; ++p) a[p] = *reinterpret_cast<const u32x4*>(pa + offA[p]);
+    for (int j = 0; j < LA; ++j)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(srcA[j] + (size_t)tile * kRowBytes),
+                                       (__attribute__((address_space(3))) void*)(dst + (j * kWaves + uwave) * 1024), 16, 0, 0);
 #pragma unroll
-    for (int p = 0; p < PB; ++p) b[p] = *reinterpret_cast<const u32x4*>(pb + offB[p]);
+    for (int j = 0; j < LB; ++j)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(srcB[j] + (size_t)tile * kRowBytes),
+                                       (__attribute__((address_space(3))) void*)(dst + BM * kRowBytes + (j * kWaves + uwave) * 1024), 16, 0, 0);
   };
-  auto stage = [&](int s, const u32x4 (&a)[PA], const u32x4 (&b)[PB]) {
-    bf16_t* As = lds + s * kStageElems;
-    bf16_t* Bs = As + BM * LDS_STRIDE;
+  const uint32_t swz = (uint32_t)((lane >> 2) & 3);
+  static_assert((kStages - 2) * (LA + LB) <= 15, "the wait below encodes its count in four bits");
+  auto compute = [&](int stage) {
+    const char* As = lds_bytes + stage * kStageBytes;
+    const char* Bs = As + BM * kRowBytes;
 #pragma unroll
-    for (int p = 0; p < PA; ++p) *reinterpret_cast<u32x4*>(&As[(p * 64 + lrow) * LDS_STRIDE + lcol]) = a[p];
-#pragma unroll
-    for (int p = 0; p < PB; ++p) *reinterpret_cast<u32x4*>(&Bs[(p * 64 + lrow) * LDS_STRIDE + lcol]) = b[p];
-  };
-  auto compute = [&](int s) {
-    const bf16_t* As = lds + s * kStageElems;
-    const bf16_t* Bs = As + BM * LDS_STRIDE;
-#pragma unroll
-    for (int kk = 0; kk < BK; kk += 16) {
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      const uint32_t pos = ((uint32_t)(kk * 2 + (lane >> 5)) ^ swz) * 16;
       bf16x8 af[WM], bfr[WN];
 #pragma unroll
       for (int i = 0; i < WM; ++i)
-        af[i] = *reinterpret_cast<const bf16x8*>(&As[(wm * 32 * WM + i * 32 + (lane & 31)) * LDS_STRIDE + kk + (lane >> 5) * 8]);
+        af[i] = *reinterpret_cast<const bf16x8*>(As + (wm * 32 * WM + i * 32 + (lane & 31)) * kRowBytes + pos);
 #pragma unroll
       for (int j = 0; j < WN; ++j)
-        bfr[j] = *reinterpret_cast<const bf16x8*>(&Bs[(wn * 32 * WN + j * 32 + (lane & 31)) * LDS_STRIDE + kk + (lane >> 5) * 8]);
+        bfr[j] = *reinterpret_cast<const bf16x8*>(Bs + (wn * 32 * WN + j * 32 + (lane & 31)) * kRowBytes + pos);
 #pragma unroll
       for (int i = 0; i < WM; ++i)
 #pragma unroll
@@ -127,27 +139,28 @@ __global__ __launch_bounds__(kGemmThreads, 2) void k_gemm_nt(GemmArgs g) {
     }
   };
 
-  const uint32_t nk = min(g.K / BK - kt0, g.k_tiles_per_split);
-  fetch(0, ra, rb);
-  stage(0, ra, rb);
-  if (nk > 1) fetch(BK, ra, rb);
-  __syncthreads();
-  // While tile i is multiplied out of LDS stage i%2, tile i+1 waits in registers (ra, rb; it goes to the
-  // other stage at the end of the iteration) and tile i+2 is on its way from global memory (ra2, rb2): every
-  // load has two iterations to arrive, and there is one barrier per iteration.
+  // K tiles of 32 inside this split
+  const uint32_t nk = min(g.K / kKUnit - kt0, g.k_tiles_per_split) * (kKUnit / BK);
+  // Requests run kStages - 1 tiles ahead.  Near the end the last tile is requested again (into a stage nobody
+  // reads any more), so that every iteration issues the same number of loads and "all but the newest
+  // (kStages - 1) * (LA + LB) loads have landed" always means "tile i has landed".
+#pragma unroll
+  for (int t = 0; t < kStages - 1; ++t) request(min((uint32_t)t, nk - 1), t);
   for (uint32_t i = 0; i < nk; ++i) {
-    const int cur = i & 1;
-    if (i + 2 < nk) fetch((i + 2) * BK, ra2, rb2);
-    compute(cur);
-    if (i + 1 < nk) stage(cur ^ 1, ra, rb);  // that stage was last read in iteration i-1, behind a barrier
-    if (i + 2 < nk) {
-#pragma unroll
-      for (int p = 0; p < PA; ++p) ra[p] = ra2[p];
-#pragma unroll
-      for (int p = 0; p < PB; ++p) rb[p] = rb2[p];
-    }
-    __syncthreads();
+    // this wave's part of tile i has landed (all but its newest (kStages - 2) * (LA + LB) requests are done) ...
+    __builtin_amdgcn_s_waitcnt(0x0F70 | ((kStages - 2) * (LA + LB)));  // vmcnt only
+    // ... and so has everybody else's; also, everybody has finished reading the stage that is requested next
+    // (its fragments were consumed by the products above, which the wave issued before arriving here).
+    // A bare barrier: __syncthreads() would add a fence that waits for every outstanding request.
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    request(min(i + kStages - 1, nk - 1), (i + kStages - 1) % kStages);
+    compute(i % kStages);
+    __builtin_amdgcn_sched_barrier(0);
   }
+  __syncthreads();  // the epilogue reuses the stages
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // the surplus requests of the last iterations must not land on the epilogue's patch
+  __syncthreads();
 
   // epilogue: accumulator element e of lane l is C[8*(e/4) + 4*(l/32) + e%4][l%32] of its 32x32 tile
   if (g.vec_out) {
@@ -274,13 +287,13 @@ __global__ __launch_bounds__(kBlock) void k_transpose_bf16(const bf16_t* __restr
 
 template <int EPI>
 hipError_t launch_epi(const GemmArgs& g, hipStream_t stream) {
-  // the two LDS stages need more than the 64 KB a kernel gets by default
+  // the ring of LDS stages needs more than the 64 KB a kernel gets by default
   static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_nt<EPI>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLdsBytes);
   if (attr != hipSuccess) return attr;
   const uint32_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   const uint32_t grid = (tiles + kXcds - 1) / kXcds * kXcds;
-  const uint32_t splits = (g.K / BK + g.k_tiles_per_split - 1) / g.k_tiles_per_split;
+  const uint32_t splits = (g.K / kKUnit + g.k_tiles_per_split - 1) / g.k_tiles_per_split;
   hipLaunchKernelGGL(k_gemm_nt<EPI>, dim3(grid, splits), dim3(kGemmThreads), kGemmLdsBytes, stream, g);
   return hipGetLastError();
 }
@@ -302,7 +315,7 @@ __global__ __launch_bounds__(kBlock) void k_sum_splits(const float* __restrict__
 // into this many partial products (1 = no split), summed afterwards in a fixed order.
 uint32_t gemm_splits(uint32_t M, uint32_t N, uint32_t K) {
   const uint32_t tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
-  const uint32_t nk = K / BK;
+  const uint32_t nk = K / kKUnit;
   if (tiles == 0 || tiles * 2 > 256) return 1;
   uint32_t s = 256 / tiles;
   if (s > nk / 4) s = nk / 4;  // at least four K tiles per split
@@ -314,7 +327,7 @@ hipError_t launch_gemm_nt(int epilogue, const void* A, uint32_t lda, const void*
                           uint32_t K, void* C, uint32_t ldc, const float* bias, const void* mask, uint32_t ldm,
                           hipStream_t stream, void* Ct, uint32_t ldct, float* split_ws, uint64_t split_ws_elems) {
   if (M == 0 || N == 0) return hipSuccess;
-  if (K == 0 || K % BK != 0 || lda % 8 != 0 || ldb % 8 != 0) return hipErrorInvalidValue;  // 16-byte operand loads
+  if (K == 0 || K % kKUnit != 0 || lda % 8 != 0 || ldb % 8 != 0) return hipErrorInvalidValue;  // 16-byte operand loads
   if (!A || !Bt || !C || (epilogue == 0 && !bias) || (epilogue == 2 && !mask)) return hipErrorInvalidValue;
   GemmArgs g;
   g.A = reinterpret_cast<const bf16_t*>(A);
@@ -333,7 +346,7 @@ hipError_t launch_gemm_nt(int epilogue, const void* A, uint32_t lda, const void*
   // fp32 output already writes 128 contiguous bytes per row from the accumulator layout
   g.vec_out = (epilogue != 1 && N % 8 == 0 && vec16(C, ldc) && (epilogue != 2 || vec16(mask, ldm))) ? 1u : 0u;
   if (Ct && epilogue == 1) return hipErrorInvalidValue;  // the transposed copy is bf16
-  g.k_tiles_per_split = K / BK;
+  g.k_tiles_per_split = K / kKUnit;
   g.part_stride = 0;
   uint32_t splits = 1;
   if (epilogue == 1 && split_ws) {
@@ -341,8 +354,8 @@ hipError_t launch_gemm_nt(int epilogue, const void* A, uint32_t lda, const void*
     const uint64_t fit = split_ws_elems / ((uint64_t)M * N);
     if (splits > fit) splits = (uint32_t)fit;
     if (splits >= 2) {
-      g.k_tiles_per_split = (K / BK + splits - 1) / splits;
-      splits = (K / BK + g.k_tiles_per_split - 1) / g.k_tiles_per_split;  // no empty split
+      g.k_tiles_per_split = (K / kKUnit + splits - 1) / splits;
+      splits = (K / kKUnit + g.k_tiles_per_split - 1) / g.k_tiles_per_split;  // no empty split
       g.C = split_ws;
       g.ldc = N;
       g.part_stride = (uint64_t)M * N;
