@@ -509,7 +509,7 @@ static int run_dedup(emb_ctx* ctx, const emb_batch* batch, hipStream_t stream) {
 // Makes every row of the batch just deduplicated resident in its table's cache (one LRU step per call).
 static int admit_batch(emb_ctx* ctx, hipStream_t stream) {
   if (!ctx->any_cached || ctx->last_n == 0) return EMB_OK;
-  ++ctx->lru_step;
+  if (++ctx->lru_step == 0) ctx->lru_step = 1;  // 0 marks a slot that was never used
   for (size_t t = 0; t < ctx->lru.size(); ++t) {
     if (ctx->lru[t].C == 0) continue;
     LruScratch sc = ctx->lru_scratch;

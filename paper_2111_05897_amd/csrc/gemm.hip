@@ -287,7 +287,8 @@ __global__ __launch_bounds__(kBlock) void k_transpose_bf16(const bf16_t* __restr
 
 template <int EPI>
 hipError_t launch_epi(const GemmArgs& g, hipStream_t stream) {
-  // the ring of LDS stages needs more than the 64 KB a kernel gets by default
+  // the ring of LDS stages needs more than the 64 KB a kernel gets by default (set once: the library drives
+  // one device per process)
   static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_nt<EPI>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLdsBytes);
   if (attr != hipSuccess) return attr;
