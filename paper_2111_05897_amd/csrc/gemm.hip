@@ -287,10 +287,10 @@ __global__ __launch_bounds__(kBlock) void k_transpose_bf16(const bf16_t* __restr
 
 template <int EPI>
 hipError_t launch_epi(const GemmArgs& g, hipStream_t stream) {
-  // the ring of LDS stages needs more than the 64 KB a kernel gets by default (set once: the library drives
-  // one device per process)
-  static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_nt<EPI>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLdsBytes);
+  // the ring of LDS stages needs more than the 64 KB a kernel gets by default; the attribute belongs to the
+  // current device, so it is set (a host-side call) before every launch rather than once per process
+  const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_nt<EPI>),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLdsBytes);
   if (attr != hipSuccess) return attr;
   const uint32_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   const uint32_t grid = (tiles + kXcds - 1) / kXcds * kXcds;
