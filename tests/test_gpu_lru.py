@@ -189,3 +189,36 @@ def test_hybrid_loop_over_a_cached_table(B, tau):
     np.testing.assert_array_equal(out[0][2], out[1][2])
     for x, y in zip(out[0][3], out[1][3]):
         np.testing.assert_array_equal(x, y)
+
+
+def test_cached_table_is_transparent_at_full_size(B):
+    """Config 1 at its real size (2^22 rows, 2.2 M ids per batch) with the smallest cache the size rule allows:
+    hundreds of thousands of rows are replaced per call, the scans span thousands of workgroups.  Pooled
+    activations at every step and a sample of rows at the end equal those of the resident table bit for bit."""
+    import torch
+    w = W.make_workload(1)
+    cfg = w.cfg
+    batches = [W.make_batch(w, s) for s in range(5)]
+    max_ids = max(b.num_ids for b in batches)
+    ref = B.EmbContext.from_config(cfg, max_batch=w.batch, max_ids=max_ids)
+    ctx = B.EmbContext.from_config(cfg, max_batch=w.batch, max_ids=max_ids, cache_rows=[max_ids])
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(7)
+    for t in (0, 1, 2, 3, 4, 0, 2):
+        b = batches[t]
+        db = B.DeviceBatch(b.batch_size, b.ids, b.offsets)
+        got, want = ctx.emb_lookup_pool(db), ref.emb_lookup_pool(db)
+        torch.cuda.synchronize()
+        assert torch.equal(got, want), f"pooled differs at batch {t}"
+        dp = torch.randn((w.batch, cfg.pooled_width), generator=gen, device="cuda", dtype=torch.float32)
+        ctx.emb_backward_update(db, dp)
+        ref.emb_backward_update(db, dp)
+    st = ctx.emb_cache_stats(0)
+    assert st["written_back"] > 100000 and st["overflows"] == 0, st
+    rows = np.unique(np.random.default_rng(0).integers(0, cfg.tables[0].rows, size=200000).astype(np.uint64))
+    gw, ga = ctx.emb_read_rows(0, rows)
+    ww, wa = ref.emb_read_rows(0, rows)
+    np.testing.assert_array_equal(gw, ww)
+    np.testing.assert_array_equal(ga, wa)
+    ctx.close()
+    ref.close()
