@@ -209,6 +209,13 @@ int mlp_create(const mlp_config* cfg, const float* const* weights, const float* 
 int mlp_step(mlp_ctx* ctx, uint32_t batch, const float* pooled, const float* dense, const float* labels, float* d_pooled,
              float* loss, void* hip_stream);
 int mlp_read_weights(mlp_ctx* ctx, uint32_t layer, float* w, float* b);
+/* A fully asynchronous dense side, for comparison with the hybrid algorithm (section 3.1 describes what
+ * asynchrony does to the dense network; Algorithm 2 itself is synchronous): with delay d > 0 the gradients
+ * F'^nn of step t are applied at the beginning of step t + d + 1, so every step works with weights that miss
+ * the last d updates (d = 0 is the synchronous step).  Set once, before the first mlp_step (EMB_ESTATE
+ * otherwise); d <= 256; allocates d more sets of gradient buffers.  The gradients of the last d + 1 steps of a
+ * run are never applied. */
+int mlp_set_update_delay(mlp_ctx* ctx, uint32_t delay);
 /* Inspection of what the last mlp_step left behind (synchronous; for tests): what = 0 stored activation of
  * `layer` (bf16 [B, widths[layer]]; layer 0 is the packed input), 1 back-propagated delta at the input of
  * layer `layer` >= 1 (bf16 [B, widths[layer]]), 2 weight gradient (fp32 [widths[layer], widths[layer+1]]),

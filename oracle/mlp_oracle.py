@@ -51,8 +51,13 @@ def weight_grad(h_prev, delta):
 
 
 class MLP:
-    def __init__(self, weights, biases, lr, loss_mean=True, rounding=True):
-        """weights[l]: fp32 [in_l, out_l]; biases[l]: fp32 [out_l]; the last layer has out = 1."""
+    def __init__(self, weights, biases, lr, loss_mean=True, rounding=True, delay=0):
+        """weights[l]: fp32 [in_l, out_l]; biases[l]: fp32 [out_l]; the last layer has out = 1.
+        delay > 0 models a fully asynchronous dense side (the comparison of section 3.1): step t works with
+        weights that miss the gradients of the last `delay` steps (those of step t are applied at the beginning
+        of step t + delay + 1)."""
+        self.delay = int(delay)
+        self.pending = []          # gradients computed but not applied yet, oldest first
         self.W = [np.array(w, dtype=np.float32) for w in weights]
         self.b = [np.array(b, dtype=np.float32) for b in biases]
         self.lr = np.float32(lr)
@@ -65,6 +70,8 @@ class MLP:
         """One forward + backward (+ SGD update).  Returns (loss, d_pooled fp32 [B, P], grads) where grads is
         the list of (dW, db) in fp64."""
         q = self.q
+        if self.delay and len(self.pending) == self.delay + 1:       # step t - delay - 1's gradients are due
+            self._apply(self.pending.pop(0))
         B, P = pooled.shape
         y = np.asarray(labels, dtype=np.float64).reshape(B)
         h = [q(np.concatenate([pooled, dense], axis=1))]
@@ -83,7 +90,13 @@ class MLP:
             else:
                 d_x = delta @ q(self.W[0]).T                        # the input has no ReLU in front of it
         if update:
-            for l in range(L):
-                self.W[l] = (self.W[l].astype(np.float64) - float(self.lr) * grads[l][0]).astype(np.float32)
-                self.b[l] = (self.b[l].astype(np.float64) - float(self.lr) * grads[l][1]).astype(np.float32)
+            if self.delay:
+                self.pending.append(grads)
+            else:
+                self._apply(grads)
         return loss, d_x[:, :P].astype(np.float32), grads
+
+    def _apply(self, grads):
+        for l in range(len(self.W)):
+            self.W[l] = (self.W[l].astype(np.float64) - float(self.lr) * grads[l][0]).astype(np.float32)
+            self.b[l] = (self.b[l].astype(np.float64) - float(self.lr) * grads[l][1]).astype(np.float32)

@@ -102,6 +102,8 @@ def load_library() -> C.CDLL:
     L.mlp_create.argtypes = [C.POINTER(mlp_config), vp, vp, C.POINTER(vp)]
     L.mlp_step.argtypes = [vp, u32, vp, vp, vp, vp, vp, vp]
     L.mlp_read_weights.argtypes = [vp, u32, vp, vp]
+    L.mlp_set_update_delay.argtypes = [vp, u32]
+    L.mlp_set_update_delay.restype = C.c_int
     L.mlp_destroy.argtypes = [vp]
     L.mlp_device_bytes.argtypes = [vp]
     L.mlp_device_bytes.restype = u64
@@ -370,6 +372,9 @@ class MlpContext:
         self._ck(self.L.mlp_step(self.h, B, pooled.data_ptr(), dense.data_ptr(), labels.data_ptr(), d_pooled.data_ptr(),
                                  loss.data_ptr(), _stream_ptr(stream)))
         return d_pooled, loss
+
+    def mlp_set_update_delay(self, delay: int):
+        self._ck(self.L.mlp_set_update_delay(self.h, int(delay)))
 
     def mlp_read_weights(self, layer):
         w = np.empty((self.widths[layer], self.widths[layer + 1]), dtype=np.float32)

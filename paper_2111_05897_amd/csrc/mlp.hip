@@ -171,6 +171,12 @@ struct mlp_ctx {
   float* split_ws = nullptr;  // partial weight-gradient products (split along the batch dimension)
   uint64_t split_ws_elems = 0;
   uint32_t last_batch = 0;
+  // delayed application of the gradients (a fully asynchronous dense side, for comparison): step t works with
+  // weights that miss the last `delay` gradients; those of step t wait in ring_*[t % (delay + 1)] and are
+  // applied at the beginning of step t + delay + 1
+  uint32_t delay = 0;
+  uint64_t steps_done = 0;
+  std::vector<std::vector<float*>> ring_dW, ring_db;
   std::vector<void*> allocs;
   uint64_t device_bytes = 0;
   std::string err;
@@ -307,6 +313,40 @@ hipError_t colsum(mlp_ctx* c, const bf16_t* in, uint32_t R, uint32_t Cc, const f
   return hipGetLastError();
 }
 
+// w -= lr * (the gradients c->dW / c->db point at), on the fp32 masters; refreshes the bf16 copies.
+int apply_sgd(mlp_ctx* c, hipStream_t s) {
+  const std::vector<uint32_t>& w = c->widths;
+  for (uint32_t l = 0; l < c->L; ++l) {
+    const uint32_t n_in = w[l], n_out = w[l + 1];
+    hipLaunchKernelGGL(k_sgd_weights, dim3((n_out + 63) / 64, (n_in + 63) / 64), dim3(kBlock), 0, s, c->Wm[l],
+                       (const float*)c->dW[l], n_in, n_out, c->lr, c->W[l], c->Wt[l]);
+    CKM(hipGetLastError(), "sgd(weights)");
+    hipLaunchKernelGGL(k_sgd_vector, dim3((n_out + kBlock - 1) / kBlock), dim3(kBlock), 0, s, c->bias[l],
+                       (const float*)c->db[l], n_out, c->lr);
+    CKM(hipGetLastError(), "sgd(bias)");
+  }
+  return EMB_OK;
+}
+
+int mlp_set_update_delay_impl(mlp_ctx* c, uint32_t delay) {
+  if (!c) return mfail(nullptr, EMB_EINVAL, "null context");
+  if (c->steps_done != 0 || c->delay != 0) return mfail(c, EMB_ESTATE, "the delay can be set once, before the first step");
+  if (delay > 256) return mfail(c, EMB_EINVAL, "delay must be at most 256");
+  if (delay == 0) return EMB_OK;
+  CKM(hipSetDevice(c->device), "hipSetDevice");
+  c->ring_dW.assign((size_t)delay + 1, std::vector<float*>(c->L, nullptr));
+  c->ring_db.assign((size_t)delay + 1, std::vector<float*>(c->L, nullptr));
+  c->ring_dW[0] = c->dW;  // the set the context was created with is the first of the ring
+  c->ring_db[0] = c->db;
+  for (uint32_t d = 1; d <= delay; ++d)
+    for (uint32_t l = 0; l < c->L; ++l) {
+      CKM(malloc_dev(c, &c->ring_dW[d][l], (uint64_t)c->widths[l] * c->widths[l + 1]), "hipMalloc(delayed weight gradient)");
+      CKM(malloc_dev(c, &c->ring_db[d][l], c->widths[l + 1]), "hipMalloc(delayed bias gradient)");
+    }
+  c->delay = delay;
+  return EMB_OK;
+}
+
 int mlp_step_impl(mlp_ctx* c, uint32_t B, const float* pooled, const float* dense, const float* labels,
                   float* d_pooled, float* loss, void* hip_stream) {
   if (!c) return mfail(nullptr, EMB_EINVAL, "null context");
@@ -317,6 +357,15 @@ int mlp_step_impl(mlp_ctx* c, uint32_t B, const float* pooled, const float* dens
   const uint32_t L = c->L;
   const std::vector<uint32_t>& w = c->widths;
   c->last_batch = B;
+  if (c->delay) {  // the gradients computed delay + 1 steps ago are due now; this step's go into their place
+    const size_t slot = (size_t)(c->steps_done % ((uint64_t)c->delay + 1));
+    c->dW = c->ring_dW[slot];
+    c->db = c->ring_db[slot];
+    if (c->steps_done >= (uint64_t)c->delay + 1) {
+      const int rc = apply_sgd(c, s);
+      if (rc != EMB_OK) return rc;
+    }
+  }
   // forward
   {
     hipLaunchKernelGGL(k_pack_input, dim3((w[0] + 63) / 64, (B + 63) / 64), dim3(kBlock), 0, s, pooled, c->P, dense,
@@ -359,16 +408,11 @@ int mlp_step_impl(mlp_ctx* c, uint32_t B, const float* pooled, const float* dens
           "gemm(d_pooled)");
     }
   }
-  // update
-  for (uint32_t l = 0; l < L; ++l) {
-    const uint32_t n_in = w[l], n_out = w[l + 1];
-    hipLaunchKernelGGL(k_sgd_weights, dim3((n_out + 63) / 64, (n_in + 63) / 64), dim3(kBlock), 0, s, c->Wm[l],
-                       (const float*)c->dW[l], n_in, n_out, c->lr, c->W[l], c->Wt[l]);
-    CKM(hipGetLastError(), "sgd(weights)");
-    hipLaunchKernelGGL(k_sgd_vector, dim3((n_out + kBlock - 1) / kBlock), dim3(kBlock), 0, s, c->bias[l],
-                       (const float*)c->db[l], n_out, c->lr);
-    CKM(hipGetLastError(), "sgd(bias)");
+  if (c->delay == 0) {
+    const int rc = apply_sgd(c, s);
+    if (rc != EMB_OK) return rc;
   }
+  ++c->steps_done;
   return EMB_OK;
 }
 
@@ -460,6 +504,7 @@ int mlp_destroy(mlp_ctx* ctx) {
   return EMB_OK;
 }
 uint64_t mlp_device_bytes(mlp_ctx* ctx) { return ctx ? ctx->device_bytes : 0; }
+int mlp_set_update_delay(mlp_ctx* ctx, uint32_t delay) { MLP_GUARDED(ctx, mlp_set_update_delay_impl(ctx, delay)) }
 int mlp_describe(mlp_ctx* ctx, uint32_t* pooled_width, uint32_t* dense_width, uint32_t* max_batch, int32_t* device) {
   if (!ctx) return mfail(nullptr, EMB_EINVAL, "null context");
   if (pooled_width) *pooled_width = ctx->P;

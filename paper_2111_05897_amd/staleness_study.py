@@ -13,7 +13,8 @@ predicting the base rate.
 
     python -m paper_2111_05897_amd.staleness_study --taus 0 1 4 16 64 --steps 800
 
-prints one JSON line per tau.  Needs the GPU and the built library.
+prints one JSON line per tau for the hybrid algorithm and one for the fully asynchronous comparison (the dense
+network's gradients applied tau steps late too, mlp_set_update_delay).  Needs the GPU and the built library.
 """
 from __future__ import annotations
 
@@ -62,8 +63,9 @@ class Task:
         return ids, offsets.astype(np.int32), dense, labels, bayes, float(labels.mean())
 
 
-def run(tau, steps, batch_size=4096, seed=0, rows=1 << 20, dim=64, emb_lr=1.0, mlp_lr=0.1, task=None):
-    """Trains `steps` batches with staleness `tau`; returns the per-batch losses and reference levels."""
+def run(tau, steps, batch_size=4096, seed=0, rows=1 << 20, dim=64, emb_lr=1.0, mlp_lr=0.1, task=None, dense_delay=0):
+    """Trains `steps` batches with embedding staleness `tau` and, for the fully asynchronous comparison, a dense
+    side whose weights miss the last `dense_delay` gradients; returns the per-batch losses and reference levels."""
     import torch
     from . import binding
     from .workload import default_salt, make_mlp_params
@@ -78,6 +80,8 @@ def run(tau, steps, batch_size=4096, seed=0, rows=1 << 20, dim=64, emb_lr=1.0, m
                              max_batch=batch_size, max_ids=max_ids)
     Ws, bs = make_mlp_params(widths, 99 + seed)
     mlp = binding.MlpContext(widths, P, task.dense, batch_size, mlp_lr, Ws, bs, loss_mean=True)
+    if dense_delay:
+        mlp.mlp_set_update_delay(dense_delay)
     loop = binding.HybridLoop(emb, mlp, tau)
     bayes, base = [], []
     for t in range(steps):
@@ -98,9 +102,9 @@ def run(tau, steps, batch_size=4096, seed=0, rows=1 << 20, dim=64, emb_lr=1.0, m
     return losses, float(np.mean(bayes)), float(-(rate * np.log(rate) + (1 - rate) * np.log1p(-rate)))
 
 
-def summarize(tau, losses, bayes, base_entropy, window):
+def summarize(tau, losses, bayes, base_entropy, window, mode="hybrid"):
     w = min(window, len(losses) // 2)
-    return {"tau": tau, "steps": int(len(losses)), "loss_first": round(float(losses[:w].mean()), 5),
+    return {"mode": mode, "tau": tau, "steps": int(len(losses)), "loss_first": round(float(losses[:w].mean()), 5),
             "loss_last": round(float(losses[-w:].mean()), 5), "window": w, "teacher_entropy": round(bayes, 5),
             "base_rate_entropy": round(base_entropy, 5),
             "normalized_entropy_last": round(float(losses[-w:].mean()) / base_entropy, 4)}
@@ -113,11 +117,18 @@ def main(argv=None) -> int:
     ap.add_argument("--batch", type=int, default=4096)
     ap.add_argument("--window", type=int, default=100)
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-async", action="store_true", help="skip the fully asynchronous comparison runs")
     args = ap.parse_args(argv)
     task = Task(args.seed)
     for tau in args.taus:
+        # hybrid: embeddings stale by tau, dense network synchronous (tau = 0: everything synchronous)
         losses, bayes, base = run(tau, args.steps, args.batch, args.seed, task=task)
-        print(json.dumps(summarize(tau, losses, bayes, base, args.window)), flush=True)
+        print(json.dumps(summarize(tau, losses, bayes, base, args.window, "synchronous" if tau == 0 else "hybrid")),
+              flush=True)
+        if tau and not args.no_async:
+            # fully asynchronous: the dense network's gradients arrive tau steps late as well
+            losses, bayes, base = run(tau, args.steps, args.batch, args.seed, task=task, dense_delay=tau)
+            print(json.dumps(summarize(tau, losses, bayes, base, args.window, "fully asynchronous")), flush=True)
     return 0
 
 

@@ -184,3 +184,8 @@ def test_small_staleness_trains_like_synchronous(B):
     assert out[0]["loss_last"] < 0.93 * out[0]["base_rate_entropy"], out
     assert out[0]["loss_last"] > out[0]["teacher_entropy"], out
     assert abs(out[4]["loss_last"] - out[0]["loss_last"]) <= 0.02 * out[0]["loss_last"], out
+    # the comparison the hybrid algorithm is defined against: with the dense network's gradients arriving 4 steps
+    # late as well (fully asynchronous), the same run ends clearly worse, or diverges
+    losses, bayes, base = SS.run(4, 240, batch_size=2048, seed=3, task=task, dense_delay=4)
+    worse = SS.summarize(4, losses, bayes, base, 40, "fully asynchronous")
+    assert (not np.isfinite(worse["loss_last"])) or worse["loss_last"] > out[4]["loss_last"] + 0.02, (worse, out)

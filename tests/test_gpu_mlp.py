@@ -136,3 +136,38 @@ def test_mlp_create_rejects_bad_configurations(B):
     Ws, bs = _net(1, [128, 64, 2])
     with pytest.raises(B.EmbError):
         B.MlpContext([128, 64, 2], 64, 64, 64, 0.1, Ws, bs)               # two outputs
+
+
+def test_delayed_updates_follow_the_oracle(B):
+    """mlp_set_update_delay: step t works with weights that miss the gradients of the last d steps.  Losses and
+    the movement of the weights against the oracle with the same delay; a delay beyond the run leaves the
+    weights bit-identical; a context cannot change its delay after a step."""
+    import torch
+    widths, P, Bsz, d = [128 + 64, 256, 128, 1], 128, 256, 2
+    Dn = widths[0] - P
+    Ws, bs = _net(9, widths)
+    ctx = B.MlpContext(widths, P, Dn, Bsz, 0.1, Ws, bs, loss_mean=True)
+    ctx.mlp_set_update_delay(d)
+    orc = MO.MLP(Ws, bs, lr=0.1, loss_mean=True, rounding=True, delay=d)
+    frozen = B.MlpContext(widths, P, Dn, Bsz, 0.1, Ws, bs, loss_mean=True)
+    frozen.mlp_set_update_delay(50)
+    rng = np.random.default_rng(5)
+    got, want = [], []
+    for t in range(7):
+        pooled = (rng.standard_normal((Bsz, P)) * 0.3).astype(np.float32)
+        dense = rng.standard_normal((Bsz, Dn)).astype(np.float32)
+        y = (rng.random(Bsz) < 0.3).astype(np.float32)
+        args = (torch.from_numpy(pooled).cuda(), torch.from_numpy(dense).cuda(), torch.from_numpy(y).cuda())
+        got.append(ctx.mlp_step(*args)[1].item())
+        frozen.mlp_step(*args)
+        want.append(orc.step(pooled, dense, y)[0])
+    np.testing.assert_allclose(got, want, rtol=2e-2)
+    for l in range(len(widths) - 1):
+        gw, gb = ctx.mlp_read_weights(l)
+        moved = np.linalg.norm(orc.W[l].astype(np.float64) - Ws[l])
+        assert moved > 0 and np.linalg.norm(gw - orc.W[l]) <= 3e-2 * moved
+        fw, fb = frozen.mlp_read_weights(l)
+        np.testing.assert_array_equal(fw, Ws[l])
+        np.testing.assert_array_equal(fb, bs[l])
+    with pytest.raises(B.EmbError):
+        ctx.mlp_set_update_delay(1)

@@ -95,3 +95,49 @@ def test_bf16_operands_change_results_by_bf16_sized_amounts_only():
         assert np.linalg.norm(dWr - dWe) / np.linalg.norm(dWe) < 0.15
     x = np.array([1.0, 1.00390625, 1.005859375, -3.1415926, 1e-40, 65280.0], np.float32)
     np.testing.assert_array_equal(M.bf16(x), torch.tensor(x).to(torch.bfloat16).double().numpy())
+
+
+def test_delayed_updates_against_autograd_on_explicitly_stale_weights():
+    """delay d: the weights used at step t are w0 minus lr times the gradients of steps 0 .. t-d-1, each of
+    which was itself computed on its own stale weights.  Rebuilt here step by step with torch autograd on
+    explicit weight lists, for d = 2."""
+    widths = [12, 16, 8, 1]
+    Ws, bs = _net(3, widths)
+    data = [_data(10 + t, 24, 8, 4) for t in range(5)]
+    lr, d = 0.3, 2
+    m = M.MLP(Ws, bs, lr=lr, loss_mean=True, rounding=False, delay=d)
+    got_losses = [m.step(*data[t])[0] for t in range(5)]
+    # reference: weights_at[t] = weights seen by step t
+    gW, gb, want_losses = [], [], []
+    for t in range(5):
+        Wt = [w.astype(np.float64) for w in Ws]
+        bt = [b.astype(np.float64) for b in bs]
+        for k in range(max(0, t - d)):         # gradients of steps 0 .. t-d-1 have been applied, in order, in fp32
+            Wt = [(w - lr * g).astype(np.float32).astype(np.float64) for w, g in zip(Wt, gW[k])]
+            bt = [(b - lr * g).astype(np.float32).astype(np.float64) for b, g in zip(bt, gb[k])]
+        loss, _, dWs, dbs, _, _ = _torch_ref(Wt, bt, *data[t], True)
+        want_losses.append(loss)
+        gW.append(dWs)
+        gb.append(dbs)
+    np.testing.assert_allclose(got_losses, want_losses, rtol=1e-7)   # the step size is stored as fp32 in the oracle
+    assert abs(got_losses[2] - M.MLP(Ws, bs, lr=lr, rounding=False).step(*data[2])[0]) < 1e-12   # step d still sees w0
+    # the weights the oracle ends with: those step 4 saw (gradients 0 .. 4-d-1 applied)
+    Wend = [w.astype(np.float64) for w in Ws]
+    for k in range(4 - d):
+        Wend = [(w - lr * g).astype(np.float32).astype(np.float64) for w, g in zip(Wend, gW[k])]
+    for w, ref in zip(m.W, Wend):
+        np.testing.assert_allclose(w, ref, rtol=1e-6, atol=1e-7)
+
+
+def test_zero_delay_is_the_plain_step_and_a_long_delay_changes_nothing():
+    widths = [12, 16, 1]
+    Ws, bs = _net(4, widths)
+    data = [_data(20 + t, 16, 8, 4) for t in range(3)]
+    a, b = M.MLP(Ws, bs, lr=0.2, rounding=False), M.MLP(Ws, bs, lr=0.2, rounding=False, delay=0)
+    for t in range(3):
+        assert a.step(*data[t])[0] == b.step(*data[t])[0]
+    c = M.MLP(Ws, bs, lr=0.2, rounding=False, delay=7)
+    for t in range(3):
+        c.step(*data[t])
+    for w, w0 in zip(c.W, Ws):
+        np.testing.assert_array_equal(w, w0)
