@@ -79,6 +79,39 @@ def bench_codec(args, w, binding, torch, np) -> int:
     return 0
 
 
+def bench_gemm(args, binding, torch) -> int:
+    """The bf16 MFMA contraction of the dense step on its own, on the shapes config 3's step is made of
+    (batch 32768; C = A * Bt^T, operands already resident in HBM)."""
+    shapes = [("forward layer 1", 0, 32768, 4096, 10432), ("forward layer 2", 0, 32768, 2048, 4096),
+              ("weight gradient layer 1", 1, 10432, 4096, 32768), ("delta layer 1", 2, 32768, 4096, 2048),
+              ("gradient of the pooled activations", 1, 32768, 9920, 4096)]
+    out = []
+    for name, epi, M, N, K in shapes:
+        A = (torch.randn(M, K, device="cuda") * 0.1).to(torch.bfloat16)
+        Bt = (torch.randn(N, K, device="cuda") * 0.1).to(torch.bfloat16)
+        bias = torch.zeros(N, device="cuda")
+        mask = torch.ones(M, N, device="cuda", dtype=torch.bfloat16) if epi == 2 else None
+        for _ in range(max(args.warmup, 1)):
+            binding.mlp_gemm_nt(epi, A, Bt, bias, mask)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            binding.mlp_gemm_nt(epi, A, Bt, bias, mask)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        out.append({"product": name, "epilogue": epi, "M": M, "N": N, "K": K, "ms": round(ms, 4),
+                    "TFLOPs": round(2.0 * M * N * K / ms / 1e9, 1)})
+        del A, Bt, mask
+    best = max(o["TFLOPs"] for o in out)
+    print(json.dumps({"metric": "bf16 MFMA contraction C = A * Bt^T (fp32 accumulation), 1 GPU", "unit": "TFLOP/s",
+                      "n_gpus": 1, "steps": args.steps, "dtype": "bf16", "data": "synthetic", "products": out,
+                      "roofline": {"bound": "mfma", "achieved": best, "peak": 2500.0, "unit": "TFLOP/s",
+                                   "frac": round(best / 2500.0, 4), "traffic": None}}))
+    return 0
+
+
 def bench_indexed_forward(args, w, binding, torch, np, W) -> int:
     """The forward two ways on one batch: gather per bag (emb_lookup_pool) and from the index form, each unique
     row read once (emb_lookup_pool_indexed; the index form is built beforehand, outside the timed region, as if
@@ -224,6 +257,8 @@ def main() -> int:
                     help="instead of the training step, time the scaled-fp16 value codec on this config's pooled shape")
     ap.add_argument("--hybrid", action="store_true",
                     help="full hybrid step: lookup -> dense MLP step (bf16 MFMA) -> embedding update with the MLP's gradient")
+    ap.add_argument("--gemm", action="store_true",
+                    help="instead of the training step, time the dense step's bf16 MFMA contraction on config 3's shapes")
     ap.add_argument("--indexed-forward", action="store_true",
                     help="instead of the training step, time the forward per bag against the forward from the index form")
     ap.add_argument("--tau", type=int, default=None,
@@ -247,6 +282,8 @@ def main() -> int:
     binding.load_library()
     w = W.make_workload(args.config)
     cfg = w.cfg
+    if args.gemm:
+        return bench_gemm(args, binding, torch)
     if args.codec:
         return bench_codec(args, w, binding, torch, np)
     if args.hybrid:
