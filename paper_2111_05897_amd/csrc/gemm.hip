@@ -4,9 +4,9 @@
 //
 // k_gemm_nt: a 512-thread workgroup computes a 256x256 tile of C; its 8 waves sit 2x4 and own 128x64
 // each, i.e. 4x2 MFMA tiles of v_mfma_f32_32x32x16_bf16 (lane l feeds row/column l%32 with the 8
-// consecutive k values starting at 8*(l/32)).  K is walked in steps of 32 through a ring of four LDS
-// stages that global_load_lds_dwordx4 fills directly (no staging registers), three tiles ahead of the
-// products; rows are unpadded and XOR-swizzled against bank conflicts.  Workgroups are numbered so that
+// consecutive k values starting at 8*(l/32)).  K is walked in steps of 64 through two LDS stages that
+// global_load_lds_dwordx4 fills directly (no staging registers, whole 128-byte lines per row), one tile
+// ahead of the products; rows are unpadded and XOR-swizzled against bank conflicts.  Workgroups are numbered so that
 // the ones running together on an XCD cover a compact block of tiles and share their A and Bt strips in
 // that XCD's L2.
 #include "device_utils.h"
@@ -21,14 +21,14 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int BK = 32;              // K elements per LDS stage
+constexpr int BK = 64;              // K elements per LDS stage
 constexpr int kKUnit = 64;          // K must be a multiple of this; splits along K are counted in these units
-constexpr int kStages = 4;          // ring of LDS stages: tile i is multiplied while tiles i+1..i+3 arrive
+constexpr int kStages = 2;          // ring of LDS stages: tile i is multiplied while the later ones arrive
 // 512-thread workgroups: 8 waves sit 2 (M) x 4 (N); a wave owns WM x WN MFMA tiles of 32x32.
 constexpr int kGemmThreads = 512;
 constexpr int WM = 4, WN = 2;
 constexpr int BM = 2 * 32 * WM, BN = 4 * 32 * WN;  // 256 x 256
-constexpr int kRowBytes = BK * 2;                   // a staged row: 64 bytes = 4 chunks of 16, no padding
+constexpr int kRowBytes = BK * 2;                   // a staged row: chunks of 16 bytes, no padding
 constexpr int kStageBytes = (BM + BN) * kRowBytes;  // one LDS stage: A tile then Bt tile
 constexpr size_t kGemmLdsBytes = (size_t)kStages * kStageBytes;
 constexpr uint32_t kXcds = 8;
@@ -80,29 +80,40 @@ __global__ __launch_bounds__(kGemmThreads, 2) void k_gemm_nt(GemmArgs g) {
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   // Global -> LDS without passing through registers (global_load_lds_dwordx4): one wave instruction moves 64
-  // x 16 bytes to 1 KB of consecutive LDS, i.e. 16 staged rows; lane l lands on row l/4, chunk position l%4.
-  // Rows are not padded; instead chunk c of row r is kept at position c ^ ((r >> 2) & 3), which makes the
-  // fragment reads below (32 rows, one chunk each) hit every bank once.  The lane chooses the global chunk
+  // x 16 bytes to 1 KB of consecutive LDS, i.e. RPI staged rows of CPR chunks; lane l lands on row l / CPR,
+  // chunk position l % CPR.  Rows are not padded; instead chunk c of row r is kept at position
+  // c ^ ((r >> SWZ_SHIFT) & (CPR - 1)), which makes the fragment reads below (32 rows, one chunk each) hit
+  // every bank once.  The lane chooses the global chunk
   // that belongs at its position.  Rows past the end of A or Bt are replaced by the last valid row (their
   // products are never stored), so no load needs a predicate.
-  constexpr int kGroupsA = BM / 16, kGroupsB = BN / 16;            // 16-row groups per operand tile
+  constexpr int CPR = kRowBytes / 16;                               // 16-byte chunks per staged row
+  constexpr int RPI = kWave / CPR;                                  // rows one wave instruction stages
+  constexpr int SWZ_SHIFT = (256 / kRowBytes) == 4 ? 2 : 1;         // rows per 256 bytes of LDS, as a shift
+  static_assert(kRowBytes == 64 || kRowBytes == 128, "swizzle geometry");
+  constexpr int kGroupsA = BM / RPI, kGroupsB = BN / RPI;           // row groups per operand tile
   constexpr int kWaves = kGemmThreads / kWave;
   static_assert(kGroupsA % kWaves == 0 && kGroupsB % kWaves == 0, "whole wave instructions per stage");
   constexpr int LA = kGroupsA / kWaves, LB = kGroupsB / kWaves;     // loads per thread and stage
   const uint32_t kt0 = blockIdx.y * g.k_tiles_per_split;            // first K unit of this split
   const int uwave = __builtin_amdgcn_readfirstlane(wave);
-  const uint32_t chunk = (uint32_t)((lane & 3) ^ ((lane >> 4) & 3));
+  // position lane % CPR of row lane / CPR holds chunk pos ^ swz(row); the row groups start at multiples of RPI,
+  // which only matter to swz through (g * RPI) >> SWZ_SHIFT
+  auto chunk_of = [&](uint32_t row_in_tile) {
+    return (uint32_t)(lane % CPR) ^ ((row_in_tile >> SWZ_SHIFT) & (uint32_t)(CPR - 1));
+  };
   const char* srcA[LA];
   const char* srcB[LB];
 #pragma unroll
   for (int j = 0; j < LA; ++j) {
-    const uint32_t r = min((uint32_t)((j * kWaves + wave) * 16 + (lane >> 2)), g.M - 1 - m0);
-    srcA[j] = reinterpret_cast<const char*>(g.A + (size_t)(m0 + r) * g.lda + (size_t)kt0 * kKUnit + chunk * 8);
+    const uint32_t rt = (uint32_t)((j * kWaves + wave) * RPI + lane / CPR);
+    const uint32_t r = min(rt, g.M - 1 - m0);
+    srcA[j] = reinterpret_cast<const char*>(g.A + (size_t)(m0 + r) * g.lda + (size_t)kt0 * kKUnit + chunk_of(rt) * 8);
   }
 #pragma unroll
   for (int j = 0; j < LB; ++j) {
-    const uint32_t r = min((uint32_t)((j * kWaves + wave) * 16 + (lane >> 2)), g.N - 1 - n0);
-    srcB[j] = reinterpret_cast<const char*>(g.Bt + (size_t)(n0 + r) * g.ldb + (size_t)kt0 * kKUnit + chunk * 8);
+    const uint32_t rt = (uint32_t)((j * kWaves + wave) * RPI + lane / CPR);
+    const uint32_t r = min(rt, g.N - 1 - n0);
+    srcB[j] = reinterpret_cast<const char*>(g.Bt + (size_t)(n0 + r) * g.ldb + (size_t)kt0 * kKUnit + chunk_of(rt) * 8);
   }
   char* lds_bytes = reinterpret_cast<char*>(lds);
   auto request = [&](uint32_t tile, int stage) {  // tile: index of the 32-wide K tile inside this split
@@ -116,7 +127,8 @@ __global__ __launch_bounds__(kGemmThreads, 2) void k_gemm_nt(GemmArgs g) {
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(srcB[j] + (size_t)tile * kRowBytes),
                                        (__attribute__((address_space(3))) void*)(dst + BM * kRowBytes + (j * kWaves + uwave) * 1024), 16, 0, 0);
   };
-  const uint32_t swz = (uint32_t)((lane >> 2) & 3);
+  // fragment rows are base + lane % 32 with base a multiple of 32, so swz(row) depends on the lane only
+  const uint32_t swz = (uint32_t)(((lane & 31) >> SWZ_SHIFT) & (CPR - 1));
   static_assert((kStages - 2) * (LA + LB) <= 15, "the wait below encodes its count in four bits");
   auto compute = [&](int stage) {
     const char* As = lds_bytes + stage * kStageBytes;
