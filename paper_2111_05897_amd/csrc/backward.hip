@@ -52,16 +52,16 @@ __device__ __forceinline__ void finish_update(T* __restrict__ w, float* __restri
     v.y = fmaf(-step, G.y, v.y);
     v.z = fmaf(-step, G.z, v.z);
     v.w = fmaf(-step, G.w, v.w);
-    if (lane == 0) accs[row] = a;
+    if (lane == 0) __builtin_nontemporal_store(a, accs + row);
   }
-  store_frag4(p, v);
+  store_frag4_stream(p, v);
 }
 
 template <typename T, int D, int OPT>
 __device__ __forceinline__ void apply_update(T* __restrict__ w, float* __restrict__ accs, uint32_t row, float4 G,
                                              int lane, float lr, float eps) {
-  const float4 v = load_frag4(w + (size_t)row * D + lane * 4);
-  const float a_old = OPT == 0 ? 0.f : accs[row];
+  const float4 v = load_frag4_stream(w + (size_t)row * D + lane * 4);
+  const float a_old = OPT == 0 ? 0.f : __builtin_nontemporal_load(accs + row);
   finish_update<T, D, OPT>(w, accs, row, G, v, a_old, lane, lr, eps);
 }
 
@@ -120,8 +120,8 @@ __global__ __launch_bounds__(kBlock) void k_tile_reduce_update(TileArgs a) {
   // stage the tile's (key, bag) pairs in LDS with coalesced loads
   for (uint32_t e = lane; e < kTile; e += LG) {
     const bool ok = p0 + e < p1;
-    s_key[grp][e] = ok ? keys[p0 + e] : 0u;
-    s_bag[grp][e] = ok ? bags[p0 + e] : 0u;
+    s_key[grp][e] = ok ? __builtin_nontemporal_load(keys + p0 + e) : 0u;
+    s_bag[grp][e] = ok ? __builtin_nontemporal_load(bags + p0 + e) : 0u;
   }
   __syncthreads();
   if (!in_list) return;
@@ -156,8 +156,8 @@ __global__ __launch_bounds__(kBlock) void k_tile_reduce_update(TileArgs a) {
       // a run that starts here and ends inside the tile is updated by this group: fetch its row now
       const bool need_row = start[j] && !(cont_out && k[j] == last_key);
       const uint32_t row = k[j] - a.key_base;
-      wr[j] = need_row ? load_frag4(w + (size_t)row * D + lane * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
-      av[j] = (need_row && OPT != 0) ? a.accs[row] : 0.f;
+      wr[j] = need_row ? load_frag4_stream(w + (size_t)row * D + lane * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+      av[j] = (need_row && OPT != 0) ? __builtin_nontemporal_load(a.accs + row) : 0.f;
     }
     prev = k[SC - 1];
 #pragma unroll
@@ -224,8 +224,8 @@ __global__ __launch_bounds__(kBlock) void k_fixup_short(FixupArgs a) {
     const uint32_t np = t1 - t0 + 1;
     if (np > kShortSpan) continue;  // left to k_fixup_long
     const uint32_t row = key - a.key_base;
-    const float4 v = load_frag4(w + (size_t)row * D + lane * 4);  // in flight together with the partials
-    const float a_old = OPT == 0 ? 0.f : a.accs[row];
+    const float4 v = load_frag4_stream(w + (size_t)row * D + lane * 4);  // in flight together with the partials
+    const float a_old = OPT == 0 ? 0.f : __builtin_nontemporal_load(a.accs + row);
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     for (uint32_t k0 = 0; k0 < np; k0 += 4) {
       float4 pv[4];

@@ -70,6 +70,28 @@ __device__ __forceinline__ void store_frag4(bf16_t* p, float4 v) {
   *reinterpret_cast<uint2*>(p) = o;
 }
 
+// The same with the streaming hint: for data a kernel touches once (a table row being updated), so that it
+// does not displace what the kernel re-reads (gradient rows) from the caches.
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float4 load_frag4_stream(const float* p) {
+  const f32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(p));
+  return make_float4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ float4 load_frag4_stream(const bf16_t* p) {
+  const u32x2_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t*>(p));
+  return make_float4(__uint_as_float(v[0] << 16), __uint_as_float(v[0] & 0xFFFF0000u), __uint_as_float(v[1] << 16),
+                     __uint_as_float(v[1] & 0xFFFF0000u));
+}
+__device__ __forceinline__ void store_frag4_stream(float* p, float4 v) {
+  const f32x4_t o = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(o, reinterpret_cast<f32x4_t*>(p));
+}
+__device__ __forceinline__ void store_frag4_stream(bf16_t* p, float4 v) {
+  const u32x2_t o = {f32_to_bf16(v.x) | (f32_to_bf16(v.y) << 16), f32_to_bf16(v.z) | (f32_to_bf16(v.w) << 16)};
+  __builtin_nontemporal_store(o, reinterpret_cast<u32x2_t*>(p));
+}
+
 // ---- block-wide exclusive scan over kBlock threads; s_w: shared uint32_t[kWavesPerBlock] ----
 __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* s_w, uint32_t* total) {
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;

@@ -87,7 +87,8 @@ __global__ __launch_bounds__(kBlock) void k_gather_pool(GatherArgs a) {
 #pragma unroll
     for (int q = 0; q < IPL; ++q) {
       const int idx = cbase + q * LANES + lane;
-      uint32_t r = idx < end ? hash_row(ids[idx], salt, a.rows, a.mask, a.mix) : 0u;
+      // ids are read once and pooled rows written once: streamed past the caches, which are kept for table rows
+      uint32_t r = idx < end ? hash_row(__builtin_nontemporal_load(ids + idx), salt, a.rows, a.mask, a.mix) : 0u;
       if (a.where) {  // table behind the LRU cache: the row's slot (every row of the batch was admitted)
         const int32_t slot = idx < end ? a.where[r] : 0;
         r = slot >= 0 ? (uint32_t)slot : 0u;
@@ -119,7 +120,11 @@ __global__ __launch_bounds__(kBlock) void k_gather_pool(GatherArgs a) {
   float* out = a.pooled + (size_t)b * a.width + a.slot_col[slot] + lane * VEC;
 #pragma unroll
   for (int e = 0; e < VEC; e += 4)
-    *reinterpret_cast<float4*>(out + e) = make_float4(acc[e], acc[e + 1], acc[e + 2], acc[e + 3]);
+    {
+      typedef float f32x4 __attribute__((ext_vector_type(4)));
+      const f32x4 v = {acc[e], acc[e + 1], acc[e + 2], acc[e + 3]};
+      __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(out + e));
+    }
 }
 
 // 8 lanes per bag; lane j takes ids beg+j, beg+j+8, ...
