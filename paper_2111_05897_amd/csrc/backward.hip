@@ -32,6 +32,31 @@ __device__ __forceinline__ void kahan_add4(float4& s, float4& c, float4 x) {
 // the row's gradient; v = the lane's part of the row, a_old = the row's accumulator (both may have
 // been fetched long before).  OPT 0: SGD.  OPT 1: row-wise Adagrad (mean of G^2 over the row feeds
 // one accumulator; eps outside the square root).
+// A table row is touched once per update.  When a row fills whole cache lines (>= 128 bytes) it is read and
+// written with the streaming hint, so that it does not displace the gradient rows the kernel re-reads; smaller
+// rows share their lines with neighbours that other lane-groups touch, and there the hint was measured to cost
+// (16..64-byte rows of the mixed-width configuration: 7.7 -> 8.7 ms), so they take the ordinary path.
+template <typename T, int D>
+struct RowIo {
+  static constexpr bool kStream = D * sizeof(T) >= 128;
+  static __device__ __forceinline__ float4 load(const T* p) {
+    if constexpr (kStream) return load_frag4_stream(p);
+    else return load_frag4(p);
+  }
+  static __device__ __forceinline__ void store(T* p, float4 v) {
+    if constexpr (kStream) store_frag4_stream(p, v);
+    else store_frag4(p, v);
+  }
+  static __device__ __forceinline__ float load_acc(const float* p) {
+    if constexpr (kStream) return __builtin_nontemporal_load(p);
+    else return *p;
+  }
+  static __device__ __forceinline__ void store_acc(float* p, float a) {
+    if constexpr (kStream) __builtin_nontemporal_store(a, p);
+    else *p = a;
+  }
+};
+
 template <typename T, int D, int OPT>
 __device__ __forceinline__ void finish_update(T* __restrict__ w, float* __restrict__ accs, uint32_t row, float4 G,
                                               float4 v, float a_old, int lane, float lr, float eps) {
@@ -52,16 +77,16 @@ __device__ __forceinline__ void finish_update(T* __restrict__ w, float* __restri
     v.y = fmaf(-step, G.y, v.y);
     v.z = fmaf(-step, G.z, v.z);
     v.w = fmaf(-step, G.w, v.w);
-    if (lane == 0) __builtin_nontemporal_store(a, accs + row);
+    if (lane == 0) RowIo<T, D>::store_acc(accs + row, a);
   }
-  store_frag4_stream(p, v);
+  RowIo<T, D>::store(p, v);
 }
 
 template <typename T, int D, int OPT>
 __device__ __forceinline__ void apply_update(T* __restrict__ w, float* __restrict__ accs, uint32_t row, float4 G,
                                              int lane, float lr, float eps) {
-  const float4 v = load_frag4_stream(w + (size_t)row * D + lane * 4);
-  const float a_old = OPT == 0 ? 0.f : __builtin_nontemporal_load(accs + row);
+  const float4 v = RowIo<T, D>::load(w + (size_t)row * D + lane * 4);
+  const float a_old = OPT == 0 ? 0.f : RowIo<T, D>::load_acc(accs + row);
   finish_update<T, D, OPT>(w, accs, row, G, v, a_old, lane, lr, eps);
 }
 
@@ -120,8 +145,8 @@ __global__ __launch_bounds__(kBlock) void k_tile_reduce_update(TileArgs a) {
   // stage the tile's (key, bag) pairs in LDS with coalesced loads
   for (uint32_t e = lane; e < kTile; e += LG) {
     const bool ok = p0 + e < p1;
-    s_key[grp][e] = ok ? __builtin_nontemporal_load(keys + p0 + e) : 0u;
-    s_bag[grp][e] = ok ? __builtin_nontemporal_load(bags + p0 + e) : 0u;
+    s_key[grp][e] = ok ? keys[p0 + e] : 0u;
+    s_bag[grp][e] = ok ? bags[p0 + e] : 0u;
   }
   __syncthreads();
   if (!in_list) return;
@@ -156,8 +181,8 @@ __global__ __launch_bounds__(kBlock) void k_tile_reduce_update(TileArgs a) {
       // a run that starts here and ends inside the tile is updated by this group: fetch its row now
       const bool need_row = start[j] && !(cont_out && k[j] == last_key);
       const uint32_t row = k[j] - a.key_base;
-      wr[j] = need_row ? load_frag4_stream(w + (size_t)row * D + lane * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
-      av[j] = (need_row && OPT != 0) ? __builtin_nontemporal_load(a.accs + row) : 0.f;
+      wr[j] = need_row ? RowIo<T, D>::load(w + (size_t)row * D + lane * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+      av[j] = (need_row && OPT != 0) ? RowIo<T, D>::load_acc(a.accs + row) : 0.f;
     }
     prev = k[SC - 1];
 #pragma unroll
@@ -224,8 +249,8 @@ __global__ __launch_bounds__(kBlock) void k_fixup_short(FixupArgs a) {
     const uint32_t np = t1 - t0 + 1;
     if (np > kShortSpan) continue;  // left to k_fixup_long
     const uint32_t row = key - a.key_base;
-    const float4 v = load_frag4_stream(w + (size_t)row * D + lane * 4);  // in flight together with the partials
-    const float a_old = OPT == 0 ? 0.f : __builtin_nontemporal_load(a.accs + row);
+    const float4 v = RowIo<T, D>::load(w + (size_t)row * D + lane * 4);  // in flight together with the partials
+    const float a_old = OPT == 0 ? 0.f : RowIo<T, D>::load_acc(a.accs + row);
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     for (uint32_t k0 = 0; k0 < np; k0 += 4) {
       float4 pv[4];

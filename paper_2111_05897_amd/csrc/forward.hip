@@ -23,6 +23,7 @@ struct GatherArgs {
   uint32_t n_slots_t, S, width;
   uint32_t n_local_bags;       // B * n_slots_t
   int mix;
+  int stream_out;              // 1: the table serves every slot, so a launch writes whole rows of `pooled`
   float* pooled;
 };
 
@@ -87,8 +88,10 @@ __global__ __launch_bounds__(kBlock) void k_gather_pool(GatherArgs a) {
 #pragma unroll
     for (int q = 0; q < IPL; ++q) {
       const int idx = cbase + q * LANES + lane;
-      // ids are read once and pooled rows written once: streamed past the caches, which are kept for table rows
-      uint32_t r = idx < end ? hash_row(__builtin_nontemporal_load(ids + idx), salt, a.rows, a.mask, a.mix) : 0u;
+      // ids are read once and pooled rows written once: with one table they are streamed past the caches, which
+      // are kept for table rows (with several tables the launches share cache lines of both arrays)
+      const uint64_t id = idx < end ? (a.stream_out ? __builtin_nontemporal_load(ids + idx) : ids[idx]) : 0ull;
+      uint32_t r = idx < end ? hash_row(id, salt, a.rows, a.mask, a.mix) : 0u;
       if (a.where) {  // table behind the LRU cache: the row's slot (every row of the batch was admitted)
         const int32_t slot = idx < end ? a.where[r] : 0;
         r = slot >= 0 ? (uint32_t)slot : 0u;
@@ -120,10 +123,12 @@ __global__ __launch_bounds__(kBlock) void k_gather_pool(GatherArgs a) {
   float* out = a.pooled + (size_t)b * a.width + a.slot_col[slot] + lane * VEC;
 #pragma unroll
   for (int e = 0; e < VEC; e += 4)
-    {
+    if (a.stream_out) {  // this launch writes whole pooled rows: streamed, nothing re-reads them here
       typedef float f32x4 __attribute__((ext_vector_type(4)));
       const f32x4 v = {acc[e], acc[e + 1], acc[e + 2], acc[e + 3]};
       __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(out + e));
+    } else {  // several tables share the pooled rows: their pieces of a cache line must meet in the cache
+      *reinterpret_cast<float4*>(out + e) = make_float4(acc[e], acc[e + 1], acc[e + 2], acc[e + 3]);
     }
 }
 
@@ -319,6 +324,7 @@ hipError_t launch_gather_pool(const TableView& t, const SlotArrays& sl, const ui
   a.width = width;
   a.n_local_bags = B * t.n_slots;
   a.mix = mix;
+  a.stream_out = t.n_slots == S ? 1 : 0;
   a.pooled = pooled;
   return t.dtype == 1 ? dispatch_dim<bf16_t>(t.dim, a, stream) : dispatch_dim<float>(t.dim, a, stream);
 }
