@@ -414,11 +414,16 @@ def main() -> int:
     # bytes per launch between L2 and the fabric, from the committed rocprofv3 --pmc summary (FETCH_SIZE and
     # WRITE_SIZE runs of this same script, scaled by a plain copy kernel); null if no summary covers the workload
     traffic_file = os.path.join(ROOT, "profiles", f"{w.name}_hbm_traffic.txt")
+    measured_step_bytes = None
     if os.path.exists(traffic_file):
+        per_launch = ("gather_pool", "build_keys", "reduce_update")   # the other stages are listed per step
+        measured_step_bytes = 0
         for line in open(traffic_file):
             f = line.split()
-            if len(f) == 3 and f[0] == "traffic" and f[1] == dom:
-                roofline["traffic"] = int(f[2])
+            if len(f) == 3 and f[0] == "traffic":
+                if f[1] == dom:
+                    roofline["traffic"] = int(f[2])
+                measured_step_bytes += int(f[2]) * (launches.get(f[1], 1) if f[1] in per_launch else 1)
 
     out = {
         "metric": "embedding IDs/sec (lookup+bwd+update), 1 GPU", "value": round(ids_per_s, 1), "unit": "IDs/s",
@@ -433,6 +438,12 @@ def main() -> int:
                    "schedule": "staleness-1 overlap, two streams" if args.overlap else "synchronous, one stream"},
         "effective_GBps_step": round(ab["step"] / (ms_per_step * 1e-3) / 1e9, 1),
         "effective_frac_of_hbm_peak": round(ab["step"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        # counter-measured bytes of a whole step (all stages of the committed FETCH_SIZE / WRITE_SIZE summary) over
+        # this run's step time; the counters sit between L2 and the fabric (memory-side cache hits included)
+        "measured_GBps_step": (round(measured_step_bytes / (ms_per_step * 1e-3) / 1e9, 1)
+                               if measured_step_bytes and not args.overlap and cache_report is None else None),
+        "measured_frac_of_hbm_peak": (round(measured_step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+                                      if measured_step_bytes and not args.overlap and cache_report is None else None),
         "stage_ms_per_step": {k: round(v, 4) for k, v in per_step_ms.items()},
         "stage_GBps": {k: round(ab[k] / (per_step_ms[k] * 1e-3) / 1e9, 1) for k in per_step_ms if k in ab},
         "setup_s": round(setup_s, 1),
