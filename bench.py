@@ -101,8 +101,20 @@ def bench_gemm(args, binding, torch) -> int:
         e1.record()
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / args.steps
+        # the vendor library's plain product of the same operands (no epilogue), through torch.matmul: a reference
+        # beside the figure, not part of the path
+        for _ in range(max(args.warmup, 1)):
+            torch.matmul(A, Bt.t())
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            torch.matmul(A, Bt.t())
+        e1.record()
+        torch.cuda.synchronize()
+        lib_ms = e0.elapsed_time(e1) / args.steps
         out.append({"product": name, "epilogue": epi, "M": M, "N": N, "K": K, "ms": round(ms, 4),
-                    "TFLOPs": round(2.0 * M * N * K / ms / 1e9, 1)})
+                    "TFLOPs": round(2.0 * M * N * K / ms / 1e9, 1),
+                    "library_reference_TFLOPs": round(2.0 * M * N * K / lib_ms / 1e9, 1)})
         del A, Bt, mask
     best = max(o["TFLOPs"] for o in out)
     print(json.dumps({"metric": "bf16 MFMA contraction C = A * Bt^T (fp32 accumulation), 1 GPU", "unit": "TFLOP/s",
