@@ -113,7 +113,6 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(const uint32_t* __rest
   __shared__ uint32_t s_w[kWavesPerBlock];
 
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
-  const uint64_t lt_mask = (1ull << lane) - 1ull;
   const bool owner = tid * DPT < NB;
 
   // Where this block's first pair of each owned digit goes: pairs of smaller digits anywhere, plus
@@ -160,20 +159,26 @@ __global__ __launch_bounds__(kBlock) void k_radix_scatter(const uint32_t* __rest
       const uint32_t off = wave * (kWave * kSortItems) + k * kWave + lane;
       const bool valid = off < tile_cnt;
       const uint32_t d = (key[k] >> shift) & (NB - 1);
-      uint64_t peers = __ballot(valid);
+      // peers: the valid lanes of this wave whose key has the same digit (includes this lane), kept as two 32-bit
+      // halves.  Per bit: all-ones or zero from the lane's own bit, one ballot, and peers &= ~(ballot ^ own), which
+      // is the ballot where the own bit is set and its complement where it is not.
+      const uint64_t vmask = __ballot(valid);
+      uint32_t plo = (uint32_t)vmask, phi = (uint32_t)(vmask >> 32);
 #pragma unroll
       for (int b = 0; b < BITS; ++b) {
-        const bool bit = (d >> b) & 1u;
-        const uint64_t bt = __ballot(bit);
-        peers &= bit ? bt : ~bt;
+        const uint32_t own = 0u - ((d >> b) & 1u);
+        const uint64_t bt = __ballot(own != 0u);
+        plo &= ~((uint32_t)bt ^ own);
+        phi &= ~((uint32_t)(bt >> 32) ^ own);
       }
       lrank[k] = 0;
-      if (valid) {  // peers: the valid lanes of this wave whose key has the same digit (includes this lane)
-        const int leader = __ffsll((unsigned long long)peers) - 1;
+      if (valid) {
+        const int leader = plo ? __ffs((int)plo) - 1 : 32 + __ffs((int)phi) - 1;
         uint32_t old = 0;
-        if (lane == leader) old = atomicAdd(&s_cnt[wave][d], (uint32_t)__popcll(peers));
+        if (lane == leader) old = atomicAdd(&s_cnt[wave][d], (uint32_t)(__popc(plo) + __popc(phi)));
         old = __shfl(old, leader);
-        lrank[k] = old + (uint32_t)__popcll(peers & lt_mask);
+        // peers below this lane: mbcnt counts the bits of a mask that belong to lower lanes
+        lrank[k] = old + __builtin_amdgcn_mbcnt_hi(phi, __builtin_amdgcn_mbcnt_lo(plo, 0u));
       }
     }
     __syncthreads();
