@@ -340,21 +340,30 @@ __global__ __launch_bounds__(kBlock) void k_fixup_long(FixupArgs a) {
   }
 }
 
-// tile_key[t] = (table of the tile's first key) << 8 | (first bag of tile t) >> shift, tile_val[t] = t.
+// tile_key[t] = (table of the tile's first key) << 8 | bucket << 1 | mixed, tile_val[t] = t.  A tile that lies
+// inside one key's segment (first key = last key) is put in bucket (first bag of the tile) >> (shift + 1), at
+// most 127; a tile with several keys ("mixed": runs end inside it, the optimizer is applied many times) has no
+// bag order to follow and is put in bucket t * 128 / n_tiles.  In every bucket the single-key tiles run first,
+// then the mixed ones: the four tiles a wave holds are then mostly of one kind (the waves of single-key tiles
+// never execute the optimizer's instructions), while over time the launch keeps its blend of gradient reads
+// (single-key tiles) and table-row traffic (mixed tiles).
 __global__ __launch_bounds__(kBlock) void k_tile_keys(const uint32_t* __restrict__ keys,
-                                                      const uint32_t* __restrict__ bags, uint32_t n_tiles, int shift,
-                                                      const uint32_t* __restrict__ key_base, uint32_t num_tables,
-                                                      uint32_t* __restrict__ tile_key,
+                                                      const uint32_t* __restrict__ bags, uint32_t n, uint32_t n_tiles,
+                                                      int shift, const uint32_t* __restrict__ key_base,
+                                                      uint32_t num_tables, uint32_t* __restrict__ tile_key,
                                                       uint32_t* __restrict__ tile_val) {
   const uint32_t t = blockIdx.x * kBlock + threadIdx.x;
   if (t >= n_tiles) return;
+  const size_t p0 = (size_t)t * kTile;
+  const size_t p1 = p0 + kTile < n ? p0 + kTile : n;
+  const uint32_t k = keys[p0];
   uint32_t table = 0;
-  if (num_tables > 1) {
-    const uint32_t k = keys[(size_t)t * kTile];
+  if (num_tables > 1)
     while (table + 1 < num_tables && k >= key_base[table + 1]) ++table;
-  }
-  const uint32_t bucket = bags[(size_t)t * kTile] >> shift;
-  tile_key[t] = (table << 8) | (bucket < 255u ? bucket : 255u);
+  const bool mixed = keys[p1 - 1] != k;
+  uint32_t bucket = mixed ? (uint32_t)(((uint64_t)t * 128u) / n_tiles) : bags[p0] >> (shift + 1);
+  if (bucket > 127u) bucket = 127u;
+  tile_key[t] = (table << 8) | (bucket << 1) | (mixed ? 1u : 0u);
   tile_val[t] = t;
 }
 
@@ -433,7 +442,7 @@ hipError_t launch_tile_order(const uint32_t* keys, const uint32_t* bags, uint32_
   const uint32_t n_tiles = (n + kTile - 1) / kTile;
   *perm_out = nullptr;
   if (n_tiles < 2) return hipSuccess;  // nothing to order
-  hipLaunchKernelGGL(k_tile_keys, dim3((n_tiles + kBlock - 1) / kBlock), dim3(kBlock), 0, stream, keys, bags, n_tiles,
+  hipLaunchKernelGGL(k_tile_keys, dim3((n_tiles + kBlock - 1) / kBlock), dim3(kBlock), 0, stream, keys, bags, n, n_tiles,
                      shift, key_base_dev, num_tables, tile_key[0], tile_val[0]);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
