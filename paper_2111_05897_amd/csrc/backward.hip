@@ -96,6 +96,7 @@ struct TileArgs {
   uint32_t n;
   const float* d_pooled;
   uint32_t S, width;
+  uint32_t s_mul, s_shift;  // bag / S as a multiply-high and shifts (div_by_S below)
   const uint32_t* slot_col;
   int uniform;
   float* partials;
@@ -108,10 +109,18 @@ struct TileArgs {
   float lr, eps;
 };
 
+// n / S for any 32-bit n, with the constants the host prepared for S (round-up method of Granlund and
+// Montgomery: S = 1 is s_mul = 0, s_shift = 0, where the formula below gives n itself).  The division instruction
+// sequence the compiler emits for a run-time divisor is about twenty instructions, paid per entry.
+__device__ __forceinline__ uint32_t div_by_S(const TileArgs& a, uint32_t n) {
+  const uint32_t t = __umulhi(a.s_mul, n);
+  return (t + ((n - t) >> (a.s_shift ? 1 : 0))) >> (a.s_shift ? a.s_shift - 1 : 0);
+}
+
 template <int D>
 __device__ __forceinline__ const float* grad_ptr(const TileArgs& a, uint32_t bag, int lane) {
   if (a.uniform) return a.d_pooled + (size_t)bag * D + lane * 4;
-  const uint32_t b = bag / a.S;
+  const uint32_t b = div_by_S(a, bag);
   const uint32_t s = bag - b * a.S;
   return a.d_pooled + (size_t)b * a.width + a.slot_col[s] + lane * 4;
 }
@@ -471,6 +480,12 @@ hipError_t launch_tile_reduce_update(const TableView& t, const BackwardArgs& b, 
   a.n = b.n;
   a.d_pooled = b.d_pooled;
   a.S = b.S;
+  {  // l = ceil(log2 S), m = floor(2^32 (2^l - S) / S) + 1
+    uint32_t l = 0;
+    while ((1ull << l) < b.S) ++l;
+    a.s_shift = l;
+    a.s_mul = l ? (uint32_t)((((1ull << l) - b.S) << 32) / b.S + 1) : 0u;
+  }
   a.width = b.width;
   a.slot_col = b.slot_col;
   a.uniform = b.uniform;
