@@ -45,7 +45,7 @@ def _draw(seed):
     return cfg, bsz, batches, grads
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(48))
 def test_random_configuration(B, seed):
     cfg, bsz, batches, grads = _draw(seed)
     w = W.Workload(f"random{seed}", 0, cfg, bsz, "uniform", 0, 1, "uniform", 1, seed=seed)
