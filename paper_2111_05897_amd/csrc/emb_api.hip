@@ -631,7 +631,7 @@ static int emb_backward_update_impl(emb_ctx* ctx, const emb_batch* batch, const 
   a.long_list = ctx->long_list;
   {
     StageTimer tm(ctx, ST_TILE_ORDER, stream);
-    // 256 buckets of consecutive bags (sample-major), whatever the batch size
+    // shift that leaves 8 bits of the bag index (the tile keys use 7: 128 buckets of consecutive bags, sample-major)
     int shift = bit_length((uint64_t)batch->batch_size * ctx->S - 1) - 8;
     if (shift < 0) shift = 0;
     CKH(launch_tile_order(a.keys, a.bags, n, shift, ctx->key_base_dev, (uint32_t)ctx->tables.size(), ctx->tile_key,

@@ -2,7 +2,7 @@
 //
 // One radix pass = three kernels.  hist: every block counts the digits of its contiguous chunk.
 // scan: one block per digit turns that digit's per-block counts into exclusive prefixes and
-// emits the digit total.  scatter: every block walks its chunk in tiles of 2048 pairs; inside a
+// emits the digit total.  scatter: every block walks its chunk in tiles of kSortTile pairs; inside a
 // tile each wave ranks its keys with ballot-based digit matching (stable: rank = number of
 // earlier pairs of the tile with the same digit), the tile is reordered digit-major through LDS,
 // and written out so that consecutive lanes store to consecutive addresses of a digit's region.
