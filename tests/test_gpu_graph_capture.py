@@ -65,3 +65,48 @@ def test_captured_step_replays_like_direct_calls(B, tables, slots, opt):
     del graph
     graphed.close()
     direct.close()
+
+
+def test_captured_dense_step_replays_like_direct_calls(B):
+    """mlp_step (forward, loss, backward, SGD step: a few dozen kernels, split-K workspaces included) captured once
+    and replayed three times against the same call enqueued directly: gradients of the pooled activations, losses
+    and the updated weights, bit for bit."""
+    import torch
+    P, Dn, bsz = 192, 64, 256
+    widths = [P + Dn, 256, 128, 1]
+    Ws, bs = W.make_mlp_params(widths, 5)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1)
+    pooled = torch.randn((bsz, P), generator=gen, device="cuda")
+    dense = torch.randn((bsz, Dn), generator=gen, device="cuda")
+    labels = (torch.rand((bsz,), generator=gen, device="cuda") < 0.3).float()
+    out = {}
+    for mode in ("direct", "graph"):
+        mlp = B.MlpContext(widths, P, Dn, bsz, 0.1, Ws, bs, loss_mean=True)
+        d_pooled = torch.empty_like(pooled)
+        if mode == "graph":
+            side, graph = torch.cuda.Stream(), torch.cuda.CUDAGraph()
+            torch.cuda.synchronize()
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(graph, stream=side):
+                    _, loss = mlp.mlp_step(pooled, dense, labels, d_pooled)
+            torch.cuda.synchronize()
+        seen = []
+        for _ in range(3):
+            if mode == "graph":
+                graph.replay()
+            else:
+                _, loss = mlp.mlp_step(pooled, dense, labels, d_pooled)
+            torch.cuda.synchronize()
+            seen.append((d_pooled.clone(), loss.clone()))
+            d_pooled.fill_(float("nan"))
+            torch.randn(1 << 16, device="cuda").sum().item()     # eager work between the replays
+        out[mode] = (seen, [mlp.mlp_read_weights(l) for l in range(len(widths) - 1)])
+        if mode == "graph":
+            del graph
+        mlp.close()
+    for (dp_d, loss_d), (dp_g, loss_g) in zip(out["direct"][0], out["graph"][0]):
+        assert torch.equal(dp_d, dp_g) and torch.equal(loss_d, loss_g)
+    for (w_d, b_d), (w_g, b_g) in zip(out["direct"][1], out["graph"][1]):
+        np.testing.assert_array_equal(w_d, w_g)
+        np.testing.assert_array_equal(b_d, b_g)
