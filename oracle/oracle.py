@@ -51,6 +51,8 @@ def _configure(L):
     L.orc_mix64.argtypes = [C.c_uint64]
     L.orc_round_bf16.restype = C.c_float
     L.orc_round_bf16.argtypes = [C.c_float]
+    L.orc_round_bf16_once.restype = C.c_float
+    L.orc_round_bf16_once.argtypes = [C.c_double]
     L.orc_init_value.restype = C.c_float
     L.orc_init_value.argtypes = [C.c_uint64, C.c_uint32, C.c_uint64, C.c_uint32, C.c_uint32, C.c_float, C.c_float]
     L.orc_create.restype = C.c_void_p
@@ -85,6 +87,11 @@ def round_bf16(x: np.ndarray) -> np.ndarray:
     x = np.asarray(x, dtype=np.float32)
     f = lib().orc_round_bf16
     return np.array([f(C.c_float(v)) for v in x.ravel()], dtype=np.float32).reshape(x.shape)
+
+
+def round_bf16_once(v: float) -> float:
+    """fp64 -> bf16 in one rounding (what a bf16 table stores of an fp64 result), widened to fp32."""
+    return float(lib().orc_round_bf16_once(C.c_double(v)))
 
 
 def init_value(seed, t, r, dim, d, lo, hi) -> float:

@@ -28,12 +28,15 @@
 //             Adagrad (one fp32 accumulator per row, fed by the mean over the row of
 //             the squared gradient, eps outside the square root).
 //
-// All floating-point accumulation is fp64; each stored quantity is rounded once.
+// All floating-point accumulation is fp64; each stored quantity is rounded once, from the
+// fp64 result straight to its storage type (fp32, or bf16 for bf16 tables: never fp64 -> fp32 -> bf16,
+// whose two roundings can differ from one at a bf16 tie).
 // Parity pins live in tests/test_oracle_*.py.
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
 #include <cstring>
+#include <limits>
 #include <unordered_map>
 #include <vector>
 
@@ -69,6 +72,26 @@ float round_bf16(float x) {
   float r;
   std::memcpy(&r, &u, 4);
   return r;
+}
+
+// fp64 -> bf16 in ONE rounding (nearest, ties to even), returned widened to fp32.  A bf16 value is
+// m * 2^(e-7) with an 8-bit integer m (7 stored bits + the leading one) and the exponent range of
+// fp32; below 2^-126 the spacing stays 2^-133 (subnormals).  So: find the spacing for |v|'s binade,
+// divide (exact: a power of two), round the quotient to the nearest integer, ties to even, multiply
+// back (exact).  Beyond the largest finite bf16 the result is infinity.
+float round_bf16_once(double v) {
+  if (std::isnan(v)) return std::numeric_limits<float>::quiet_NaN();
+  if (std::isinf(v) || v == 0.0) return (float)v;
+  int e;
+  std::frexp(v, &e);           // |v| = f * 2^e with f in [0.5, 1): the binade is [2^(e-1), 2^e)
+  int q = e - 1 - 7;           // spacing 2^q of bf16 values in that binade
+  if (q < -133) q = -133;      // subnormal range
+  const double scaled = std::ldexp(v, -q);
+  const double r = std::nearbyint(scaled);   // the default rounding mode: to nearest, ties to even
+  const double out = std::ldexp(r, q);
+  const double max_bf16 = std::ldexp(255.0, 127 - 7);  // 0x7F7F: (2 - 2^-7) * 2^127
+  if (std::fabs(out) > max_bf16) return std::copysign(std::numeric_limits<float>::infinity(), (float)v);
+  return (float)out;           // exact: every finite bf16 value is an fp32 value
 }
 
 // Initial value of element d of row r of table t: 24 random bits k from a counter
@@ -111,10 +134,7 @@ struct Oracle {
   std::vector<double> grad;  // ragged: dim(table(u)) doubles per unique key u
 };
 
-float store_round(const Table& t, double v) {
-  float f = (float)v;
-  return t.dtype == DT_BF16 ? round_bf16(f) : f;
-}
+float store_round(const Table& t, double v) { return t.dtype == DT_BF16 ? round_bf16_once(v) : (float)v; }
 
 void init_row(const Oracle& o, uint32_t ti, const Table& t, uint64_t r, float* dst) {
   for (uint32_t d = 0; d < t.dim; ++d) {
@@ -149,6 +169,7 @@ extern "C" {
 
 uint64_t orc_mix64(uint64_t z) { return mix64(z); }
 float orc_round_bf16(float x) { return round_bf16(x); }
+float orc_round_bf16_once(double v) { return round_bf16_once(v); }
 float orc_init_value(uint64_t seed, uint32_t t, uint64_t r, uint32_t dim, uint32_t d, float lo, float hi) {
   return init_value(seed, t, r, dim, d, lo, hi);
 }

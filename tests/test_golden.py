@@ -1,6 +1,8 @@
 """The stored small case (tests/golden/small_case.txt, written by tests/golden/make_golden.py from the oracle
-alone): the oracle must still reproduce it exactly, and the HIP path must match it -- integers bit for bit,
-floats within the tolerance of the table's storage type."""
+alone).  It is a change detector, not a pin: the oracle reproducing its own stored output proves nothing about the
+oracle (the independent expectation is tests/test_golden_adagrad.py and the pins of tests/test_oracle_pins.py); it
+only makes a change of the oracle's arithmetic show up as a diff that has to be justified.  The HIP path is
+compared with the same numbers -- integers bit for bit, floats within the tolerance of the table's storage type."""
 import importlib.util
 import os
 
@@ -28,7 +30,7 @@ def _stored():
     return out
 
 
-def test_oracle_reproduces_the_stored_case_exactly():
+def test_oracle_output_on_the_stored_case_has_not_changed():
     want = [l for l in open(G.PATH).read().splitlines()]
     assert G.lines() == want
 

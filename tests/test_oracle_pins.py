@@ -3,6 +3,7 @@ library routines (torch embedding_bag / autograd / SGD / Adagrad / bf16 cast, nu
 brute force on tiny inputs (dense count-matrix products, python dicts), an explicit inverse of
 the hash mixer, and invariants.  CPU only."""
 import math
+from fractions import Fraction
 
 import numpy as np
 import pytest
@@ -120,6 +121,88 @@ def test_bf16_round_is_identity_on_all_bf16_patterns():
     got = O.round_bf16(x)
     fin = ~np.isnan(x)
     np.testing.assert_array_equal(got[fin].view(np.uint32), hi[fin])
+
+
+# Exact binary rounding with integers and fractions only: the nearest value m * 2^q with |m| < 2^p (p significant
+# bits), exponent of the spacing no lower than q_min (where subnormals begin), ties to the even m.
+def round_to_format(x: Fraction, p: int, q_min: int) -> Fraction:
+    if x == 0:
+        return Fraction(0)
+    sign = -1 if x < 0 else 1
+    a = abs(x)
+    e = a.numerator.bit_length() - a.denominator.bit_length()      # 2^(e-1) <= a < 2^(e+1)
+    if Fraction(2) ** e > a:
+        e -= 1                                                      # now 2^e <= a < 2^(e+1)
+    q = max(e - (p - 1), q_min)
+    scaled = a / Fraction(2) ** q
+    m = scaled.numerator // scaled.denominator
+    rest = scaled - m
+    if rest > Fraction(1, 2) or (rest == Fraction(1, 2) and m % 2 == 1):
+        m += 1
+    return sign * m * Fraction(2) ** q
+
+
+def to_f32_exact(x: Fraction) -> Fraction:
+    return round_to_format(x, 24, -149)
+
+
+def to_bf16_exact(x: Fraction) -> Fraction:
+    return round_to_format(x, 8, -133)
+
+
+def test_exact_rounding_helper_agrees_with_numpy_on_fp32():
+    # the helper itself, against the machine's own fp64 -> fp32 conversion
+    rng = np.random.default_rng(12)
+    xs = np.concatenate([rng.standard_normal(2000) * 10.0 ** rng.integers(-40, 38, 2000),
+                         [1.0 + 2.0 ** -24, 1.0 + 3 * 2.0 ** -24, 2.0 ** -149 * 0.5, 2.0 ** -149 * 1.5, 2.0 ** -127]])
+    for x in xs:
+        assert float(to_f32_exact(Fraction(float(x)))) == float(np.float32(x)), x
+
+
+def test_store_rounds_fp64_to_bf16_once():
+    rng = np.random.default_rng(13)
+    xs = list(rng.standard_normal(3000) * 10.0 ** rng.integers(-42, 38, 3000))
+    # exact bf16 ties, and fp64 values a hair off a tie: fp64 -> fp32 lands ON the tie, so a second rounding
+    # (ties to even) goes the other way than the single rounding
+    for m in (128, 129, 200, 255):
+        for e in (-130, -20, 0, 5, 100):
+            tie = (m + 0.5) * 2.0 ** (e - 7)
+            xs += [tie, -tie, tie * (1 + 2.0 ** -40), tie * (1 - 2.0 ** -40), -tie * (1 + 2.0 ** -40)]
+    xs += [0.0, -0.0, 2.0 ** -134, 2.0 ** -134 * 1.0001, 3 * 2.0 ** -134, 2.0 ** -126, 3.3895e38, 3.4e38, -3.4e38, 1e-300]
+    twice_differs = 0
+    for x in xs:
+        got = O.round_bf16_once(float(x))
+        want = to_bf16_exact(Fraction(float(x)))
+        if abs(want) > Fraction(255) * Fraction(2) ** 120:
+            assert math.isinf(got) and (got > 0) == (x > 0), x
+            continue
+        assert Fraction(got) == want, (x, got, float(want))
+        with np.errstate(over="ignore"):
+            twice = float(O.round_bf16(np.array([np.float32(x)]))[0])
+        twice_differs += twice != got
+    assert twice_differs >= 10          # the cases above do tell one rounding from two
+    assert math.isnan(O.round_bf16_once(float("nan"))) and O.round_bf16_once(float("inf")) == float("inf")
+
+
+def test_init_value_is_exactly_the_two_rounding_definition():
+    """value = fl32(fl32(k * scale) + mid), k = (top 24 bits of the element's hash) - 2^23, scale = fl32(hi - lo) * 2^-24,
+    mid = fl32(hi + lo) / 2 -- every rounding done here in exact rational arithmetic.  The hash comes from the
+    oracle's mix64, which the bijection pin above covers."""
+    fused_differs = 0
+    for seed, lo, hi, dim in [(3, -0.5, 0.25, 8), (2021, -0.01, 0.03, 16), (9, 0.125, 1.0, 32), (11, -0.01, 0.01, 64)]:
+        lo32, hi32 = Fraction(float(np.float32(lo))), Fraction(float(np.float32(hi)))
+        scale = to_f32_exact(hi32 - lo32) * Fraction(1, 1 << 24)
+        mid = to_f32_exact(hi32 + lo32) / 2
+        for t in (0, 3):
+            table_key = O.mix64(seed + (t + 1) * 0x9E3779B97F4A7C15)
+            for r in (0, 1, 77, 123456789):
+                for d in range(dim):
+                    k = (O.mix64(table_key + r * dim + d) >> 40) - (1 << 23)
+                    want = to_f32_exact(to_f32_exact(k * scale) + mid)
+                    got = O.init_value(seed, t, r, dim, d, lo, hi)
+                    assert Fraction(got) == want, (seed, t, r, d)
+                    fused_differs += to_f32_exact(k * scale + mid) != want
+    assert fused_differs > 50           # a fused multiply-add would have been noticed
 
 
 # ----------------------------------------------------------------------------- init
@@ -460,10 +543,24 @@ def test_bf16_table_update_rounds_once_to_nearest_even():
     ids = np.array([1, 1, 6], np.uint64)
     orc.backward_update(ids, np.array([0, 1, 2, 3], np.int32), dp)
     w, _ = table_values(orc, 0)
-    G1 = dp[0].astype(np.float64) + dp[1]
-    want1 = (w0[1].astype(np.float64) - float(np.float32(0.01)) * G1).astype(np.float32)
-    np.testing.assert_array_equal(w[1], torch.from_numpy(want1).to(torch.bfloat16).float().numpy())
+    lr = Fraction(float(np.float32(0.01)))
+    for d in range(D):     # exact arithmetic, one rounding to the bf16 grid
+        want = to_bf16_exact(Fraction(float(w0[1, d])) - lr * (Fraction(float(dp[0, d])) + Fraction(float(dp[1, d]))))
+        assert Fraction(float(w[1, d])) == want
     np.testing.assert_array_equal(w[[0, 2, 3, 4, 5, 7]], w0[[0, 2, 3, 4, 5, 7]])
+
+
+def test_bf16_table_update_does_not_round_through_fp32():
+    # w = 1, lr * G chosen so that w - lr G sits a hair above the tie between the bf16 neighbours 1 and 1 + 2^-7:
+    # fp64 -> fp32 lands exactly on the tie and a second rounding would then go to the even neighbour 1.0
+    orc = make_oracle([(4, 8, W.BF16)], [0], hash_kind=W.HASH_IDENTITY_MOD, opt=W.OPT_SGD, lr=1.0)
+    orc.write_rows(0, np.arange(4, dtype=np.uint64), np.ones((4, 8), np.float32))
+    g = np.float32(-(2.0 ** -8 + 2.0 ** -30))                  # exact in fp32; 1 - g = 1 + 2^-8 + 2^-30
+    dp = np.full((1, 8), g, np.float32)
+    orc.backward_update(np.array([2], np.uint64), np.array([0, 1], np.int32), dp)
+    w, _ = table_values(orc, 0)
+    assert (w[2] == np.float32(1.0 + 2.0 ** -7)).all()
+    assert float(np.float32(1.0 - float(g))) == 1.0 + 2.0 ** -8   # what fp32 would have kept: the exact tie
 
 
 def test_sparse_and_dense_oracle_agree_over_steps():
