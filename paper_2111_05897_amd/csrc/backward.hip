@@ -11,22 +11,16 @@
 // Segments that span tiles are listed by the unique kernels and finished by the fix-up kernels, which add
 // last[t0], first[t0+1], ..., first[t1] in a fixed order and then apply the optimizer.  No float
 // atomics: the summation order is a function of the batch alone, so results are reproducible.
+//
+// Arithmetic: the gradient sums, the partial sums and the optimizer are fp64, and every stored quantity (row
+// element, accumulator) is rounded once from the fp64 result -- the definition of the update evaluated to
+// within fp64 rounding, whatever the length of a segment or the cancellation inside it.  These kernels move
+// bytes; fp64 adds run at the rate of fp32 adds here and the conversions are hidden behind the loads.
 #include "device_utils.h"
 #include "launch.h"
 
 namespace pemb {
 namespace {
-
-__device__ __forceinline__ float4 add4(float4 a, float4 b) {
-  return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w);
-}
-
-__device__ __forceinline__ void kahan_add4(float4& s, float4& c, float4 x) {
-  kahan_add(s.x, c.x, x.x);
-  kahan_add(s.y, c.y, x.y);
-  kahan_add(s.z, c.z, x.z);
-  kahan_add(s.w, c.w, x.w);
-}
 
 // Row update by a group of LG lanes; lane owns elements [4*lane, 4*lane+4) and G holds its part of
 // the row's gradient; v = the lane's part of the row, a_old = the row's accumulator (both may have
@@ -43,9 +37,9 @@ struct RowIo {
     if constexpr (kStream) return load_frag4_stream(p);
     else return load_frag4(p);
   }
-  static __device__ __forceinline__ void store(T* p, float4 v) {
-    if constexpr (kStream) store_frag4_stream(p, v);
-    else store_frag4(p, v);
+  static __device__ __forceinline__ void store(T* p, const d4& v) {  // fp64 results, rounded once to T
+    if constexpr (kStream) store_round4_stream(p, v);
+    else store_round4(p, v);
   }
   static __device__ __forceinline__ float load_acc(const float* p) {
     if constexpr (kStream) return __builtin_nontemporal_load(p);
@@ -58,32 +52,31 @@ struct RowIo {
 };
 
 template <typename T, int D, int OPT>
-__device__ __forceinline__ void finish_update(T* __restrict__ w, float* __restrict__ accs, uint32_t row, float4 G,
+__device__ __forceinline__ void finish_update(T* __restrict__ w, float* __restrict__ accs, uint32_t row, const d4& G,
                                               float4 v, float a_old, int lane, float lr, float eps) {
   constexpr int LG = D / 4;
   T* p = w + (size_t)row * D + lane * 4;
+  double step;
   if constexpr (OPT == 0) {
-    v.x = fmaf(-lr, G.x, v.x);
-    v.y = fmaf(-lr, G.y, v.y);
-    v.z = fmaf(-lr, G.z, v.z);
-    v.w = fmaf(-lr, G.w, v.w);
+    step = (double)lr;
   } else {
-    float sq = G.x * G.x + G.y * G.y + G.z * G.z + G.w * G.w;
+    double sq = G.x * G.x + G.y * G.y + G.z * G.z + G.w * G.w;
 #pragma unroll
     for (int m = LG / 2; m >= 1; m >>= 1) sq += __shfl_xor(sq, m);
-    const float a = a_old + sq * (1.0f / D);
-    const float step = lr / (sqrtf(a) + eps);
-    v.x = fmaf(-step, G.x, v.x);
-    v.y = fmaf(-step, G.y, v.y);
-    v.z = fmaf(-step, G.z, v.z);
-    v.w = fmaf(-step, G.w, v.w);
-    if (lane == 0) RowIo<T, D>::store_acc(accs + row, a);
+    const double a = (double)a_old + sq * (1.0 / D);
+    step = (double)lr / (sqrt(a) + (double)eps);
+    if (lane == 0) RowIo<T, D>::store_acc(accs + row, (float)a);
   }
-  RowIo<T, D>::store(p, v);
+  d4 o;
+  o.x = fma(-step, G.x, (double)v.x);
+  o.y = fma(-step, G.y, (double)v.y);
+  o.z = fma(-step, G.z, (double)v.z);
+  o.w = fma(-step, G.w, (double)v.w);
+  RowIo<T, D>::store(p, o);
 }
 
 template <typename T, int D, int OPT>
-__device__ __forceinline__ void apply_update(T* __restrict__ w, float* __restrict__ accs, uint32_t row, float4 G,
+__device__ __forceinline__ void apply_update(T* __restrict__ w, float* __restrict__ accs, uint32_t row, const d4& G,
                                              int lane, float lr, float eps) {
   const float4 v = RowIo<T, D>::load(w + (size_t)row * D + lane * 4);
   const float a_old = OPT == 0 ? 0.f : RowIo<T, D>::load_acc(accs + row);
@@ -99,7 +92,7 @@ struct TileArgs {
   uint32_t s_mul, s_shift;  // bag / S as a multiply-high and shifts (div_by_S below)
   const uint32_t* slot_col;
   int uniform;
-  float* partials;
+  double* partials;
   uint32_t pstride;
   const uint32_t* range;
   const uint32_t* tile_perm;
@@ -170,8 +163,8 @@ __global__ __launch_bounds__(kBlock) void k_tile_reduce_update(TileArgs a) {
   // the run being summed: its key, sum, and (fetched when the run started) its table row + accumulator
   uint32_t cur = sk[q0 - p0];
   uint32_t prev = cont_in ? cur : ~cur;   // key before entry q0: equal = the first run came in from the left
-  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  float4 cur_row = acc;
+  d4 acc = d4_zero();
+  float4 cur_row = make_float4(0.f, 0.f, 0.f, 0.f);
   float cur_a = 0.f;
   bool first = true, have_run = cont_in;
 
@@ -200,7 +193,7 @@ __global__ __launch_bounds__(kBlock) void k_tile_reduce_update(TileArgs a) {
         if (start[j]) {
           if (have_run) {  // the run of `cur` ended inside the tile
             if (first && cont_in)
-              store_frag4(a.partials + (size_t)(2 * tile) * a.pstride + lane * 4, acc);
+              store_d4(a.partials + (size_t)(2 * tile) * a.pstride + lane * 4, acc);
             else
               finish_update<T, D, OPT>(w, a.accs, cur - a.key_base, acc, cur_row, cur_a, lane, a.lr, a.eps);
             first = false;
@@ -209,16 +202,16 @@ __global__ __launch_bounds__(kBlock) void k_tile_reduce_update(TileArgs a) {
           cur = k[j];
           cur_row = wr[j];
           cur_a = av[j];
-          acc = make_float4(0.f, 0.f, 0.f, 0.f);
+          acc = d4_zero();
         }
-        acc = add4(acc, g[j]);
+        d4_add(acc, g[j]);
       }
     }
   }
   if (first && cont_in)
-    store_frag4(a.partials + (size_t)(2 * tile) * a.pstride + lane * 4, acc);
+    store_d4(a.partials + (size_t)(2 * tile) * a.pstride + lane * 4, acc);
   else if (cont_out)
-    store_frag4(a.partials + (size_t)(2 * tile + 1) * a.pstride + lane * 4, acc);
+    store_d4(a.partials + (size_t)(2 * tile + 1) * a.pstride + lane * 4, acc);
   else
     finish_update<T, D, OPT>(w, a.accs, cur - a.key_base, acc, cur_row, cur_a, lane, a.lr, a.eps);
 }
@@ -229,7 +222,7 @@ struct FixupArgs {
   const uint32_t* counters;   // [1] = entries of multi_list, [2] = entries of long_list
   const uint32_t* multi_list;
   const uint32_t* long_list;
-  const float* partials;
+  const double* partials;
   uint32_t pstride;
   void* w;
   float* accs;
@@ -260,18 +253,18 @@ __global__ __launch_bounds__(kBlock) void k_fixup_short(FixupArgs a) {
     const uint32_t row = key - a.key_base;
     const float4 v = RowIo<T, D>::load(w + (size_t)row * D + lane * 4);  // in flight together with the partials
     const float a_old = OPT == 0 ? 0.f : RowIo<T, D>::load_acc(a.accs + row);
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    d4 acc = d4_zero();
     for (uint32_t k0 = 0; k0 < np; k0 += 4) {
-      float4 pv[4];
+      d4 pv[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const uint32_t k = k0 + j;
         const size_t slot = (k == 0) ? (size_t)2 * t0 + 1 : (size_t)2 * (t0 + k);
-        pv[j] = k < np ? load_frag4(a.partials + slot * a.pstride + lane * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+        pv[j] = k < np ? load_d4(a.partials + slot * a.pstride + lane * 4) : d4_zero();
       }
 #pragma unroll
       for (int j = 0; j < 4; ++j)
-        if (k0 + j < np) acc = add4(acc, pv[j]);
+        if (k0 + j < np) d4_add(acc, pv[j]);
     }
     finish_update<T, D, OPT>(w, a.accs, row, acc, v, a_old, lane, a.lr, a.eps);
   }
@@ -307,13 +300,12 @@ __global__ __launch_bounds__(kBlock) void k_classify_multi(const uint32_t* __res
 }
 
 // Longer segments (hot keys): one workgroup per entry of long_list (grid-stride).  Group g adds partials
-// g, g+NG, ... of the segment in order (compensated); the NG group sums are then added in group order
-// and the row is updated.
+// g, g+NG, ... of the segment in order; the NG group sums are then added in group order and the row is updated.
 template <typename T, int D, int OPT>
 __global__ __launch_bounds__(kBlock) void k_fixup_long(FixupArgs a) {
   constexpr int LG = D / 4;
   constexpr int NG = kBlock / LG;
-  __shared__ float s_part[NG][D];
+  __shared__ double s_part[NG][D];
   const int g = threadIdx.x / LG, lane = threadIdx.x % LG;
   const uint32_t count = a.counters[2];
   T* w = reinterpret_cast<T*>(a.w);
@@ -324,25 +316,25 @@ __global__ __launch_bounds__(kBlock) void k_fixup_long(FixupArgs a) {
     const uint32_t s = a.seg_off[u], end = a.seg_off[u + 1];
     const uint32_t t0 = s / kTile, t1 = (end - 1) / kTile;
     const uint32_t np = t1 - t0 + 1;
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f), comp = acc;
+    d4 acc = d4_zero();
     for (uint32_t k0 = g; k0 < np; k0 += 4 * NG) {  // four loads in flight per lane
-      float4 v[4];
+      d4 v[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const uint32_t k = k0 + j * NG;
         const size_t slot = (k == 0) ? (size_t)2 * t0 + 1 : (size_t)2 * (t0 + k);
-        v[j] = k < np ? load_frag4(a.partials + slot * a.pstride + lane * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+        v[j] = k < np ? load_d4(a.partials + slot * a.pstride + lane * 4) : d4_zero();
       }
 #pragma unroll
       for (int j = 0; j < 4; ++j)
-        if (k0 + j * NG < np) kahan_add4(acc, comp, v[j]);
+        if (k0 + j * NG < np) d4_add(acc, v[j]);
     }
-    store_frag4(&s_part[g][lane * 4], acc);
+    store_d4(&s_part[g][lane * 4], acc);
     __syncthreads();
     if (g == 0) {
-      float4 tot = make_float4(0.f, 0.f, 0.f, 0.f), tc = tot;
+      d4 tot = d4_zero();
       const int ng = np < (uint32_t)NG ? (int)np : NG;
-      for (int gg = 0; gg < ng; ++gg) kahan_add4(tot, tc, load_frag4(&s_part[gg][lane * 4]));
+      for (int gg = 0; gg < ng; ++gg) d4_add(tot, load_d4(&s_part[gg][lane * 4]));
       apply_update<T, D, OPT>(w, a.accs, key - a.key_base, tot, lane, a.lr, a.eps);
     }
     __syncthreads();

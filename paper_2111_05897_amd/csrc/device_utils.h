@@ -55,6 +55,46 @@ __device__ __forceinline__ void kahan_add(float& sum, float& comp, float x) {
   sum = t;
 }
 
+// ---- fp64 results -> storage.  Sums and the optimizer are evaluated in fp64 and every stored quantity is
+// rounded once: to fp32 by the conversion instruction, to bf16 through "round to odd" -- the fp64 value is
+// truncated to fp32 and the last fp32 bit is set when anything was cut off; that sticky bit sits 16 places below the
+// bf16 rounding point, so the nearest-even rounding of the fp32 pattern to bf16 sees exactly on which side of a tie
+// the fp64 value lay, and the result is the one a direct fp64 -> bf16 rounding gives.
+__device__ __forceinline__ uint32_t f64_to_bf16(double v) {
+  const float f = __double2float_rz(v);
+  uint32_t u = __float_as_uint(f);
+  if ((double)f != v) u |= 1u;  // inexact (also true of a NaN, which stays a NaN)
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x0040u;
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+// 4 consecutive row elements in fp64: what one lane of the backward kernels accumulates.
+struct d4 {
+  double x, y, z, w;
+};
+__device__ __forceinline__ d4 d4_zero() { return d4{0.0, 0.0, 0.0, 0.0}; }
+__device__ __forceinline__ void d4_add(d4& a, float4 g) {
+  a.x += (double)g.x;
+  a.y += (double)g.y;
+  a.z += (double)g.z;
+  a.w += (double)g.w;
+}
+__device__ __forceinline__ void d4_add(d4& a, const d4& b) {
+  a.x += b.x;
+  a.y += b.y;
+  a.z += b.z;
+  a.w += b.w;
+}
+__device__ __forceinline__ d4 load_d4(const double* p) {
+  const double2 a = *reinterpret_cast<const double2*>(p), b = *reinterpret_cast<const double2*>(p + 2);
+  return d4{a.x, a.y, b.x, b.y};
+}
+__device__ __forceinline__ void store_d4(double* p, const d4& v) {
+  *reinterpret_cast<double2*>(p) = make_double2(v.x, v.y);
+  *reinterpret_cast<double2*>(p + 2) = make_double2(v.z, v.w);
+}
+
 // ---- 4-element row fragments (what one lane owns of a row in the backward kernels) ----
 __device__ __forceinline__ float4 load_frag4(const float* p) { return *reinterpret_cast<const float4*>(p); }
 __device__ __forceinline__ float4 load_frag4(const bf16_t* p) {
@@ -67,6 +107,16 @@ __device__ __forceinline__ void store_frag4(bf16_t* p, float4 v) {
   uint2 o;
   o.x = f32_to_bf16(v.x) | (f32_to_bf16(v.y) << 16);
   o.y = f32_to_bf16(v.z) | (f32_to_bf16(v.w) << 16);
+  *reinterpret_cast<uint2*>(p) = o;
+}
+// fp64 results, each rounded once to the storage type
+__device__ __forceinline__ void store_round4(float* p, const d4& v) {
+  *reinterpret_cast<float4*>(p) = make_float4((float)v.x, (float)v.y, (float)v.z, (float)v.w);
+}
+__device__ __forceinline__ void store_round4(bf16_t* p, const d4& v) {
+  uint2 o;
+  o.x = f64_to_bf16(v.x) | (f64_to_bf16(v.y) << 16);
+  o.y = f64_to_bf16(v.z) | (f64_to_bf16(v.w) << 16);
   *reinterpret_cast<uint2*>(p) = o;
 }
 
@@ -83,12 +133,12 @@ __device__ __forceinline__ float4 load_frag4_stream(const bf16_t* p) {
   return make_float4(__uint_as_float(v[0] << 16), __uint_as_float(v[0] & 0xFFFF0000u), __uint_as_float(v[1] << 16),
                      __uint_as_float(v[1] & 0xFFFF0000u));
 }
-__device__ __forceinline__ void store_frag4_stream(float* p, float4 v) {
-  const f32x4_t o = {v.x, v.y, v.z, v.w};
+__device__ __forceinline__ void store_round4_stream(float* p, const d4& v) {
+  const f32x4_t o = {(float)v.x, (float)v.y, (float)v.z, (float)v.w};
   __builtin_nontemporal_store(o, reinterpret_cast<f32x4_t*>(p));
 }
-__device__ __forceinline__ void store_frag4_stream(bf16_t* p, float4 v) {
-  const u32x2_t o = {f32_to_bf16(v.x) | (f32_to_bf16(v.y) << 16), f32_to_bf16(v.z) | (f32_to_bf16(v.w) << 16)};
+__device__ __forceinline__ void store_round4_stream(bf16_t* p, const d4& v) {
+  const u32x2_t o = {f64_to_bf16(v.x) | (f64_to_bf16(v.y) << 16), f64_to_bf16(v.z) | (f64_to_bf16(v.w) << 16)};
   __builtin_nontemporal_store(o, reinterpret_cast<u32x2_t*>(p));
 }
 

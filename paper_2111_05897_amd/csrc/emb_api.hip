@@ -55,12 +55,13 @@ struct emb_ctx {
   std::vector<uint32_t> key_base_host;
   SlotArrays slots{};
   uint32_t* key_base_dev = nullptr;  // [T]
+  uint32_t* zero_row = nullptr;      // kZeroRowBytes of zeros
   // workspace
   uint32_t *keys[2] = {nullptr, nullptr}, *bags[2] = {nullptr, nullptr};
   uint32_t *hist = nullptr, *total = nullptr, *blk_heads = nullptr, *blk_multi = nullptr;
   uint32_t *unique_keys = nullptr, *seg_off = nullptr, *multi_list = nullptr, *long_list = nullptr;
   uint32_t *counters = nullptr, *ranges = nullptr;
-  float* partials = nullptr;
+  double* partials = nullptr;
   uint32_t *tile_key[2] = {nullptr, nullptr}, *tile_val[2] = {nullptr, nullptr};
   // tables kept in host memory behind an LRU cache (emb_create_cached); lru[t].C == 0: table t is resident
   std::vector<LruView> lru;
@@ -398,6 +399,8 @@ static int emb_create_impl(const emb_config* cfg, const uint64_t* cache_rows, em
     ctx->slots.key_base = p_kb;
     ctx->slots.col = p_col;
     CK(dev_upload(ctx, &ctx->key_base_dev, ctx->key_base_host), "upload(table key base)");
+    CK(dev_alloc(ctx, &ctx->zero_row, kZeroRowBytes / sizeof(uint32_t)), "hipMalloc(zero row)");
+    CK(hipMemset(ctx->zero_row, 0, kZeroRowBytes), "hipMemset(zero row)");
   }
   // workspace
   const uint64_t cap = ctx->max_ids ? ctx->max_ids : 1;
@@ -535,7 +538,7 @@ static int emb_lookup_pool_impl(emb_ctx* ctx, const emb_batch* batch, float* poo
   for (const TableView& tv : ctx->tables) {
     StageTimer tm(ctx, ST_GATHER_POOL, stream);
     CKH(launch_gather_pool(tv, ctx->slots, batch->ids, batch->offsets, batch->batch_size, ctx->S, ctx->width,
-                           ctx->mix, pooled, stream),
+                           ctx->mix, ctx->zero_row, pooled, stream),
         "gather_pool");
   }
   return EMB_OK;

@@ -15,6 +15,7 @@ struct GatherArgs {
   const uint64_t* ids;
   const int32_t* offsets;
   const void* w;
+  const void* zeros;           // 512 bytes of zeros (the widest row): what a load past the end of a bag reads
   const int32_t* where;        // null, or row -> cache slot for a table kept behind the LRU cache
   uint64_t rows, mask;
   const uint32_t* slot_list;   // slots reading this table
@@ -27,22 +28,23 @@ struct GatherArgs {
   float* pooled;
 };
 
-// 16 bytes of a row as loaded, widened to fp32 only when it is added.
+// 16 bytes of a row as loaded, widened only when it is added.
 template <typename T>
 struct Raw16 {
   uint4 v;
   static constexpr int VEC = 16 / (int)sizeof(T);
   __device__ __forceinline__ void load(const T* p) { v = *reinterpret_cast<const uint4*>(p); }
   __device__ __forceinline__ void zero() { v = make_uint4(0u, 0u, 0u, 0u); }
-  __device__ __forceinline__ void add_to(float (&s)[VEC]) const {
+  template <typename A>  // A = double for the per-bag sums, float where a single row is widened
+  __device__ __forceinline__ void add_to(A (&s)[VEC]) const {
     if constexpr (sizeof(T) == 4) {
-      s[0] += __uint_as_float(v.x); s[1] += __uint_as_float(v.y);
-      s[2] += __uint_as_float(v.z); s[3] += __uint_as_float(v.w);
+      s[0] += (A)__uint_as_float(v.x); s[1] += (A)__uint_as_float(v.y);
+      s[2] += (A)__uint_as_float(v.z); s[3] += (A)__uint_as_float(v.w);
     } else {
-      s[0] += __uint_as_float(v.x << 16); s[1] += __uint_as_float(v.x & 0xFFFF0000u);
-      s[2] += __uint_as_float(v.y << 16); s[3] += __uint_as_float(v.y & 0xFFFF0000u);
-      s[4] += __uint_as_float(v.z << 16); s[5] += __uint_as_float(v.z & 0xFFFF0000u);
-      s[6] += __uint_as_float(v.w << 16); s[7] += __uint_as_float(v.w & 0xFFFF0000u);
+      s[0] += (A)__uint_as_float(v.x << 16); s[1] += (A)__uint_as_float(v.x & 0xFFFF0000u);
+      s[2] += (A)__uint_as_float(v.y << 16); s[3] += (A)__uint_as_float(v.y & 0xFFFF0000u);
+      s[4] += (A)__uint_as_float(v.z << 16); s[5] += (A)__uint_as_float(v.z & 0xFFFF0000u);
+      s[6] += (A)__uint_as_float(v.w << 16); s[7] += (A)__uint_as_float(v.w & 0xFFFF0000u);
     }
   }
 };
@@ -55,7 +57,7 @@ __device__ __forceinline__ uint32_t group_bcast(uint32_t v, int src) {
 }
 
 template <typename T, int D>
-__global__ __launch_bounds__(kBlock) void k_gather_pool(GatherArgs a) {
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(sizeof(T) == 4 && D <= 64 ? 8 : 1, 8))) void k_gather_pool(GatherArgs a) {
   constexpr int VEC = 16 / (int)sizeof(T);
   constexpr int LANES = D / VEC;            // lanes that cover one row with 16 bytes each
   constexpr int GPB = kBlock / LANES;       // bags per workgroup
@@ -73,13 +75,14 @@ __global__ __launch_bounds__(kBlock) void k_gather_pool(GatherArgs a) {
   const int beg = a.offsets[bag], end = a.offsets[bag + 1];
   const uint64_t salt = a.slot_salt[slot];
   const T* __restrict__ base = reinterpret_cast<const T*>(a.w) + lane * VEC;
+  const T* __restrict__ zero_row = reinterpret_cast<const T*>(a.zeros) + lane * VEC;
   const uint64_t* __restrict__ ids = a.ids;
 
-  // Rows are summed in batch order: plain fp32 inside a sub-chunk of RIF rows, and the sub-chunk
-  // sums are added with compensation (Kahan), so the error does not grow with the bag length.
-  float acc[VEC], comp[VEC];
+  // Rows are summed in batch order in fp64 and the sum is rounded once to fp32: the definition of the pooled
+  // vector to within fp64 rounding, whatever the bag length or the cancellation between its rows.
+  double acc[VEC];
 #pragma unroll
-  for (int e = 0; e < VEC; ++e) acc[e] = comp[e] = 0.f;
+  for (int e = 0; e < VEC; ++e) acc[e] = 0.0;
 
   for (int cbase = beg; cbase < end; cbase += CH) {
     const int cnt = end - cbase < CH ? end - cbase : CH;
@@ -101,21 +104,18 @@ __global__ __launch_bounds__(kBlock) void k_gather_pool(GatherArgs a) {
 #pragma unroll
     for (int j0 = 0; j0 < CH; j0 += RIF) {
       if (j0 < cnt) {  // same for all lanes of the group
+        // Every one of the RIF loads is issued, without a branch: past the bag's end it reads a row of zeros (one
+        // cached line).  Straight-line code keeps all RIF requests in flight and the widening to fp64 behind them;
+        // with a branch per row the compiler widens inside the branch and waits for every load in turn.
         Raw16<T> r[RIF];
 #pragma unroll
         for (int jj = 0; jj < RIF; ++jj) {
           const int j = j0 + jj;  // compile-time: id j of the round sits in lane j % LANES, register j / LANES
           const uint32_t row = group_bcast<LANES>(myrow[j / LANES], j % LANES);
-          if (j < cnt) r[jj].load(base + (size_t)row * D);
-          else r[jj].zero();
+          r[jj].load(j < cnt ? base + (size_t)row * D : zero_row);
         }
-        float s[VEC];
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) s[e] = 0.f;
-#pragma unroll
-        for (int jj = 0; jj < RIF; ++jj) r[jj].add_to(s);
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) kahan_add(acc[e], comp[e], s[e]);
+        for (int jj = 0; jj < RIF; ++jj) r[jj].add_to(acc);
       }
     }
   }
@@ -125,10 +125,11 @@ __global__ __launch_bounds__(kBlock) void k_gather_pool(GatherArgs a) {
   for (int e = 0; e < VEC; e += 4)
     if (a.stream_out) {  // this launch writes whole pooled rows: streamed, nothing re-reads them here
       typedef float f32x4 __attribute__((ext_vector_type(4)));
-      const f32x4 v = {acc[e], acc[e + 1], acc[e + 2], acc[e + 3]};
+      const f32x4 v = {(float)acc[e], (float)acc[e + 1], (float)acc[e + 2], (float)acc[e + 3]};
       __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(out + e));
     } else {  // several tables share the pooled rows: their pieces of a cache line must meet in the cache
-      *reinterpret_cast<float4*>(out + e) = make_float4(acc[e], acc[e + 1], acc[e + 2], acc[e + 3]);
+      *reinterpret_cast<float4*>(out + e) =
+          make_float4((float)acc[e], (float)acc[e + 1], (float)acc[e + 2], (float)acc[e + 3]);
     }
 }
 
@@ -307,12 +308,15 @@ hipError_t launch_indexed_pool(const TableView& t, uint32_t table, const SlotArr
 }
 
 hipError_t launch_gather_pool(const TableView& t, const SlotArrays& sl, const uint64_t* ids, const int32_t* offsets,
-                              uint32_t B, uint32_t S, uint32_t width, int mix, float* pooled, hipStream_t stream) {
+                              uint32_t B, uint32_t S, uint32_t width, int mix, const void* zeros, float* pooled,
+                              hipStream_t stream) {
   if (B == 0 || t.n_slots == 0) return hipSuccess;
+  if (!zeros) return hipErrorInvalidValue;
   GatherArgs a;
   a.ids = ids;
   a.offsets = offsets;
   a.w = t.w;
+  a.zeros = zeros;
   a.where = t.where;
   a.rows = t.rows;
   a.mask = t.mask;

@@ -86,8 +86,11 @@ hipError_t launch_write_rows(const TableView& t, const uint64_t* rows_dev, uint6
                              const float* acc_in, hipStream_t stream);
 
 // ---- forward.hip ----
+// zeros: kZeroRowBytes of device memory holding zeros (read in place of rows past the end of a bag).
+constexpr uint32_t kZeroRowBytes = 512;
 hipError_t launch_gather_pool(const TableView& t, const SlotArrays& sl, const uint64_t* ids, const int32_t* offsets,
-                              uint32_t B, uint32_t S, uint32_t width, int mix, float* pooled, hipStream_t stream);
+                              uint32_t B, uint32_t S, uint32_t width, int mix, const void* zeros, float* pooled,
+                              hipStream_t stream);
 // The forward from the index form: pooled (zeroed first, launch_zero_f32) += row of keys[u] for every bag of
 // seg_bags[seg_off[u] .. seg_off[u+1]), for the keys of table `table`; fp32 hardware atomics.
 hipError_t launch_zero_f32(float* p, uint64_t n, hipStream_t stream);
@@ -128,7 +131,7 @@ struct BackwardArgs {
   uint32_t S, width;
   const uint32_t* slot_col;  // device [S]
   int uniform;               // every slot has this table's dim: gradient of a bag starts at bag*dim
-  float* partials;           // [2 * ntiles, pstride]
+  double* partials;          // [2 * ntiles, pstride] fp64 partial sums of segments that cross tile edges
   uint32_t pstride;
   const uint32_t* range;     // device [2]: occurrences [range[0], range[1]) belong to this table; null = all
   const uint32_t* tile_perm; // device [ntiles]: order in which lane-groups take the tiles; null = ascending

@@ -5,25 +5,25 @@ import numpy as np
 # spec tolerances: fp32 tables 1e-5 relative + 1e-6 absolute; bf16 storage 2e-2 relative
 TOL = {0: dict(rtol=1e-5, atol=1e-6), 1: dict(rtol=2e-2, atol=1e-6)}
 LOW32 = np.uint64(0xFFFFFFFF)
-# A sum of fp32 terms formed in fp32 (in any order, compensated or not) carries an error of a few units in the last
-# place of its LARGEST partial sum, which no bound relative to the result covers when the terms cancel.  The
-# comparisons below therefore allow, on top of the spec bar, SUM_EPS times the sum of the terms' magnitudes:
-# 8 roundings of 2^-24 (the kernels add at most 8 terms before a compensated step).  At the benchmark's value
-# ranges (rows of ~1e-2) this is ~1e-8 and plays no part; it matters only in the stress tests, whose rows and
-# steps are hundreds of times larger.
-SUM_EPS = 8.0 * 2.0 ** -24
+# How close the two sides really are.  Both evaluate the same definitions in fp64 (sums of fp32 terms, the optimizer)
+# and round each stored quantity once, so they differ only where the order of the fp64 additions moved a result across
+# an fp32 (or bf16) rounding boundary: a difference of one unit in the last place, at a rate of order 1e-8 per
+# element.  Besides the spec bar above, the comparisons below therefore require that all but MAX_DIFFERING of
+# the elements are identical bit for bit.
+MAX_DIFFERING = 1e-3
 
 
 def tol_for(cfg):
     return TOL[1] if any(t.dtype == 1 for t in cfg.tables) else TOL[0]
 
 
-def assert_close(got, want, rtol, atol, slack=None, err_msg=""):
-    """|got - want| <= atol + rtol |want| (+ slack, elementwise)."""
+def assert_close(got, want, rtol, atol, err_msg=""):
+    """|got - want| <= atol + rtol |want| for every element, and at most MAX_DIFFERING of them differ at all."""
     got, want = np.asarray(got, dtype=np.float64), np.asarray(want, dtype=np.float64)
     bound = atol + rtol * np.abs(want)
-    if slack is not None:
-        bound = bound + slack
+    differing = float((got != want).mean()) if got.size else 0.0
+    assert differing <= max(MAX_DIFFERING, 2.0 / max(got.size, 1)), \
+        f"{err_msg}: {differing:.2e} of {got.size} elements are not bit-identical"
     bad = ~(np.abs(got - want) <= bound)       # NaNs count as bad
     if bad.any():
         i = np.unravel_index(np.argmax(np.where(bad, np.abs(got - want) - bound, -np.inf)), got.shape)
@@ -31,54 +31,8 @@ def assert_close(got, want, rtol, atol, slack=None, err_msg=""):
                              f"got {got[i]!r}, want {want[i]!r}, bound {bound[i] if np.ndim(bound) else bound!r}")
 
 
-def compare_pooled(got, want, cfg, slack=None):
-    assert_close(got, want, **tol_for(cfg), slack=slack, err_msg="pooled")
-
-
-def pooled_magnitudes(orc, cfg, b):
-    """Sum of |row| over the rows each pooled element is made of, [B, pooled width] (numpy, for small batches):
-    read from the oracle's tables as they stand."""
-    S = cfg.num_slots
-    cols, dims = np.array(cfg.slot_cols()), np.array(cfg.slot_dims())
-    slot_table = np.array([s.table for s in cfg.slots])
-    out = np.zeros((b.batch_size, cfg.pooled_width), dtype=np.float64)
-    if b.num_ids == 0:
-        return out
-    rows = orc.hash_rows(b.ids, b.offsets).astype(np.uint64)
-    lens = np.diff(b.offsets.astype(np.int64))
-    bag_of = np.repeat(np.arange(len(lens)), lens)
-    for t in range(len(cfg.tables)):
-        sel = np.flatnonzero(slot_table[bag_of % S] == t)
-        if not len(sel):
-            continue
-        ur, inv = np.unique(rows[sel], return_inverse=True)
-        w_abs = np.abs(orc.read_rows(t, ur)[0].astype(np.float64))[inv]          # [n_t, D_t]
-        bb, ss = bag_of[sel] // S, bag_of[sel] % S
-        D = cfg.tables[t].dim
-        for d in range(D):
-            np.add.at(out, (bb, cols[ss] + d), w_abs[:, d])
-    return out
-
-
-def gradient_magnitudes(cfg, index_form, dp):
-    """For each unique key of the index form: max over the row's elements of the sum of |upstream gradient| over
-    the key's occurrences (numpy, for small batches)."""
-    keys, seg_off, bags = index_form
-    S = cfg.num_slots
-    cols = np.array(cfg.slot_cols())
-    out = np.zeros(len(keys), dtype=np.float64)
-    tables = (keys >> np.uint64(32)).astype(np.int64)
-    seg_off = seg_off.astype(np.int64)
-    absdp = np.abs(dp.astype(np.float64))
-    for u in range(len(keys)):
-        D = cfg.tables[tables[u]].dim
-        bg = bags[seg_off[u]:seg_off[u + 1]].astype(np.int64)
-        bb, ss = bg // S, bg % S
-        acc = np.zeros(D)
-        for b_, s_ in zip(bb, ss):
-            acc += absdp[b_, cols[s_]:cols[s_] + D]
-        out[u] = acc.max() if D else 0.0
-    return out
+def compare_pooled(got, want, cfg):
+    assert_close(got, want, **tol_for(cfg), err_msg="pooled")
 
 
 def compare_dedup(gpu, orc):
@@ -91,11 +45,9 @@ def compare_dedup(gpu, orc):
     np.testing.assert_array_equal(gb, ob)
 
 
-def compare_rows(ctx, orc, cfg, keys, extra_rows=64, seed=0, all_touched=None, grad_mag=None):
+def compare_rows(ctx, orc, cfg, keys, extra_rows=64, seed=0, all_touched=None):
     """Touched rows (and their accumulators) within tolerance; a sample of other rows bit-exact.
-    all_touched: every key the GPU batch touched, when `keys` is only a sample of them.
-    grad_mag: per key (aligned with `keys`), the value gradient_magnitudes gives; widens the bound by what
-    SUM_EPS * grad_mag in the summed gradient can do to the row and to its accumulator (tolerances)."""
+    all_touched: every key the GPU batch touched, when `keys` is only a sample of them."""
     tables = (keys >> np.uint64(32)).astype(np.int64)
     rows = keys & LOW32
     if all_touched is None:
@@ -109,18 +61,8 @@ def compare_rows(ctx, orc, cfg, keys, extra_rows=64, seed=0, all_touched=None, g
         if len(r):
             gw, ga = ctx.emb_read_rows(t, r)
             ow, oa = orc.read_rows(t, r)
-            slack_w = slack_a = None
-            if grad_mag is not None:
-                gm = grad_mag[tables == t]
-                delta = SUM_EPS * gm                                   # error of an element of the summed gradient
-                if cfg.opt == 0:                                        # w' = w - lr G
-                    slack_w = (cfg.lr * delta)[:, None]
-                else:                                                   # a' = a + mean G^2; w' = w - lr G / (sqrt a' + eps)
-                    step = cfg.lr / (np.sqrt(oa.astype(np.float64)) + cfg.eps)
-                    slack_w = (step * (1.0 + np.sqrt(td.dim)) * delta)[:, None]
-                    slack_a = 2.0 * gm * delta + delta * delta
-            assert_close(gw, ow, **tol, slack=slack_w, err_msg=f"table {t} rows")
-            assert_close(ga, oa, rtol=1e-5, atol=1e-6, slack=slack_a, err_msg=f"table {t} accumulators")
+            assert_close(gw, ow, **tol, err_msg=f"table {t} rows")
+            assert_close(ga, oa, rtol=1e-5, atol=1e-6, err_msg=f"table {t} accumulators")
         probe = rng.integers(0, td.rows, size=extra_rows, dtype=np.uint64)
         probe = np.setdiff1d(probe, at_rows[at_tables == t])
         if len(probe):
@@ -130,23 +72,10 @@ def compare_rows(ctx, orc, cfg, keys, extra_rows=64, seed=0, all_touched=None, g
             np.testing.assert_array_equal(ga, oa)
 
 
-def sync_rows(ctx, orc, cfg, keys):
-    """After a step has been compared, copy the oracle's rows into the GPU table.  A row on which the two sides
-    differ within the bar (neighbouring bf16 values; a few fp32 units in the last place) would otherwise show up
-    in the next step's pooled sums, where cancellation can magnify it beyond any bound relative to the result;
-    with the state re-aligned every step is judged on its own arithmetic."""
-    tables = (keys >> np.uint64(32)).astype(np.int64)
-    rows = keys & LOW32
-    for t in range(len(cfg.tables)):
-        r = rows[tables == t]
-        if len(r):
-            ow, oa = orc.read_rows(t, r)
-            ctx.emb_write_rows(t, r, ow, oa)
-
-
 def run_steps(binding, workload_mod, oracle_mod, w, steps=1, dense=None, batches=None, grads=None, check_hash=True,
               cache_rows=None):
-    """Runs `steps` forward+backward steps of workload w on both sides and compares everything."""
+    """Runs `steps` forward+backward steps of workload w on both sides, each side on its own trajectory (the state
+    of one side is never copied into the other), and compares everything after every step."""
     cfg = w.cfg
     if batches is None:
         batches = [workload_mod.make_batch(w, s) for s in range(steps)]
@@ -165,24 +94,58 @@ def run_steps(binding, workload_mod, oracle_mod, w, steps=1, dense=None, batches
         if check_hash and b.num_ids:
             np.testing.assert_array_equal(ctx.emb_hash_rows(db).cpu().numpy().view(np.uint32),
                                           orc.hash_rows(b.ids, b.offsets))
-        small = b.num_ids <= 50000        # the magnitude terms of the bound are computed in numpy
         pooled = ctx.emb_lookup_pool(db)
         torch.cuda.synchronize()
-        compare_pooled(pooled.cpu().numpy(), orc.lookup_pool(b.ids, b.offsets), cfg,
-                       slack=SUM_EPS * pooled_magnitudes(orc, cfg, b) if small else None)
+        compare_pooled(pooled.cpu().numpy(), orc.lookup_pool(b.ids, b.offsets), cfg)
         ctx.emb_backward_update(db, torch.from_numpy(dp).cuda())
         gd = ctx.emb_read_dedup()
         od = orc.backward_update(b.ids, b.offsets, dp)
         compare_dedup(gd, od)
         touched.append(od[0])
-        if small:   # this step's rows with the widened bound, every row touched so far (re-aligned below) flat
-            compare_rows(ctx, orc, cfg, od[0], grad_mag=gradient_magnitudes(cfg, od, dp))
-        else:
-            compare_rows(ctx, orc, cfg, np.unique(np.concatenate(touched)))
-        if small or any(t.dtype == 1 for t in cfg.tables):
-            sync_rows(ctx, orc, cfg, od[0])
+        compare_rows(ctx, orc, cfg, np.unique(np.concatenate(touched)))   # every row touched so far
     ctx.close()
     orc.close()
+
+
+class Trajectory:
+    """The HIP library and the oracle side by side over several steps of one workload, each on its own state (no
+    value of one side ever enters the other).  step(t) runs lookup + backward/update of batch t on both sides and
+    compares the pooled activations and the index form; final_check() compares rows and accumulators."""
+
+    def __init__(self, binding, workload_mod, oracle_mod, w, max_ids):
+        self.B, self.W, self.w, self.cfg = binding, workload_mod, w, w.cfg
+        self.orc = oracle_mod.Oracle.from_config(w.cfg, dense=False)
+        self.ctx = binding.EmbContext.from_config(w.cfg, max_batch=w.batch, max_ids=max_ids)
+        self.touched = []
+        self.steps_done = 0
+
+    def step(self, t):
+        import torch
+        b = self.W.make_batch(self.w, t)
+        dp = self.W.make_d_pooled(self.w, t)
+        db = self.B.DeviceBatch(b.batch_size, b.ids, b.offsets)
+        pooled = self.ctx.emb_lookup_pool(db)
+        torch.cuda.synchronize()
+        compare_pooled(pooled.cpu().numpy(), self.orc.lookup_pool(b.ids, b.offsets), self.cfg)
+        del pooled
+        self.ctx.emb_backward_update(db, torch.from_numpy(dp).cuda())
+        od = self.orc.backward_update(b.ids, b.offsets, dp)
+        compare_dedup(self.ctx.emb_read_dedup(), od)
+        self.touched.append(od[0])
+        self.steps_done += 1
+
+    def final_check(self, max_rows=1 << 20, seed=0):
+        """Rows and accumulators: every row of the last step, and a sample of the rows touched in earlier steps."""
+        allk = np.unique(np.concatenate(self.touched))
+        earlier = np.setdiff1d(allk, self.touched[-1])
+        if len(earlier) > max_rows:
+            earlier = np.random.default_rng(seed).choice(earlier, size=max_rows, replace=False)
+        compare_rows(self.ctx, self.orc, self.cfg, np.union1d(self.touched[-1], earlier), extra_rows=256, seed=seed,
+                     all_touched=allk)
+
+    def close(self):
+        self.ctx.close()
+        self.orc.close()
 
 
 def sampled_step_check(binding, workload_mod, oracle_mod, w, n_bags=4096, n_rows=2048, seed=0):
