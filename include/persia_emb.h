@@ -119,12 +119,18 @@ int emb_destroy(emb_ctx* ctx); /* synchronous; frees everything the context owns
 int emb_lookup_pool(emb_ctx* ctx, const emb_batch* batch, float* pooled, void* hip_stream);
 
 /* The forward from the index form (section 4.2.3: a batch compressed losslessly as its unique keys, each with
- * the list of places that hold it) -- the same pooled activations as emb_lookup_pool, from what
- * emb_read_dedup describes: keys[u] = (table << 32) | row ascending (device, [num_unique]), seg_off (device,
+ * the list of places that hold it) -- the same pooled activations as emb_lookup_pool, from what emb_read_dedup
+ * describes: keys[u] = (table << 32) | row strictly ascending (device, [num_unique]), seg_off (device,
  * [num_unique + 1], seg_off[0] = 0, seg_off[num_unique] = num_ids), seg_bags (device, [num_ids], bag = sample *
- * num_slots + slot).  Each unique row is read once and added to its bags' pooled rows with fp32 atomics, so
- * a bag's sum forms in no fixed order: equal to emb_lookup_pool within the fp32 tolerance, not bit for bit.
- * pooled: device fp32 [batch_size, W], written whole.  Not available for tables behind a cache. */
+ * num_slots + slot).  The lists are turned back into per-bag lists by a stable sort of (bag, key position) pairs
+ * -- no atomics -- and every bag sums its rows in fp64 in ascending key order: reproducible, and equal to
+ * emb_lookup_pool up to the order of fp64 additions (i.e. bit for bit except where that order tips an fp32
+ * rounding).  Entries that name no bag of the batch or no row of a table contribute nothing.
+ * pooled: device fp32 [batch_size, W], written whole.  Uses the context's sort workspace: num_ids <= max_ids, and
+ * the index form of an earlier emb_backward_update is gone afterwards (emb_read_dedup then returns EMB_ESTATE).
+ * Not available for tables behind a cache.  This is the wire format of the paper put to use; with the table in
+ * local HBM emb_lookup_pool is the faster forward, since the sort that undoes the compression costs more than the
+ * repeated row reads it saves. */
 int emb_lookup_pool_indexed(emb_ctx* ctx, uint32_t batch_size, uint64_t num_unique, uint64_t num_ids, const uint64_t* keys,
                             const uint32_t* seg_off, const uint32_t* seg_bags, float* pooled, void* hip_stream);
 

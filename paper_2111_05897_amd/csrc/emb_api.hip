@@ -39,7 +39,20 @@ struct EventRec {
 
 thread_local std::string g_create_error;
 
+// Scratch memory of one emb_backward_update (and of the dedup a cached context runs in its lookups): either the
+// buffers a context allocated in emb_create for its max_ids, or the carved-up static array below.
+struct Workspace {
+  uint64_t cap = 0;  // ids the buffers are sized for
+  uint32_t *keys[2] = {nullptr, nullptr}, *bags[2] = {nullptr, nullptr};
+  uint32_t *hist = nullptr, *total = nullptr, *blk_heads = nullptr, *blk_multi = nullptr;
+  uint32_t *unique_keys = nullptr, *seg_off = nullptr, *multi_list = nullptr, *long_list = nullptr;
+  uint32_t *counters = nullptr, *ranges = nullptr;
+  double* partials = nullptr;
+  uint32_t *tile_key[2] = {nullptr, nullptr}, *tile_val[2] = {nullptr, nullptr};
+};
+
 }  // namespace
+
 
 struct emb_ctx {
   int device = 0;
@@ -56,13 +69,9 @@ struct emb_ctx {
   SlotArrays slots{};
   uint32_t* key_base_dev = nullptr;  // [T]
   uint32_t* zero_row = nullptr;      // kZeroRowBytes of zeros
-  // workspace
-  uint32_t *keys[2] = {nullptr, nullptr}, *bags[2] = {nullptr, nullptr};
-  uint32_t *hist = nullptr, *total = nullptr, *blk_heads = nullptr, *blk_multi = nullptr;
-  uint32_t *unique_keys = nullptr, *seg_off = nullptr, *multi_list = nullptr, *long_list = nullptr;
-  uint32_t *counters = nullptr, *ranges = nullptr;
-  double* partials = nullptr;
-  uint32_t *tile_key[2] = {nullptr, nullptr}, *tile_val[2] = {nullptr, nullptr};
+  uint32_t *bag_beg = nullptr, *bag_end = nullptr;  // [max_batch * S + 1] each: bag bounds of the forward from the index form
+  Workspace ws;                      // allocated in emb_create for max_ids
+  Workspace last_ws;                 // the workspace that holds the index form of the last dedup
   // tables kept in host memory behind an LRU cache (emb_create_cached); lru[t].C == 0: table t is resident
   std::vector<LruView> lru;
   std::vector<uint64_t*> lru_stats;   // device [4] per cached table
@@ -178,12 +187,14 @@ struct StageTimer {
   }
 };
 
-int check_batch(emb_ctx* ctx, const emb_batch* b) {
+int check_batch(emb_ctx* ctx, const emb_batch* b, uint64_t ids_limit = 0) {  // ids_limit 0: the context's max_ids
   if (!ctx) return fail(nullptr, EMB_EINVAL, "null context");
   if (!b) return fail(ctx, EMB_EINVAL, "null batch");
   if (b->reserved != 0) return fail(ctx, EMB_EINVAL, "batch.reserved must be 0");
   if (b->batch_size > ctx->max_batch) return fail(ctx, EMB_EINVAL, "batch_size exceeds max_batch given to emb_create");
-  if (b->num_ids > ctx->max_ids) return fail(ctx, EMB_EINVAL, "num_ids exceeds max_ids given to emb_create");
+  if (b->num_ids > (ids_limit ? ids_limit : ctx->max_ids))
+    return fail(ctx, EMB_EINVAL, ids_limit ? "num_ids exceeds what the workspace is sized for"
+                                           : "num_ids exceeds max_ids given to emb_create");
   if (b->batch_size && !b->offsets) return fail(ctx, EMB_EINVAL, "null offsets");
   if (b->num_ids && !b->ids) return fail(ctx, EMB_EINVAL, "null ids");
   if (b->batch_size == 0 && b->num_ids != 0) return fail(ctx, EMB_EINVAL, "ids without samples");
@@ -191,11 +202,11 @@ int check_batch(emb_ctx* ctx, const emb_batch* b) {
 }
 
 // Every buffer the backward kernels dereference; a null here would be a device-side fault.
-bool workspace_complete(const emb_ctx* c) {
-  const void* ptrs[] = {c->keys[0],  c->keys[1],     c->bags[0], c->bags[1],    c->hist,     c->total,
-                        c->blk_heads, c->blk_multi,  c->unique_keys, c->seg_off, c->multi_list, c->long_list, c->counters,
-                        c->tile_key[0], c->tile_key[1], c->tile_val[0], c->tile_val[1],
-                        c->ranges,    c->partials,   c->key_base_dev, c->slots.salt, c->slots.rows, c->slots.mask,
+bool workspace_complete(const emb_ctx* c, const Workspace& w) {
+  const void* ptrs[] = {w.keys[0],  w.keys[1],     w.bags[0], w.bags[1],    w.hist,     w.total,
+                        w.blk_heads, w.blk_multi,  w.unique_keys, w.seg_off, w.multi_list, w.long_list, w.counters,
+                        w.tile_key[0], w.tile_key[1], w.tile_val[0], w.tile_val[1],
+                        w.ranges,    w.partials,   c->key_base_dev, c->slots.salt, c->slots.rows, c->slots.mask,
                         c->slots.key_base, c->slots.col};
   for (const void* p : ptrs)
     if (!p) return false;
@@ -401,28 +412,31 @@ static int emb_create_impl(const emb_config* cfg, const uint64_t* cache_rows, em
     CK(dev_upload(ctx, &ctx->key_base_dev, ctx->key_base_host), "upload(table key base)");
     CK(dev_alloc(ctx, &ctx->zero_row, kZeroRowBytes / sizeof(uint32_t)), "hipMalloc(zero row)");
     CK(hipMemset(ctx->zero_row, 0, kZeroRowBytes), "hipMemset(zero row)");
+    CK(dev_alloc(ctx, &ctx->bag_beg, (uint64_t)cfg->max_batch * cfg->num_slots + 1), "hipMalloc(bag bounds)");
+    CK(dev_alloc(ctx, &ctx->bag_end, (uint64_t)cfg->max_batch * cfg->num_slots + 1), "hipMalloc(bag bounds)");
   }
   // workspace
   const uint64_t cap = ctx->max_ids ? ctx->max_ids : 1;
   const uint64_t ntiles = (cap + kTile - 1) / kTile;
+  ctx->ws.cap = cap;
   for (int i = 0; i < 2; ++i) {
-    CK(dev_alloc(ctx, &ctx->keys[i], cap), "hipMalloc(sort keys)");
-    CK(dev_alloc(ctx, &ctx->bags[i], cap), "hipMalloc(sort payload)");
+    CK(dev_alloc(ctx, &ctx->ws.keys[i], cap), "hipMalloc(sort keys)");
+    CK(dev_alloc(ctx, &ctx->ws.bags[i], cap), "hipMalloc(sort payload)");
   }
-  CK(dev_alloc(ctx, &ctx->hist, ((uint64_t)1 << kSortMaxBits) * kSortMaxBlocks), "hipMalloc(histograms)");
-  CK(dev_alloc(ctx, &ctx->total, (uint64_t)1 << kSortMaxBits), "hipMalloc(digit totals)");
-  CK(dev_alloc(ctx, &ctx->blk_heads, (cap + kUniqueTile - 1) / kUniqueTile + 1), "hipMalloc(block heads)");
-  CK(dev_alloc(ctx, &ctx->blk_multi, (cap + kUniqueTile - 1) / kUniqueTile + 1), "hipMalloc(block multi-tile counts)");
-  CK(dev_alloc(ctx, &ctx->unique_keys, cap), "hipMalloc(unique keys)");
-  CK(dev_alloc(ctx, &ctx->seg_off, cap + 1), "hipMalloc(segment offsets)");
-  CK(dev_alloc(ctx, &ctx->multi_list, ntiles), "hipMalloc(multi-tile list)");
-  CK(dev_alloc(ctx, &ctx->long_list, ntiles), "hipMalloc(long segment list)");
-  CK(dev_alloc(ctx, &ctx->counters, 8), "hipMalloc(counters)");
-  CK(dev_alloc(ctx, &ctx->ranges, cfg->num_tables + 1), "hipMalloc(table ranges)");
-  CK(dev_alloc(ctx, &ctx->partials, 2 * ntiles * ctx->pstride), "hipMalloc(partials)");
+  CK(dev_alloc(ctx, &ctx->ws.hist, ((uint64_t)1 << kSortMaxBits) * kSortMaxBlocks), "hipMalloc(histograms)");
+  CK(dev_alloc(ctx, &ctx->ws.total, (uint64_t)1 << kSortMaxBits), "hipMalloc(digit totals)");
+  CK(dev_alloc(ctx, &ctx->ws.blk_heads, (cap + kUniqueTile - 1) / kUniqueTile + 1), "hipMalloc(block heads)");
+  CK(dev_alloc(ctx, &ctx->ws.blk_multi, (cap + kUniqueTile - 1) / kUniqueTile + 1), "hipMalloc(block multi-tile counts)");
+  CK(dev_alloc(ctx, &ctx->ws.unique_keys, cap), "hipMalloc(unique keys)");
+  CK(dev_alloc(ctx, &ctx->ws.seg_off, cap + 1), "hipMalloc(segment offsets)");
+  CK(dev_alloc(ctx, &ctx->ws.multi_list, ntiles), "hipMalloc(multi-tile list)");
+  CK(dev_alloc(ctx, &ctx->ws.long_list, ntiles), "hipMalloc(long segment list)");
+  CK(dev_alloc(ctx, &ctx->ws.counters, 8), "hipMalloc(counters)");
+  CK(dev_alloc(ctx, &ctx->ws.ranges, cfg->num_tables + 1), "hipMalloc(table ranges)");
+  CK(dev_alloc(ctx, &ctx->ws.partials, 2 * ntiles * ctx->pstride), "hipMalloc(partials)");
   for (int i = 0; i < 2; ++i) {
-    CK(dev_alloc(ctx, &ctx->tile_key[i], ntiles), "hipMalloc(tile order keys)");
-    CK(dev_alloc(ctx, &ctx->tile_val[i], ntiles), "hipMalloc(tile order)");
+    CK(dev_alloc(ctx, &ctx->ws.tile_key[i], ntiles), "hipMalloc(tile order keys)");
+    CK(dev_alloc(ctx, &ctx->ws.tile_val[i], ntiles), "hipMalloc(tile order)");
   }
 
   if (ctx->any_cached) {
@@ -462,21 +476,22 @@ int emb_destroy(emb_ctx* ctx) {
 
 // The index form of the batch (section 4.2.3): keys built, sorted (stable LSD radix) and run-length encoded.
 // Leaves the sorted pairs in keys/bags[ctx->sorted_buf] and unique_keys / seg_off / counters filled.
-static int run_dedup(emb_ctx* ctx, const emb_batch* batch, hipStream_t stream) {
+static int run_dedup(emb_ctx* ctx, const Workspace& ws, const emb_batch* batch, hipStream_t stream) {
   const uint32_t n = (uint32_t)batch->num_ids;
   ctx->last_n = n;
   ctx->have_dedup = true;
+  ctx->last_ws = ws;
   ctx->sorted_buf = 0;
   if (n == 0) {  // leave an empty index form behind
-    CKH(launch_unique(ctx->keys[0], 0, ctx->blk_heads, ctx->blk_multi, ctx->unique_keys, ctx->seg_off,
-                      ctx->multi_list, ctx->counters, stream),
+    CKH(launch_unique(ws.keys[0], 0, ws.blk_heads, ws.blk_multi, ws.unique_keys, ws.seg_off,
+                      ws.multi_list, ws.counters, stream),
         "unique");
     return EMB_OK;
   }
   {
     StageTimer tm(ctx, ST_BUILD_KEYS, stream);
     CKH(launch_build_keys(ctx->slots, batch->ids, batch->offsets, batch->batch_size, ctx->S, ctx->mix, 0,
-                          ctx->keys[0], ctx->bags[0], stream),
+                          ws.keys[0], ws.bags[0], stream),
         "build_keys");
   }
   const SortPlan plan = make_sort_plan(n, ctx->key_bits, ctx->sort_max_bits);
@@ -485,16 +500,16 @@ static int run_dedup(emb_ctx* ctx, const emb_batch* batch, hipStream_t stream) {
     const int shift = pass * plan.bits;
     {
       StageTimer tm(ctx, ST_SORT_HIST, stream);
-      CKH(launch_radix_hist(plan, shift, ctx->keys[src], ctx->hist, stream), "radix_hist");
+      CKH(launch_radix_hist(plan, shift, ws.keys[src], ws.hist, stream), "radix_hist");
     }
     {
       StageTimer tm(ctx, ST_SORT_SCAN, stream);
-      CKH(launch_radix_scan(plan, ctx->hist, ctx->total, stream), "radix_scan");
+      CKH(launch_radix_scan(plan, ws.hist, ws.total, stream), "radix_scan");
     }
     {
       StageTimer tm(ctx, ST_SORT_SCATTER, stream);
-      CKH(launch_radix_scatter(plan, shift, ctx->keys[src], ctx->bags[src], ctx->keys[src ^ 1], ctx->bags[src ^ 1],
-                               ctx->hist, ctx->total, stream),
+      CKH(launch_radix_scatter(plan, shift, ws.keys[src], ws.bags[src], ws.keys[src ^ 1], ws.bags[src ^ 1],
+                               ws.hist, ws.total, stream),
           "radix_scatter");
     }
     src ^= 1;
@@ -502,8 +517,8 @@ static int run_dedup(emb_ctx* ctx, const emb_batch* batch, hipStream_t stream) {
   ctx->sorted_buf = src;
   {
     StageTimer tm(ctx, ST_UNIQUE, stream);
-    CKH(launch_unique(ctx->keys[src], n, ctx->blk_heads, ctx->blk_multi, ctx->unique_keys, ctx->seg_off,
-                      ctx->multi_list, ctx->counters, stream),
+    CKH(launch_unique(ws.keys[src], n, ws.blk_heads, ws.blk_multi, ws.unique_keys, ws.seg_off,
+                      ws.multi_list, ws.counters, stream),
         "unique");
   }
   return EMB_OK;
@@ -517,7 +532,7 @@ static int admit_batch(emb_ctx* ctx, hipStream_t stream) {
     if (ctx->lru[t].C == 0) continue;
     LruScratch sc = ctx->lru_scratch;
     sc.stats = ctx->lru_stats[t];
-    CKH(launch_lru_admit(ctx->lru[t], sc, ctx->unique_keys, ctx->counters, (uint32_t)ctx->last_n, ctx->lru_step, stream),
+    CKH(launch_lru_admit(ctx->lru[t], sc, ctx->ws.unique_keys, ctx->ws.counters, (uint32_t)ctx->last_n, ctx->lru_step, stream),
         "lru_admit");
   }
   return EMB_OK;
@@ -531,8 +546,8 @@ static int emb_lookup_pool_impl(emb_ctx* ctx, const emb_batch* batch, float* poo
   hipStream_t stream = (hipStream_t)hip_stream;
   CKH(hipSetDevice(ctx->device), "hipSetDevice");
   if (ctx->any_cached) {  // the rows must be in the cache before they are gathered
-    if (!workspace_complete(ctx)) return fail(ctx, EMB_ESTATE, "workspace is incomplete (a buffer is null)");
-    if ((rc = run_dedup(ctx, batch, stream)) != EMB_OK) return rc;
+    if (!workspace_complete(ctx, ctx->ws)) return fail(ctx, EMB_ESTATE, "workspace is incomplete (a buffer is null)");
+    if ((rc = run_dedup(ctx, ctx->ws, batch, stream)) != EMB_OK) return rc;
     if ((rc = admit_batch(ctx, stream)) != EMB_OK) return rc;
   }
   for (const TableView& tv : ctx->tables) {
@@ -553,14 +568,53 @@ static int emb_lookup_pool_indexed_impl(emb_ctx* ctx, uint32_t batch_size, uint6
   if (batch_size == 0) return EMB_OK;
   if (!pooled || (num_ids && (!keys || !seg_off || !seg_bags))) return fail(ctx, EMB_EINVAL, "null buffer");
   if (ctx->any_cached) return fail(ctx, EMB_ESTATE, "not available for tables kept behind a cache");
+  const Workspace& ws = ctx->ws;
+  if (!workspace_complete(ctx, ws) || !ctx->bag_beg || !ctx->bag_end)
+    return fail(ctx, EMB_ESTATE, "workspace is incomplete (a buffer is null)");
   hipStream_t stream = (hipStream_t)hip_stream;
   CKH(hipSetDevice(ctx->device), "hipSetDevice");
-  CKH(launch_zero_f32(pooled, (uint64_t)batch_size * ctx->width, stream), "zero(pooled)");
+  ctx->have_dedup = false;  // the sort buffers that held the last index form are reused below
+  const uint32_t n = (uint32_t)num_ids, n_bags = batch_size * ctx->S;
+  if (n == 0 || num_unique == 0) {
+    CKH(launch_zero_f32(pooled, (uint64_t)batch_size * ctx->width, stream), "zero(pooled)");
+    return EMB_OK;
+  }
+  int src = 0;
+  {
+    StageTimer tm(ctx, ST_BUILD_KEYS, stream);
+    CKH(launch_expand_index(seg_off, seg_bags, (uint32_t)num_unique, n, n_bags, ws.keys[0], ws.bags[0], stream), "expand_index");
+  }
+  const SortPlan plan = make_sort_plan(n, bit_length(n_bags), ctx->sort_max_bits);  // bag values 0 .. n_bags
+  for (int pass = 0; pass < plan.passes; ++pass) {
+    const int shift = pass * plan.bits;
+    {
+      StageTimer tm(ctx, ST_SORT_HIST, stream);
+      CKH(launch_radix_hist(plan, shift, ws.keys[src], ws.hist, stream), "radix_hist");
+    }
+    {
+      StageTimer tm(ctx, ST_SORT_SCAN, stream);
+      CKH(launch_radix_scan(plan, ws.hist, ws.total, stream), "radix_scan");
+    }
+    {
+      StageTimer tm(ctx, ST_SORT_SCATTER, stream);
+      CKH(launch_radix_scatter(plan, shift, ws.keys[src], ws.bags[src], ws.keys[src ^ 1], ws.bags[src ^ 1], ws.hist,
+                               ws.total, stream),
+          "radix_scatter");
+    }
+    src ^= 1;
+  }
+  {
+    StageTimer tm(ctx, ST_UNIQUE, stream);
+    CKH(launch_zero_u32(ctx->bag_beg, (uint64_t)n_bags + 1, stream), "zero(bag bounds)");
+    CKH(launch_zero_u32(ctx->bag_end, (uint64_t)n_bags + 1, stream), "zero(bag bounds)");
+    CKH(launch_bag_bounds(ws.keys[src], n, ctx->bag_beg, ctx->bag_end, stream), "bag_bounds");
+  }
   for (size_t t = 0; t < ctx->tables.size(); ++t) {
     StageTimer tm(ctx, ST_GATHER_POOL, stream);
-    CKH(launch_indexed_pool(ctx->tables[t], (uint32_t)t, ctx->slots, keys, seg_off, seg_bags, (uint32_t)num_unique,
-                            (uint32_t)num_ids, batch_size, ctx->S, ctx->width, pooled, stream),
-        "indexed_pool");
+    IndexedBags ix{ctx->bag_beg, ctx->bag_end, ws.bags[src], keys, (uint32_t)num_unique, (uint32_t)t};
+    CKH(launch_gather_pool(ctx->tables[t], ctx->slots, nullptr, nullptr, batch_size, ctx->S, ctx->width, ctx->mix,
+                           ctx->zero_row, pooled, stream, &ix),
+        "gather_pool(indexed)");
   }
   return EMB_OK;
 }
@@ -578,49 +632,50 @@ static int emb_hash_rows_impl(emb_ctx* ctx, const emb_batch* batch, uint32_t* ro
   return EMB_OK;
 }
 
-static int emb_backward_update_impl(emb_ctx* ctx, const emb_batch* batch, const float* d_pooled, void* hip_stream) {
-  int rc = check_batch(ctx, batch);
+static int backward_update_with(emb_ctx* ctx, const Workspace& ws, const emb_batch* batch, const float* d_pooled,
+                                void* hip_stream) {
+  int rc = check_batch(ctx, batch, ws.cap);
   if (rc) return rc;
-  if (!workspace_complete(ctx)) return fail(ctx, EMB_ESTATE, "workspace is incomplete (a buffer is null)");
+  if (!workspace_complete(ctx, ws)) return fail(ctx, EMB_ESTATE, "workspace is incomplete (a buffer is null)");
   if (batch->batch_size && !d_pooled) return fail(ctx, EMB_EINVAL, "null d_pooled");
   hipStream_t stream = (hipStream_t)hip_stream;
   CKH(hipSetDevice(ctx->device), "hipSetDevice");
   const uint32_t n = (uint32_t)batch->num_ids;
-  if ((rc = run_dedup(ctx, batch, stream)) != EMB_OK) return rc;
+  if ((rc = run_dedup(ctx, ws, batch, stream)) != EMB_OK) return rc;
   if (n == 0) return EMB_OK;  // nothing to update
   const int src = ctx->sorted_buf;
   const bool multi_table = ctx->tables.size() > 1;
   if (multi_table)  // each table's stretch of the sorted list (found before any key is rewritten below)
-    CKH(launch_table_ranges(ctx->keys[src], n, ctx->key_base_dev, (uint32_t)ctx->tables.size(), ctx->ranges, stream),
+    CKH(launch_table_ranges(ws.keys[src], n, ctx->key_base_dev, (uint32_t)ctx->tables.size(), ws.ranges, stream),
         "table_ranges");
-  const uint32_t* sorted_keys = ctx->keys[src];
-  const uint32_t* unique_keys = ctx->unique_keys;
+  const uint32_t* sorted_keys = ws.keys[src];
+  const uint32_t* unique_keys = ws.unique_keys;
   if (ctx->any_cached) {
     // rows that were evicted since the lookup come back; then the kernels below address cache slots: they
     // only compare neighbouring keys for equality, and key_base + slot stays inside the table's key range
     if ((rc = admit_batch(ctx, stream)) != EMB_OK) return rc;
-    uint32_t* tk = ctx->keys[src ^ 1];
-    CKH(hipMemcpyAsync(tk, ctx->keys[src], (size_t)n * sizeof(uint32_t), hipMemcpyDeviceToDevice, stream), "copy(keys)");
-    CKH(hipMemcpyAsync(ctx->unique_slots, ctx->unique_keys, (size_t)n * sizeof(uint32_t), hipMemcpyDeviceToDevice, stream),
+    uint32_t* tk = ws.keys[src ^ 1];
+    CKH(hipMemcpyAsync(tk, ws.keys[src], (size_t)n * sizeof(uint32_t), hipMemcpyDeviceToDevice, stream), "copy(keys)");
+    CKH(hipMemcpyAsync(ctx->unique_slots, ws.unique_keys, (size_t)n * sizeof(uint32_t), hipMemcpyDeviceToDevice, stream),
         "copy(unique keys)");
     for (size_t t = 0; t < ctx->lru.size(); ++t) {
       if (ctx->lru[t].C == 0) continue;
-      CKH(launch_lru_translate(ctx->lru[t], tk, multi_table ? ctx->ranges + t : nullptr, nullptr, n, stream), "lru_translate");
-      CKH(launch_lru_translate(ctx->lru[t], ctx->unique_slots, nullptr, ctx->counters, n, stream), "lru_translate");
+      CKH(launch_lru_translate(ctx->lru[t], tk, multi_table ? ws.ranges + t : nullptr, nullptr, n, stream), "lru_translate");
+      CKH(launch_lru_translate(ctx->lru[t], ctx->unique_slots, nullptr, ws.counters, n, stream), "lru_translate");
     }
     sorted_keys = tk;
     unique_keys = ctx->unique_slots;
   }
   BackwardArgs a{};
   a.keys = sorted_keys;
-  a.bags = ctx->bags[src];
+  a.bags = ws.bags[src];
   a.n = n;
   a.d_pooled = d_pooled;
   a.S = ctx->S;
   a.width = ctx->width;
   a.slot_col = ctx->slots.col;
   a.uniform = ctx->uniform;
-  a.partials = ctx->partials;
+  a.partials = ws.partials;
   a.pstride = ctx->pstride;
   a.range = nullptr;
   a.tile_perm = nullptr;
@@ -628,27 +683,27 @@ static int emb_backward_update_impl(emb_ctx* ctx, const emb_batch* batch, const 
   a.lr = ctx->lr;
   a.eps = ctx->eps;
   a.unique_keys = unique_keys;
-  a.seg_off = ctx->seg_off;
-  a.counters = ctx->counters;
-  a.multi_list = ctx->multi_list;
-  a.long_list = ctx->long_list;
+  a.seg_off = ws.seg_off;
+  a.counters = ws.counters;
+  a.multi_list = ws.multi_list;
+  a.long_list = ws.long_list;
   {
     StageTimer tm(ctx, ST_TILE_ORDER, stream);
     // shift that leaves 8 bits of the bag index (the tile keys use 7: 128 buckets of consecutive bags, sample-major)
     int shift = bit_length((uint64_t)batch->batch_size * ctx->S - 1) - 8;
     if (shift < 0) shift = 0;
-    CKH(launch_tile_order(a.keys, a.bags, n, shift, ctx->key_base_dev, (uint32_t)ctx->tables.size(), ctx->tile_key,
-                          ctx->tile_val, ctx->hist, ctx->total, &a.tile_perm, stream),
+    CKH(launch_tile_order(a.keys, a.bags, n, shift, ctx->key_base_dev, (uint32_t)ctx->tables.size(), ws.tile_key,
+                          ws.tile_val, ws.hist, ws.total, &a.tile_perm, stream),
         "tile_order");
   }
   for (size_t t = 0; t < ctx->tables.size(); ++t) {
     StageTimer tm(ctx, ST_REDUCE_UPDATE, stream);
-    a.range = multi_table ? ctx->ranges + t : nullptr;
+    a.range = multi_table ? ws.ranges + t : nullptr;
     CKH(launch_tile_reduce_update(ctx->tables[t], a, stream), "tile_reduce_update");
   }
   {
     StageTimer tm(ctx, ST_FIXUP, stream);
-    CKH(launch_classify_multi(a, ctx->counters, ctx->long_list, stream), "classify_multi");
+    CKH(launch_classify_multi(a, ws.counters, ws.long_list, stream), "classify_multi");
   }
   for (size_t t = 0; t < ctx->tables.size(); ++t) {
     StageTimer tm(ctx, ST_FIXUP, stream);
@@ -657,13 +712,18 @@ static int emb_backward_update_impl(emb_ctx* ctx, const emb_batch* batch, const 
   return EMB_OK;
 }
 
+static int emb_backward_update_impl(emb_ctx* ctx, const emb_batch* batch, const float* d_pooled, void* hip_stream) {
+  if (!ctx) return fail(nullptr, EMB_EINVAL, "null context");
+  return backward_update_with(ctx, ctx->ws, batch, d_pooled, hip_stream);
+}
+
 static int emb_dedup_sizes_impl(emb_ctx* ctx, uint64_t* num_unique, uint64_t* num_ids) {
   if (!ctx) return fail(nullptr, EMB_EINVAL, "null context");
   if (!ctx->have_dedup) return fail(ctx, EMB_ESTATE, "no emb_backward_update has run on this context");
   CKH(hipSetDevice(ctx->device), "hipSetDevice");
   CKH(hipDeviceSynchronize(), "hipDeviceSynchronize");
   uint32_t c[2] = {0, 0};
-  CKH(hipMemcpy(c, ctx->counters, sizeof(c), hipMemcpyDeviceToHost), "hipMemcpy(counters)");
+  CKH(hipMemcpy(c, ctx->last_ws.counters, sizeof(c), hipMemcpyDeviceToHost), "hipMemcpy(counters)");
   if (num_unique) *num_unique = c[0];
   if (num_ids) *num_ids = ctx->last_n;
   return EMB_OK;
@@ -675,7 +735,7 @@ static int emb_read_dedup_impl(emb_ctx* ctx, uint64_t* keys, uint32_t* seg_off, 
   if (rc) return rc;
   if (keys && U) {
     std::vector<uint32_t> tmp(U);
-    CKH(hipMemcpy(tmp.data(), ctx->unique_keys, U * sizeof(uint32_t), hipMemcpyDeviceToHost), "hipMemcpy(keys)");
+    CKH(hipMemcpy(tmp.data(), ctx->last_ws.unique_keys, U * sizeof(uint32_t), hipMemcpyDeviceToHost), "hipMemcpy(keys)");
     size_t t = 0;
     const size_t T = ctx->key_base_host.size();
     for (uint64_t u = 0; u < U; ++u) {  // keys ascend, so the table index only moves forward
@@ -683,9 +743,9 @@ static int emb_read_dedup_impl(emb_ctx* ctx, uint64_t* keys, uint32_t* seg_off, 
       keys[u] = ((uint64_t)t << 32) | (uint64_t)(tmp[u] - ctx->key_base_host[t]);
     }
   }
-  if (seg_off) CKH(hipMemcpy(seg_off, ctx->seg_off, (U + 1) * sizeof(uint32_t), hipMemcpyDeviceToHost), "hipMemcpy(seg_off)");
+  if (seg_off) CKH(hipMemcpy(seg_off, ctx->last_ws.seg_off, (U + 1) * sizeof(uint32_t), hipMemcpyDeviceToHost), "hipMemcpy(seg_off)");
   if (seg_bags && N)
-    CKH(hipMemcpy(seg_bags, ctx->bags[ctx->sorted_buf], N * sizeof(uint32_t), hipMemcpyDeviceToHost),
+    CKH(hipMemcpy(seg_bags, ctx->last_ws.bags[ctx->sorted_buf], N * sizeof(uint32_t), hipMemcpyDeviceToHost),
         "hipMemcpy(seg_bags)");
   return EMB_OK;
 }

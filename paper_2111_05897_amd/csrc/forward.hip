@@ -26,6 +26,13 @@ struct GatherArgs {
   int mix;
   int stream_out;              // 1: the table serves every slot, so a launch writes whole rows of `pooled`
   float* pooled;
+  // forward from the index form (INDEXED kernels): bag `g` holds entries [bag_beg[g], bag_end[g]) of entry_key,
+  // entry_key[i] = position u of a unique key, keys64[u] = (table << 32) | row
+  const uint32_t* bag_beg;
+  const uint32_t* bag_end;
+  const uint32_t* entry_key;
+  const uint64_t* keys64;
+  uint32_t num_unique, table;
 };
 
 // 16 bytes of a row as loaded, widened only when it is added.
@@ -56,7 +63,9 @@ __device__ __forceinline__ uint32_t group_bcast(uint32_t v, int src) {
   else return (uint32_t)__shfl((int)v, src, LANES);
 }
 
-template <typename T, int D>
+constexpr uint32_t kNoRow = 0xFFFFFFFFu;  // INDEXED: an entry that names no row of this table (malformed input) adds zeros
+
+template <typename T, int D, bool INDEXED>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(sizeof(T) == 4 && D <= 64 ? 8 : 1, 8))) void k_gather_pool(GatherArgs a) {
   constexpr int VEC = 16 / (int)sizeof(T);
   constexpr int LANES = D / VEC;            // lanes that cover one row with 16 bytes each
@@ -72,7 +81,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(sizeof(T
   const uint32_t b = lb / a.n_slots_t;
   const uint32_t slot = a.slot_list[lb - b * a.n_slots_t];
   const size_t bag = (size_t)b * a.S + slot;
-  const int beg = a.offsets[bag], end = a.offsets[bag + 1];
+  const int beg = INDEXED ? (int)a.bag_beg[bag] : a.offsets[bag];
+  const int end = INDEXED ? (int)a.bag_end[bag] : a.offsets[bag + 1];
   const uint64_t salt = a.slot_salt[slot];
   const T* __restrict__ base = reinterpret_cast<const T*>(a.w) + lane * VEC;
   const T* __restrict__ zero_row = reinterpret_cast<const T*>(a.zeros) + lane * VEC;
@@ -93,9 +103,18 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(sizeof(T
       const int idx = cbase + q * LANES + lane;
       // ids are read once and pooled rows written once: with one table they are streamed past the caches, which
       // are kept for table rows (with several tables the launches share cache lines of both arrays)
-      const uint64_t id = idx < end ? (a.stream_out ? __builtin_nontemporal_load(ids + idx) : ids[idx]) : 0ull;
-      uint32_t r = idx < end ? hash_row(id, salt, a.rows, a.mask, a.mix) : 0u;
-      if (a.where) {  // table behind the LRU cache: the row's slot (every row of the batch was admitted)
+      uint32_t r = 0u;
+      if constexpr (INDEXED) {
+        if (idx < end) {
+          const uint32_t u = a.entry_key[idx];
+          const uint64_t key = u < a.num_unique ? a.keys64[u] : ~0ull;
+          r = ((uint32_t)(key >> 32) == a.table && (key & 0xFFFFFFFFull) < a.rows) ? (uint32_t)key : kNoRow;
+        }
+      } else {
+        const uint64_t id = idx < end ? (a.stream_out ? __builtin_nontemporal_load(ids + idx) : ids[idx]) : 0ull;
+        r = idx < end ? hash_row(id, salt, a.rows, a.mask, a.mix) : 0u;
+      }
+      if (a.where && r != kNoRow) {  // table behind the LRU cache: the row's slot (every row of the batch was admitted)
         const int32_t slot = idx < end ? a.where[r] : 0;
         r = slot >= 0 ? (uint32_t)slot : 0u;
       }
@@ -112,7 +131,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(sizeof(T
         for (int jj = 0; jj < RIF; ++jj) {
           const int j = j0 + jj;  // compile-time: id j of the round sits in lane j % LANES, register j / LANES
           const uint32_t row = group_bcast<LANES>(myrow[j / LANES], j % LANES);
-          r[jj].load(j < cnt ? base + (size_t)row * D : zero_row);
+          r[jj].load((j < cnt && !(INDEXED && row == kNoRow)) ? base + (size_t)row * D : zero_row);
         }
 #pragma unroll
         for (int jj = 0; jj < RIF; ++jj) r[jj].add_to(acc);
@@ -157,7 +176,10 @@ hipError_t launch_gp(const GatherArgs& a, hipStream_t stream) {
   constexpr int LANES = D / (16 / (int)sizeof(T));
   constexpr int GPB = kBlock / LANES;
   const uint32_t grid = (a.n_local_bags + GPB - 1) / GPB;
-  hipLaunchKernelGGL((k_gather_pool<T, D>), dim3(grid), dim3(kBlock), 0, stream, a);
+  if (a.entry_key)
+    hipLaunchKernelGGL((k_gather_pool<T, D, true>), dim3(grid), dim3(kBlock), 0, stream, a);
+  else
+    hipLaunchKernelGGL((k_gather_pool<T, D, false>), dim3(grid), dim3(kBlock), 0, stream, a);
   return hipGetLastError();
 }
 
@@ -175,98 +197,72 @@ hipError_t dispatch_dim(uint32_t dim, const GatherArgs& a, hipStream_t stream) {
 
 // ---- forward from the index form (section 4.2.3: the batch arrives as unique keys, each with the list of
 // bags that hold it) ----
-// A group of LANES lanes walks a tile of kTile entries of the bag list.  The table row of the unique key the
-// entries belong to is read once per (tile, key) and added into the pooled rows of the listed bags with
-// hardware fp32 atomics: a bag's sum then forms in no fixed order (fp32 rounding may differ from run to run,
-// inside the forward's tolerance), which is the price of reading each row once.  pooled must start at zero.
-struct IndexedArgs {
-  const uint64_t* keys;      // [U] (table << 32) | row, ascending
+// The list is turned back into per-bag lists without atomics: every entry p of seg_bags becomes the pair
+// (bag, u) with u the unique key whose segment holds p (k_expand_index), the pairs are sorted by bag with the
+// stable radix sort of the dedup (a bag's entries then stand in ascending key order, whatever the launch), the
+// first and last position of every bag are recorded (k_bag_bounds), and the gather kernel above runs with the
+// bag's entries naming unique keys instead of ids.  The sums are fp64 in a fixed order: reproducible, and equal to
+// emb_lookup_pool up to the order of fp64 additions.
+struct ExpandArgs {
   const uint32_t* seg_off;   // [U + 1]
   const uint32_t* seg_bags;  // [N]
-  uint32_t U, N;
-  const void* w;
-  const int32_t* where;
-  uint32_t table;
-  uint64_t rows;
-  const uint32_t* slot_col;
-  uint32_t S, width, n_bags;
-  float* pooled;
+  uint32_t U, N, n_bags;
+  uint32_t* key_out;         // [N] bag of the entry (n_bags for an entry that names no bag)
+  uint32_t* val_out;         // [N] u of the entry
 };
 
-template <typename T, int D>
-__global__ __launch_bounds__(kBlock) void k_indexed_pool(IndexedArgs a) {
-  constexpr int VEC = 16 / (int)sizeof(T);
-  constexpr int LANES = D / VEC;
-  constexpr int GPB = kBlock / LANES;
-  const uint32_t tile = blockIdx.x * GPB + threadIdx.x / LANES;
-  const int lane = threadIdx.x % LANES;
-  const uint64_t p0 = (uint64_t)tile * kTile;
-  if (p0 >= a.N) return;
-  const uint32_t p1 = (a.N - p0 < kTile) ? a.N : (uint32_t)p0 + kTile;
-  // the unique key entry p0 belongs to: the last u with seg_off[u] <= p0 (seg_off[U] = N > p0)
-  uint32_t lo = 0, hi = a.U;
+__global__ __launch_bounds__(kBlock) void k_expand_index(ExpandArgs a) {
+  __shared__ uint32_t s_first;
+  const uint32_t p0 = blockIdx.x * kBlock;
+  if (threadIdx.x == 0) {  // the unique key entry p0 belongs to: the last u with seg_off[u] <= p0
+    uint32_t lo = 0, hi = a.U;
+    while (hi - lo > 1) {
+      const uint32_t mid = lo + (hi - lo) / 2;
+      if (a.seg_off[mid] <= p0) lo = mid;
+      else hi = mid;
+    }
+    s_first = lo;
+  }
+  __syncthreads();
+  const uint32_t p = p0 + threadIdx.x;
+  if (p >= a.N) return;
+  // entries of one block span at most kBlock segment starts: search that window only
+  uint32_t lo = s_first, hi = s_first + kBlock + 1 < a.U ? s_first + kBlock + 1 : a.U;
   while (hi - lo > 1) {
     const uint32_t mid = lo + (hi - lo) / 2;
-    if (a.seg_off[mid] <= p0) lo = mid;
+    if (a.seg_off[mid] <= p) lo = mid;
     else hi = mid;
   }
-  uint32_t u = lo, u_end = a.seg_off[u + 1];
-  const T* __restrict__ base = reinterpret_cast<const T*>(a.w) + lane * VEC;
-  bool mine = false, loaded = false;
-  float r[VEC];
-  for (uint32_t p = (uint32_t)p0; p < p1; ++p) {
-    while (p >= u_end) {  // next key (empty segments are skipped)
-      if (u + 1 >= a.U) return;  // seg_off does not reach N: a malformed index form must not run off the arrays
-      ++u;
-      u_end = a.seg_off[u + 1];
-      loaded = false;
-    }
-    if (!loaded) {
-      const uint64_t key = a.keys[u];
-      mine = (uint32_t)(key >> 32) == a.table && (key & 0xFFFFFFFFull) < a.rows;
-      if (mine) {
-        uint32_t row = (uint32_t)key;
-        if (a.where) {
-          const int32_t slot = a.where[row];
-          row = slot >= 0 ? (uint32_t)slot : 0u;
-        }
-        Raw16<T> raw;
-        raw.load(base + (size_t)row * D);
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) r[e] = 0.f;
-        raw.add_to(r);
-      }
-      loaded = true;
-    }
-    if (mine) {
-      const uint32_t bag = a.seg_bags[p];
-      if (bag >= a.n_bags) continue;  // malformed input: no such bag
-      const uint32_t b = bag / a.S, s = bag - b * a.S;
-      float* out = a.pooled + (size_t)b * a.width + a.slot_col[s] + lane * VEC;
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) unsafeAtomicAdd(out + e, r[e]);
+  if (hi < a.U && a.seg_off[hi] <= p) {  // only with empty segments in the input: search the rest of the list
+    lo = hi;
+    hi = a.U;
+    while (hi - lo > 1) {
+      const uint32_t mid = lo + (hi - lo) / 2;
+      if (a.seg_off[mid] <= p) lo = mid;
+      else hi = mid;
     }
   }
+  const uint32_t bag = a.seg_bags[p];
+  a.key_out[p] = bag < a.n_bags ? bag : a.n_bags;
+  a.val_out[p] = lo;
 }
 
-template <typename T, int D>
-hipError_t launch_ip(const IndexedArgs& a, hipStream_t stream) {
-  constexpr int LANES = D / (16 / (int)sizeof(T));
-  constexpr int GPB = kBlock / LANES;
-  const uint64_t tiles = ((uint64_t)a.N + kTile - 1) / kTile;
-  hipLaunchKernelGGL((k_indexed_pool<T, D>), dim3((uint32_t)((tiles + GPB - 1) / GPB)), dim3(kBlock), 0, stream, a);
-  return hipGetLastError();
-}
-template <typename T>
-hipError_t dispatch_ip(uint32_t dim, const IndexedArgs& a, hipStream_t stream) {
-  switch (dim) {
-    case 8: return launch_ip<T, 8>(a, stream);
-    case 16: return launch_ip<T, 16>(a, stream);
-    case 32: return launch_ip<T, 32>(a, stream);
-    case 64: return launch_ip<T, 64>(a, stream);
-    case 128: return launch_ip<T, 128>(a, stream);
-    default: return hipErrorInvalidValue;
+// bag_beg / bag_end (zeroed first) from the pairs sorted by bag: position i starts the run of sorted[i] and ends
+// the run of sorted[i - 1] when the two differ.  The sentinel bag n_bags is recorded like any other and never read.
+__global__ __launch_bounds__(kBlock) void k_bag_bounds(const uint32_t* __restrict__ sorted, uint32_t n,
+                                                       uint32_t* __restrict__ bag_beg, uint32_t* __restrict__ bag_end) {
+  const uint32_t i = blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n) return;
+  const uint32_t k = sorted[i];
+  if (i == 0 || sorted[i - 1] != k) {
+    bag_beg[k] = i;
+    if (i) bag_end[sorted[i - 1]] = i;
   }
+  if (i == n - 1) bag_end[k] = n;
+}
+
+__global__ __launch_bounds__(kBlock) void k_zero_u32(uint32_t* __restrict__ p, uint64_t n) {
+  for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (uint64_t)gridDim.x * kBlock) p[i] = 0u;
 }
 
 __global__ __launch_bounds__(kBlock) void k_zero_f32(float4* __restrict__ p, uint64_t n4) {
@@ -285,31 +281,32 @@ hipError_t launch_zero_f32(float* p, uint64_t n, hipStream_t stream) {  // n a m
   return hipGetLastError();
 }
 
-hipError_t launch_indexed_pool(const TableView& t, uint32_t table, const SlotArrays& sl, const uint64_t* keys,
-                               const uint32_t* seg_off, const uint32_t* seg_bags, uint32_t U, uint32_t N, uint32_t B,
-                               uint32_t S, uint32_t width, float* pooled, hipStream_t stream) {
-  if (N == 0 || U == 0 || t.n_slots == 0) return hipSuccess;
-  IndexedArgs a;
-  a.keys = keys;
-  a.seg_off = seg_off;
-  a.seg_bags = seg_bags;
-  a.U = U;
-  a.N = N;
-  a.w = t.w;
-  a.where = t.where;
-  a.table = table;
-  a.rows = t.rows;
-  a.slot_col = sl.col;
-  a.S = S;
-  a.width = width;
-  a.n_bags = B * S;
-  a.pooled = pooled;
-  return t.dtype == 1 ? dispatch_ip<bf16_t>(t.dim, a, stream) : dispatch_ip<float>(t.dim, a, stream);
+hipError_t launch_zero_u32(uint32_t* p, uint64_t n, hipStream_t stream) {
+  if (n == 0) return hipSuccess;
+  const uint64_t blocks = (n + kBlock - 1) / kBlock;
+  hipLaunchKernelGGL(k_zero_u32, dim3((uint32_t)(blocks > 16384 ? 16384 : blocks)), dim3(kBlock), 0, stream, p, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_expand_index(const uint32_t* seg_off, const uint32_t* seg_bags, uint32_t U, uint32_t N, uint32_t n_bags,
+                               uint32_t* key_out, uint32_t* val_out, hipStream_t stream) {
+  if (N == 0 || U == 0) return hipSuccess;
+  ExpandArgs a{seg_off, seg_bags, U, N, n_bags, key_out, val_out};
+  hipLaunchKernelGGL(k_expand_index, dim3((N + kBlock - 1) / kBlock), dim3(kBlock), 0, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_bag_bounds(const uint32_t* sorted_bags, uint32_t N, uint32_t* bag_beg, uint32_t* bag_end,
+                             hipStream_t stream) {
+  if (N == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_bag_bounds, dim3((N + kBlock - 1) / kBlock), dim3(kBlock), 0, stream, sorted_bags, N, bag_beg,
+                     bag_end);
+  return hipGetLastError();
 }
 
 hipError_t launch_gather_pool(const TableView& t, const SlotArrays& sl, const uint64_t* ids, const int32_t* offsets,
                               uint32_t B, uint32_t S, uint32_t width, int mix, const void* zeros, float* pooled,
-                              hipStream_t stream) {
+                              hipStream_t stream, const IndexedBags* ix) {
   if (B == 0 || t.n_slots == 0) return hipSuccess;
   if (!zeros) return hipErrorInvalidValue;
   GatherArgs a;
@@ -330,6 +327,13 @@ hipError_t launch_gather_pool(const TableView& t, const SlotArrays& sl, const ui
   a.mix = mix;
   a.stream_out = t.n_slots == S ? 1 : 0;
   a.pooled = pooled;
+  a.bag_beg = ix ? ix->bag_beg : nullptr;
+  a.bag_end = ix ? ix->bag_end : nullptr;
+  a.entry_key = ix ? ix->entry_key : nullptr;
+  a.keys64 = ix ? ix->keys64 : nullptr;
+  a.num_unique = ix ? ix->num_unique : 0u;
+  a.table = ix ? ix->table : 0u;
+  if (ix && (!ix->bag_beg || !ix->bag_end || !ix->entry_key || !ix->keys64)) return hipErrorInvalidValue;
   return t.dtype == 1 ? dispatch_dim<bf16_t>(t.dim, a, stream) : dispatch_dim<float>(t.dim, a, stream);
 }
 

@@ -88,15 +88,26 @@ hipError_t launch_write_rows(const TableView& t, const uint64_t* rows_dev, uint6
 // ---- forward.hip ----
 // zeros: kZeroRowBytes of device memory holding zeros (read in place of rows past the end of a bag).
 constexpr uint32_t kZeroRowBytes = 512;
+// ix (optional): the forward from the index form -- a bag's entries are positions of unique keys instead of ids
+// (ids / offsets are then not read): bag g holds entry_key[bag_beg[g] .. bag_end[g]), keys64[u] = (table << 32) | row.
+struct IndexedBags {
+  const uint32_t* bag_beg;
+  const uint32_t* bag_end;
+  const uint32_t* entry_key;
+  const uint64_t* keys64;
+  uint32_t num_unique, table;
+};
 hipError_t launch_gather_pool(const TableView& t, const SlotArrays& sl, const uint64_t* ids, const int32_t* offsets,
                               uint32_t B, uint32_t S, uint32_t width, int mix, const void* zeros, float* pooled,
-                              hipStream_t stream);
-// The forward from the index form: pooled (zeroed first, launch_zero_f32) += row of keys[u] for every bag of
-// seg_bags[seg_off[u] .. seg_off[u+1]), for the keys of table `table`; fp32 hardware atomics.
+                              hipStream_t stream, const IndexedBags* ix = nullptr);
+// Pieces of the forward from the index form: (bag, u) pairs of every entry of the bag lists; first / last position
+// of every bag in the pairs once sorted by bag (bag_beg / bag_end zeroed beforehand).
 hipError_t launch_zero_f32(float* p, uint64_t n, hipStream_t stream);
-hipError_t launch_indexed_pool(const TableView& t, uint32_t table, const SlotArrays& sl, const uint64_t* keys,
-                               const uint32_t* seg_off, const uint32_t* seg_bags, uint32_t U, uint32_t N, uint32_t B,
-                               uint32_t S, uint32_t width, float* pooled, hipStream_t stream);
+hipError_t launch_zero_u32(uint32_t* p, uint64_t n, hipStream_t stream);
+hipError_t launch_expand_index(const uint32_t* seg_off, const uint32_t* seg_bags, uint32_t U, uint32_t N, uint32_t n_bags,
+                               uint32_t* key_out, uint32_t* val_out, hipStream_t stream);
+hipError_t launch_bag_bounds(const uint32_t* sorted_bags, uint32_t N, uint32_t* bag_beg, uint32_t* bag_end,
+                             hipStream_t stream);
 // keys_out[i] = key_base(slot) + row (or the bare row when bare_rows != 0); bags_out may be null.
 hipError_t launch_build_keys(const SlotArrays& sl, const uint64_t* ids, const int32_t* offsets, uint32_t B,
                              uint32_t S, int mix, int bare_rows, uint32_t* keys_out, uint32_t* bags_out,
