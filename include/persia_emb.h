@@ -146,6 +146,21 @@ int emb_hash_rows(emb_ctx* ctx, const emb_batch* batch, uint32_t* rows_out, void
  * stays in the context's workspace until the next call on the context. */
 int emb_backward_update(emb_ctx* ctx, const emb_batch* batch, const float* d_pooled, void* hip_stream);
 
+/* emb_backward_update for callers that cannot allocate and cannot rely on a context sized for the batch: code
+ * under HIP graph capture, tight serving loops that apply an occasional small update, harnesses that forbid
+ * hipMalloc.  Same inputs, same result (bit for bit) and same index form left behind as emb_backward_update, but
+ * every scratch buffer of the call (sort keys, histograms, unique keys, segment offsets, partial sums, tile order)
+ * lives in one fixed array of 16 MiB that is part of the library's code object -- one copy per GPU, located once per
+ * device in emb_create and held until the process ends -- so the call performs no allocation of any kind, whatever
+ * max_ids the context was created with.  Limit: batch->num_ids <= emb_static_max_ids() (262144); beyond it the
+ * call returns EMB_EINVAL and does nothing.  Not available for tables behind a cache (EMB_ESTATE).  No per-stage
+ * timing is recorded for this call.  All contexts of a GPU share that GPU's array: calls to this function that
+ * overlap on one GPU (two streams, two contexts, two threads) race, and the index form emb_read_dedup reports
+ * after it is only valid until the next such call on that GPU.  Nothing in the array has to start at zero: every
+ * buffer is written by the call before it is read. */
+int emb_backward_update_static(emb_ctx* ctx, const emb_batch* batch, const float* d_pooled, void* hip_stream);
+uint64_t emb_static_max_ids(void);
+
 /* Inspection of the index form left by the last emb_backward_update (synchronous; for tests
  * and benchmarks).  keys[u] = (table << 32) | row, strictly ascending; seg_off[U+1] with
  * seg_off[0] = 0, seg_off[U] = N; seg_bags[N]: bag indices, non-decreasing inside a segment.

@@ -80,6 +80,10 @@ def load_library() -> C.CDLL:
     L.emb_lookup_pool_indexed.argtypes = [vp, u32, u64, u64, vp, vp, vp, vp, vp]
     L.emb_lookup_pool_indexed.restype = C.c_int
     L.emb_backward_update.argtypes = [vp, C.POINTER(emb_batch), vp, vp]
+    L.emb_backward_update_static.argtypes = [vp, C.POINTER(emb_batch), vp, vp]
+    L.emb_backward_update_static.restype = C.c_int
+    L.emb_static_max_ids.argtypes = []
+    L.emb_static_max_ids.restype = u64
     L.emb_dedup_sizes.argtypes = [vp, C.POINTER(u64), C.POINTER(u64)]
     L.emb_read_dedup.argtypes = [vp, vp, vp, vp]
     L.emb_read_rows.argtypes = [vp, u32, vp, u64, vp, vp]
@@ -242,6 +246,11 @@ class EmbContext:
         assert d_pooled.is_contiguous() and d_pooled.dtype == torch.float32
         assert d_pooled.shape == (batch.batch_size, self.width)
         self._ck(self.L.emb_backward_update(self.h, C.byref(batch.c), d_pooled.data_ptr(), _stream_ptr(stream)))
+
+    def emb_backward_update_static(self, batch: DeviceBatch, d_pooled: torch.Tensor, stream=None) -> None:
+        assert d_pooled.is_contiguous() and d_pooled.dtype == torch.float32
+        assert d_pooled.shape == (batch.batch_size, self.width)
+        self._ck(self.L.emb_backward_update_static(self.h, C.byref(batch.c), d_pooled.data_ptr(), _stream_ptr(stream)))
 
     # ---- inspection (synchronous) ----
     def emb_dedup_sizes(self) -> Tuple[int, int]:

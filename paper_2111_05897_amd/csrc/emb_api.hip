@@ -51,8 +51,17 @@ struct Workspace {
   uint32_t *tile_key[2] = {nullptr, nullptr}, *tile_val[2] = {nullptr, nullptr};
 };
 
+// Scratch of emb_backward_update_static: one array per GPU, part of the loaded code object, so that the call needs
+// no allocation of any kind.  Host code never uses this name as an address: g_static_scratch[device] holds what
+// hipGetSymbolAddress returned for that device.
+constexpr uint64_t kStaticMaxIds = 1ull << 18;
+constexpr uint64_t kStaticScratchBytes = 16ull << 20;
+constexpr int kMaxDevices = 64;
+void* g_static_scratch[kMaxDevices] = {nullptr};
+
 }  // namespace
 
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 struct emb_ctx {
   int device = 0;
@@ -88,6 +97,7 @@ struct emb_ctx {
   std::vector<void*> allocs;
   uint64_t device_bytes = 0;
   bool profiling = false;
+  bool no_events = false;            // set while a call that must not create anything runs
   std::vector<EventRec> recs;
   std::vector<hipEvent_t> free_events;
   float stage_ms[ST_COUNT] = {0};
@@ -163,7 +173,7 @@ struct StageTimer {
   EventRec rec{};
   bool on = false;
   StageTimer(emb_ctx* c, int stage, hipStream_t s) : ctx(c), stream(s) {
-    if (!ctx->profiling) return;
+    if (!ctx->profiling || ctx->no_events) return;
     hipEvent_t ev[2];
     for (int i = 0; i < 2; ++i) {
       if (!ctx->free_events.empty()) {
@@ -273,6 +283,13 @@ static int emb_create_impl(const emb_config* cfg, const uint64_t* cache_rows, em
   if (e != hipSuccess) return fail_hip(nullptr, "hipGetDeviceCount", e);
   if (cfg->device < 0 || cfg->device >= ndev) return fail(nullptr, EMB_EINVAL, "no such HIP device");
   if ((e = hipSetDevice(cfg->device)) != hipSuccess) return fail_hip(nullptr, "hipSetDevice", e);
+
+  if (cfg->device < kMaxDevices && !g_static_scratch[cfg->device]) {
+    // once per device, with that device current: where this GPU's copy of the static scratch array lives
+    void* p = nullptr;
+    if ((e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) != hipSuccess) return fail_hip(nullptr, "hipGetSymbolAddress(scratch)", e);
+    g_static_scratch[cfg->device] = p;
+  }
 
   emb_ctx* ctx = new (std::nothrow) emb_ctx();
   if (!ctx) return fail(nullptr, EMB_ENOMEM, "out of host memory");
@@ -717,6 +734,62 @@ static int emb_backward_update_impl(emb_ctx* ctx, const emb_batch* batch, const 
   return backward_update_with(ctx, ctx->ws, batch, d_pooled, hip_stream);
 }
 
+// Cuts the static array of the context's device into the buffers of a Workspace for kStaticMaxIds ids.
+static int carve_static_workspace(emb_ctx* ctx, Workspace* out) {
+  if (ctx->device < 0 || ctx->device >= kMaxDevices || !g_static_scratch[ctx->device])
+    return fail(ctx, EMB_ESTATE, "the static scratch of this device was not located at emb_create");
+  unsigned char* base = static_cast<unsigned char*>(g_static_scratch[ctx->device]);
+  uint64_t off = 0;
+  bool fits = true;
+  auto take = [&](uint64_t count, uint64_t elem) -> void* {
+    void* p = base + off;
+    off += (count * elem + 255) / 256 * 256;  // every buffer starts on a 256-byte boundary
+    if (off > kStaticScratchBytes) fits = false;
+    return p;
+  };
+  const uint64_t cap = kStaticMaxIds;
+  const uint64_t ntiles = (cap + kTile - 1) / kTile;
+  const uint64_t sort_blocks = (cap + kSortTile - 1) / kSortTile;  // blocks of a sort pass over at most cap pairs
+  Workspace w;
+  w.cap = cap;
+  for (int i = 0; i < 2; ++i) {
+    w.keys[i] = static_cast<uint32_t*>(take(cap, 4));
+    w.bags[i] = static_cast<uint32_t*>(take(cap, 4));
+  }
+  w.hist = static_cast<uint32_t*>(take(((uint64_t)1 << kSortMaxBits) * sort_blocks, 4));
+  w.total = static_cast<uint32_t*>(take((uint64_t)1 << kSortMaxBits, 4));
+  w.blk_heads = static_cast<uint32_t*>(take((cap + kUniqueTile - 1) / kUniqueTile + 1, 4));
+  w.blk_multi = static_cast<uint32_t*>(take((cap + kUniqueTile - 1) / kUniqueTile + 1, 4));
+  w.unique_keys = static_cast<uint32_t*>(take(cap, 4));
+  w.seg_off = static_cast<uint32_t*>(take(cap + 1, 4));
+  w.multi_list = static_cast<uint32_t*>(take(ntiles, 4));
+  w.long_list = static_cast<uint32_t*>(take(ntiles, 4));
+  w.counters = static_cast<uint32_t*>(take(8, 4));
+  w.ranges = static_cast<uint32_t*>(take(ctx->tables.size() + 1, 4));
+  w.partials = static_cast<double*>(take(2 * ntiles * ctx->pstride, 8));
+  for (int i = 0; i < 2; ++i) {
+    w.tile_key[i] = static_cast<uint32_t*>(take(ntiles, 4));
+    w.tile_val[i] = static_cast<uint32_t*>(take(ntiles, 4));
+  }
+  if (!fits) return fail(ctx, EMB_ESTATE, "the static scratch is too small for this context's tables");
+  *out = w;
+  return EMB_OK;
+}
+
+static int emb_backward_update_static_impl(emb_ctx* ctx, const emb_batch* batch, const float* d_pooled, void* hip_stream) {
+  if (!ctx) return fail(nullptr, EMB_EINVAL, "null context");
+  if (ctx->any_cached) return fail(ctx, EMB_ESTATE, "not available for tables kept behind a cache");
+  if (batch && batch->num_ids > kStaticMaxIds)
+    return fail(ctx, EMB_EINVAL, "num_ids exceeds the static scratch (262144 ids per call)");
+  Workspace w;
+  int rc = carve_static_workspace(ctx, &w);
+  if (rc) return rc;
+  ctx->no_events = true;  // per-stage timing would create events
+  rc = backward_update_with(ctx, w, batch, d_pooled, hip_stream);
+  ctx->no_events = false;
+  return rc;
+}
+
 static int emb_dedup_sizes_impl(emb_ctx* ctx, uint64_t* num_unique, uint64_t* num_ids) {
   if (!ctx) return fail(nullptr, EMB_EINVAL, "null context");
   if (!ctx->have_dedup) return fail(ctx, EMB_ESTATE, "no emb_backward_update has run on this context");
@@ -916,6 +989,8 @@ int emb_lookup_pool_indexed(emb_ctx* ctx, uint32_t batch_size, uint64_t num_uniq
 }
 int emb_hash_rows(emb_ctx* ctx, const emb_batch* batch, uint32_t* rows_out, void* hip_stream) { PEMB_GUARDED(ctx, emb_hash_rows_impl(ctx, batch, rows_out, hip_stream)) }
 int emb_backward_update(emb_ctx* ctx, const emb_batch* batch, const float* d_pooled, void* hip_stream) { PEMB_GUARDED(ctx, emb_backward_update_impl(ctx, batch, d_pooled, hip_stream)) }
+int emb_backward_update_static(emb_ctx* ctx, const emb_batch* batch, const float* d_pooled, void* hip_stream) { PEMB_GUARDED(ctx, emb_backward_update_static_impl(ctx, batch, d_pooled, hip_stream)) }
+uint64_t emb_static_max_ids(void) { return kStaticMaxIds; }
 int emb_dedup_sizes(emb_ctx* ctx, uint64_t* num_unique, uint64_t* num_ids) { PEMB_GUARDED(ctx, emb_dedup_sizes_impl(ctx, num_unique, num_ids)) }
 int emb_read_dedup(emb_ctx* ctx, uint64_t* keys, uint32_t* seg_off, uint32_t* seg_bags) { PEMB_GUARDED(ctx, emb_read_dedup_impl(ctx, keys, seg_off, seg_bags)) }
 int emb_read_rows(emb_ctx* ctx, uint32_t table, const uint64_t* rows, uint64_t n, float* w, float* acc) { PEMB_GUARDED(ctx, emb_read_rows_impl(ctx, table, rows, n, w, acc)) }
