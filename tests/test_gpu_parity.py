@@ -276,3 +276,114 @@ def test_stage_timing_reports_every_kernel_stage(B):
     assert all(n == 0 for _, n in ctx.emb_read_stage_ms().values())
     assert ctx.emb_device_bytes() > w.cfg.tables[0].rows * w.cfg.tables[0].dim * 4
     ctx.close()
+
+
+class TestConfig4FullSizeOverlapOnBf16Table:
+    """Configuration 4 as BASELINE names it: the 64 GiB bf16 table (2^29 rows x 64) with its fp32 accumulators, 27.9 M
+    ids per batch under Zipf 1.4, lookup(t+1) on a second stream while update(t) runs (staleness 1, section 5).
+    The GPU runs the overlapped schedule once; the oracle (sparse tables) then follows the synchronous trajectory
+    step by step.  Checked: lookup(0) equals the oracle's; every later, overlapped lookup lies inside the staleness
+    envelope |pooled - pooled(W before update t)| <= sum_j |W_after[r_j] - W_before[r_j]| on 8192 sampled bags; the
+    index form of the last update bit for bit; rows and accumulators after the last update (all rows of the last
+    step's hottest keys and a sample of every step's) against the oracle.  One test per oracle step, so that a run
+    shows its progress."""
+    STEPS = 3
+    N_BAGS = 8192
+    state = {}
+
+    def test_gpu_overlapped_schedule(self, B):
+        import torch
+        st = TestConfig4FullSizeOverlapOnBf16Table.state
+        w = W.make_workload(4)
+        cfg = w.cfg
+        assert cfg.tables[0].dtype == W.BF16 and cfg.tables[0].rows == 1 << 29
+        steps = self.STEPS
+        batches = [W.make_batch(w, s) for s in range(steps)]
+        ctx = B.EmbContext.from_config(cfg, max_batch=w.batch, max_ids=max(b.num_ids for b in batches))
+        dbs = [B.DeviceBatch(b.batch_size, b.ids, b.offsets) for b in batches]
+        gen = torch.Generator(device="cuda")
+        dgr = []
+        for s in range(steps):
+            gen.manual_seed(4000 + s)
+            dgr.append(torch.randn((w.batch, cfg.pooled_width), generator=gen, device="cuda", dtype=torch.float32))
+        pooled = [torch.empty((w.batch, cfg.pooled_width), dtype=torch.float32, device="cuda") for _ in range(steps)]
+        s_upd, s_look = torch.cuda.Stream(), torch.cuda.Stream()          # default priority, both
+        ev_f = [torch.cuda.Event() for _ in range(steps)]
+        ev_b = [torch.cuda.Event() for _ in range(steps)]
+        torch.cuda.synchronize()
+        ctx.emb_lookup_pool(dbs[0], pooled[0], stream=s_look)
+        ev_f[0].record(s_look)
+        for t in range(steps):
+            if t + 1 < steps:
+                if t >= 1:
+                    s_look.wait_event(ev_b[t - 1])       # staleness bound: lookup(t+1) sees updates 0..t-1 at least
+                ctx.emb_lookup_pool(dbs[t + 1], pooled[t + 1], stream=s_look)
+                ev_f[t + 1].record(s_look)
+            s_upd.wait_event(ev_f[t])
+            ctx.emb_backward_update(dbs[t], dgr[t], stream=s_upd)
+            ev_b[t].record(s_upd)
+        torch.cuda.synchronize()
+        rng = np.random.default_rng(44)
+        n_all = w.batch * cfg.num_slots
+        D = cfg.tables[0].dim
+        st["pick"] = [np.sort(rng.choice(n_all, size=self.N_BAGS, replace=False)) for _ in range(steps)]
+        st["got"] = [pooled[t].view(-1, D)[torch.from_numpy(st["pick"][t]).cuda()].cpu().numpy() for t in range(steps)]
+        st["grads"] = [g.cpu().numpy() for g in dgr]
+        st["last_dedup"] = ctx.emb_read_dedup()
+        del pooled, dgr, dbs
+        st.update(w=w, cfg=cfg, batches=batches, ctx=ctx, orc=O.Oracle.from_config(cfg, dense=False), touched=[], done=0)
+
+    def _sampled_pooled(self, orc, b, pick, D):
+        keep = np.zeros(len(b.offsets) - 1, dtype=bool)
+        keep[pick] = True
+        bag_of = util.bag_of_occurrence(b.offsets)
+        ids_s, off_s = util.sub_batch(b, keep[bag_of], bag_of)
+        return orc.lookup_pool(ids_s, off_s).reshape(-1, D)[pick]
+
+    @pytest.mark.parametrize("t", range(STEPS))
+    def test_oracle_step(self, B, t):
+        st = TestConfig4FullSizeOverlapOnBf16Table.state
+        assert st.get("done") == t, "an earlier step failed"
+        cfg, orc, b = st["cfg"], st["orc"], st["batches"][t]
+        D = cfg.tables[0].dim
+        if t == 0:   # nothing can overlap the first lookup
+            want0 = self._sampled_pooled(orc, b, st["pick"][0], D)
+            util.assert_close(st["got"][0], want0, rtol=1e-5, atol=1e-6, err_msg="lookup(0)")
+        keys, _, _ = orc.dedup(b.ids, b.offsets)
+        rows = keys & util.LOW32
+        w_before, _ = orc.read_rows(0, rows)
+        if t + 1 < self.STEPS:
+            nb = st["batches"][t + 1]
+            pooled_before = self._sampled_pooled(orc, nb, st["pick"][t + 1], D).astype(np.float64)
+        od = orc.backward_update(b.ids, b.offsets, st["grads"][t])
+        w_after, _ = orc.read_rows(0, rows)
+        st["touched"].append(keys)
+        if t + 1 < self.STEPS:
+            # an fp32 table of |W_after - W_before| (zero elsewhere) looked up by the next batch gives the envelope
+            zero_cfg = W.EmbConfig(tables=[W.TableDesc(cfg.tables[0].rows, D, W.F32)], slots=cfg.slots, init_seed=1,
+                                   init_lo=0.0, init_hi=0.0)
+            delta = O.Oracle.from_config(zero_cfg, dense=False)
+            moved = np.abs(w_after.astype(np.float64) - w_before)
+            nz = moved.any(axis=1)
+            delta.write_rows(0, rows[nz], moved[nz].astype(np.float32))
+            envelope = self._sampled_pooled(delta, nb, st["pick"][t + 1], D).astype(np.float64)
+            delta.close()
+            err = np.abs(st["got"][t + 1].astype(np.float64) - pooled_before)
+            slack = 1e-5 * np.abs(pooled_before) + 1e-6
+            assert (err <= envelope + slack).all(), f"lookup({t + 1}): pooled outside the staleness envelope"
+        else:
+            util.compare_dedup(st["last_dedup"], od)
+        st["done"] = t + 1
+
+    def test_rows_after_the_last_update(self, B):
+        st = TestConfig4FullSizeOverlapOnBf16Table.state
+        assert st.get("done") == self.STEPS
+        rng = np.random.default_rng(45)
+        allk = np.unique(np.concatenate(st["touched"]))
+        _, seg_off, _ = st["last_dedup"]
+        hot = st["touched"][-1][np.argsort(np.diff(seg_off.astype(np.int64)))[-256:]]     # longest segments of the last step
+        sample = np.unique(np.concatenate([hot] + [rng.choice(k, size=min(100000, len(k)), replace=False) for k in st["touched"]]))
+        util.compare_rows(st["ctx"], st["orc"], st["cfg"], sample, extra_rows=512, seed=3, all_touched=allk)
+        st.pop("ctx").close()
+        st.pop("orc").close()
+        st.clear()

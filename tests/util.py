@@ -148,7 +148,23 @@ class Trajectory:
         self.orc.close()
 
 
-def sampled_step_check(binding, workload_mod, oracle_mod, w, n_bags=4096, n_rows=2048, seed=0):
+def bag_of_occurrence(offsets):
+    lens = np.diff(offsets).astype(np.int64)
+    return np.repeat(np.arange(len(lens), dtype=np.uint32), lens)
+
+
+def sub_batch(b, keep_occ, bag_of=None):
+    """(ids, offsets) of the CSR batch with the same bags that holds only the occurrences flagged in keep_occ."""
+    if bag_of is None:
+        bag_of = bag_of_occurrence(b.offsets)
+    n_bags = len(b.offsets) - 1
+    kept_per_bag = np.bincount(bag_of[keep_occ], minlength=n_bags)
+    off = np.zeros(n_bags + 1, dtype=np.int64)
+    np.cumsum(kept_per_bag, out=off[1:])
+    return b.ids[keep_occ], off.astype(np.int32)
+
+
+def sampled_step_check(binding, workload_mod, oracle_mod, w, n_bags=4096, n_rows=2048, seed=0, dense_step=None):
     """Full-size parity on sampled outputs (for workloads whose full oracle run would take minutes).
 
     One forward + backward step of workload w on the GPU; the oracle then recomputes, from the paper's
@@ -156,6 +172,10 @@ def sampled_step_check(binding, workload_mod, oracle_mod, w, n_bags=4096, n_rows
     bag lists of `n_rows` sampled unique rows -- a row's gradient depends only on its own occurrences, so
     a sub-batch that keeps exactly those occurrences gives the exact update -- and (c) the whole set of
     unique keys and segment offsets, which numpy derives from the oracle's hash of every id.
+    dense_step (optional): called with the pooled activations (device tensor) between the lookup and the update,
+    returns the gradient of the pooled activations (device tensor) that the update is fed with -- the dense network's
+    step; the embedding update is then checked against the oracle fed with that same gradient (stage isolation).
+    Without it the gradient is N(0, 1).
     """
     import torch
     cfg = w.cfg
@@ -163,12 +183,16 @@ def sampled_step_check(binding, workload_mod, oracle_mod, w, n_bags=4096, n_rows
     b = workload_mod.make_batch(w, 0)
     ctx = binding.EmbContext.from_config(cfg, max_batch=b.batch_size, max_ids=b.num_ids)
     db = binding.DeviceBatch(b.batch_size, b.ids, b.offsets)
-    gen = torch.Generator(device="cuda")
-    gen.manual_seed(1234 + w.index)
-    dp_dev = torch.randn((b.batch_size, cfg.pooled_width), generator=gen, device="cuda", dtype=torch.float32)
-    pooled = ctx.emb_lookup_pool(db)
+    pooled_dev = ctx.emb_lookup_pool(db)
     torch.cuda.synchronize()
-    pooled = pooled.cpu().numpy()
+    if dense_step is None:
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(1234 + w.index)
+        dp_dev = torch.randn((b.batch_size, cfg.pooled_width), generator=gen, device="cuda", dtype=torch.float32)
+    else:
+        dp_dev = dense_step(pooled_dev)
+    pooled = pooled_dev.cpu().numpy()
+    del pooled_dev
     ctx.emb_backward_update(db, dp_dev)
     gk, go, gb = ctx.emb_read_dedup()
     dp = dp_dev.cpu().numpy()
@@ -191,18 +215,11 @@ def sampled_step_check(binding, workload_mod, oracle_mod, w, n_bags=4096, n_rows
     assert go[0] == 0
     np.testing.assert_array_equal(np.bincount(gb, minlength=n_all_bags), lens)   # every occurrence listed once
 
-    def sub_batch(keep_occ):
-        """CSR with the same bags, holding only the occurrences flagged in keep_occ."""
-        kept_per_bag = np.bincount(bag_of[keep_occ], minlength=n_all_bags)
-        off = np.zeros(n_all_bags + 1, dtype=np.int64)
-        np.cumsum(kept_per_bag, out=off[1:])
-        return b.ids[keep_occ], off.astype(np.int32)
-
     # (a) pooled vectors of sampled bags
     pick = rng.choice(n_all_bags, size=min(n_bags, n_all_bags), replace=False)
     keep = np.zeros(n_all_bags, dtype=bool)
     keep[pick] = True
-    ids_s, off_s = sub_batch(keep[bag_of])
+    ids_s, off_s = sub_batch(b, keep[bag_of], bag_of)
     want = orc.lookup_pool(ids_s, off_s)
     cols = np.array(cfg.slot_cols())
     dims = np.array(cfg.slot_dims())
@@ -223,7 +240,7 @@ def sampled_step_check(binding, workload_mod, oracle_mod, w, n_bags=4096, n_rows
     sample_u = np.unique(np.concatenate([order[-64:], rng.choice(len(uk), size=min(n_rows, len(uk)), replace=False)]))
     sample_keys = uk[sample_u]
     keep_occ = np.isin(keys_occ, sample_keys)
-    ids_s, off_s = sub_batch(keep_occ)
+    ids_s, off_s = sub_batch(b, keep_occ, bag_of)
     orc2 = oracle_mod.Oracle.from_config(cfg, dense=False)
     ok, oo, ob = orc2.backward_update(ids_s, off_s, dp)
     np.testing.assert_array_equal(ok, sample_keys)
