@@ -23,20 +23,62 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 
 
 def algorithmic_bytes(tables):
-    """Bytes the method itself must move per step in each kernel stage and in the whole step (sort passes
-    and partial sums are implementation overhead and not counted).  `tables`: one dict per table with
-    N (ids hashed into it), bags (bags reading it), U (unique rows), Um (unique rows whose segment spans
-    tiles), D (dim), e (bytes per stored element).  Kernels that run once per table sum over tables."""
-    out = {"gather_pool": 0.0, "build_keys": 0.0, "reduce_update": 0.0, "fixup": 0.0, "step": 0.0}
+    """Bytes the method itself must move per step, per kernel stage and for the whole step, under two models.
+    `tables`: one dict per table with N (ids hashed into it), bags (bags reading it), U (unique rows), Um (unique
+    rows whose segment spans tiles), D (dim), e (bytes per stored element).  Kernels that run once per table sum
+    over tables.  Sort passes and partial sums are implementation overhead and are counted in neither model.
+
+    "occurrence": every occurrence of an id reads its table row (forward) and its bag's gradient row (backward) --
+    the traffic the kernels request; rows and gradient rows that occur several times are counted every time,
+    although caches serve the repeats, so this figure can exceed what HBM delivers (and the 8 TB/s peak).
+    "compulsory": every distinct byte once -- each unique row read once in the forward, each gradient row read
+    once in the backward: a lower bound of the HBM traffic, hence of the HBM fraction."""
+    keys = ("gather_pool", "build_keys", "reduce_update", "fixup", "step")
+    occ, comp = dict.fromkeys(keys, 0.0), dict.fromkeys(keys, 0.0)
     for t in tables:
         N, bags, U, Um, D, e = t["N"], t["bags"], t["U"], t["Um"], t["D"], t["e"]
-        fwd = 8 * N + 4 * (bags + 1) + N * D * e + bags * D * 4      # ids, offsets, row gathers, pooled write
-        out["gather_pool"] += fwd
-        out["build_keys"] += 8 * N + 4 * (bags + 1) + 8 * N          # ids re-read, (key, bag) pairs written
-        out["reduce_update"] += 8 * N + N * D * 4 + (U - Um) * (2 * D * e + 8)   # sorted pairs, grad gathers, row+acc RMW
-        out["fixup"] += Um * (2 * D * e + 8)                         # rows of segments that span tiles
-        out["step"] += fwd + 4 * N + 8 * N + 8 * U + N * D * 4 + U * (2 * D * e + 8)
-    return out
+        csr = 8 * N + 4 * (bags + 1)                                  # ids + offsets
+        for m, rows_fwd, grads in ((occ, N * D * e, N * D * 4), (comp, U * D * e, bags * D * 4)):
+            m["gather_pool"] += csr + rows_fwd + bags * D * 4         # row gathers, pooled write
+            m["build_keys"] += csr + 8 * N                            # ids re-read, (key, bag) pairs written
+            m["reduce_update"] += 8 * N + grads + (U - Um) * (2 * D * e + 8)   # sorted pairs, gradient rows, row + acc RMW
+            m["fixup"] += Um * (2 * D * e + 8)                        # rows of segments that span tiles
+            m["step"] += csr + rows_fwd + bags * D * 4 + 4 * N + 8 * N + 8 * U + grads + U * (2 * D * e + 8)
+    return occ, comp
+
+
+def cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown CPU"
+
+
+def host_mem_available_gb() -> float:
+    try:
+        for line in open("/proc/meminfo"):
+            if line.startswith("MemAvailable"):
+                return int(line.split()[1]) / (1 << 20)
+    except OSError:
+        pass
+    return 0.0
+
+
+def read_traffic_profile(path):
+    """The committed rocprofv3 --pmc summary of a workload: ({stage: bytes}, ids, unique rows, launches-per-step note) or None."""
+    if not os.path.exists(path):
+        return None
+    traffic, meta = {}, {}
+    for line in open(path):
+        f = line.split()
+        if len(f) == 3 and f[0] == "traffic":
+            traffic[f[1]] = int(f[2])
+        elif len(f) == 3 and f[0] == "workload":
+            meta[f[1]] = int(f[2])
+    return traffic, meta
 
 
 def bench_codec(args, w, binding, torch, np) -> int:
@@ -164,7 +206,7 @@ def bench_hybrid(args, w, binding, torch, np, W) -> int:
     cfg = w.cfg
     P = cfg.pooled_width
     widths = [P + W.DENSE_FEATURES] + W.MLP_HIDDEN + [1]
-    nb = max(1, min(args.distinct_batches, args.steps, 2))
+    nb = max(1, min(args.distinct_batches or 2, args.steps, 2))
     host_batches = [W.make_batch(w, s) for s in range(nb)]
     batches = [binding.DeviceBatch(b.batch_size, b.ids, b.offsets) for b in host_batches]
     feats = []
@@ -262,7 +304,13 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 0..4 (2 = the headline workload: 100 slots, 2^26 rows, fp32 D=64)")
-    ap.add_argument("--distinct-batches", type=int, default=4, help="synthetic batches generated and cycled")
+    ap.add_argument("--distinct-batches", type=int, default=0,
+                    help="synthetic batches generated and cycled (0 = the workload's own loop length, 10 for the headline workload, else 4)")
+    ap.add_argument("--min-seconds", type=float, default=1.0, help="the timed region runs at least this long")
+    ap.add_argument("--min-reps", type=int, default=20, help="... and holds at least this many repetitions of --steps steps")
+    ap.add_argument("--max-reps", type=int, default=400)
+    ap.add_argument("--cpu-dense-gb", type=float, default=40.0,
+                    help="the oracle is timed on whole (dense) tables up to this size, on touched-rows-only tables beyond")
     ap.add_argument("--overlap", action="store_true",
                     help="staleness-1 schedule: lookup(t+1) on a second stream while update(t) runs on the first")
     ap.add_argument("--codec", action="store_true",
@@ -302,10 +350,16 @@ def main() -> int:
         return bench_hybrid(args, w, binding, torch, np, W)
     if args.indexed_forward:
         return bench_indexed_forward(args, w, binding, torch, np, W)
+    if args.overlap and args.cache_frac is not None:
+        print("bench.py: --overlap and --cache-frac exclude each other: calls on a context whose tables sit behind the "
+              "cache share its admission state and must not overlap", file=sys.stderr)
+        return 2
     T = len(cfg.tables)
     e_of = [2 if t.dtype == W.BF16 else 4 for t in cfg.tables]
     slot_table = np.array([s.table for s in cfg.slots])
-    nb = max(1, min(args.distinct_batches, args.steps))
+    # distinct synthetic batches, cycled; the headline workload is a loop over 10 different batches
+    want_nb = args.distinct_batches if args.distinct_batches else (w.steps if w.steps > 1 else 4)
+    nb = max(1, min(want_nb, max(args.steps, 1)))
     t0 = time.time()
     host_batches = [W.make_batch(w, s) for s in range(nb)]
     batches = [binding.DeviceBatch(b.batch_size, b.ids, b.offsets) for b in host_batches]
@@ -339,6 +393,10 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
+    if args.overlap:
+        s_upd, s_look = torch.cuda.Stream(), torch.cuda.Stream()   # both at the default priority
+        pooled2 = [pooled, torch.empty_like(pooled)]
+
     def run_overlapped(first, count):
         """lookup(t+1) on s_look overlaps update(t) on s_upd; lookup(t+1) waits for update(t-1), update(t) for
         lookup(t): the embedding read is at most one update stale (section 5, tau = 1)."""
@@ -360,104 +418,156 @@ def main() -> int:
             ids += b.num_ids
         return ids
 
+    # ---- the timed region.  One repetition = exactly --steps steps (the 10-step loop of the headline workload with
+    # the default flags), bracketed by HIP events on the stream the kernels run on; the repetitions follow each other
+    # without a gap or a synchronisation until the region has run for at least --min-seconds (and at least
+    # --min-reps times), so that the clock has settled to what a sustained run gets.  The figure reported is the
+    # MEDIAN repetition; the whole region is bracketed by synchronisations and a wall clock as well.
+    K = args.steps
     if args.overlap:
-        s_upd, s_look = torch.cuda.Stream(), torch.cuda.Stream()   # both at the default priority
-        pooled2 = [pooled, torch.empty_like(pooled)]
         torch.cuda.synchronize()
         run_overlapped(0, max(args.warmup, 1))
         torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        ids_done = run_overlapped(args.warmup, args.steps)
-        torch.cuda.synchronize()
-        elapsed = time.perf_counter() - t0
     else:
         for i in range(args.warmup):
             step(i)
         torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        ids_done = 0
-        for i in range(args.steps):
-            ids_done += step(args.warmup + i)
-        torch.cuda.synchronize()
-        elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed * 1e3 / args.steps
-    ids_per_s = ids_done / elapsed
+    # one untimed repetition to size the region
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    if args.overlap:
+        run_overlapped(args.warmup, K)
+        torch.cuda.current_stream().wait_stream(s_upd)
+    else:
+        for i in range(K):
+            step(args.warmup + i)
+    e1.record()
+    torch.cuda.synchronize()
+    est_ms = max(e0.elapsed_time(e1), 1e-3)
+    reps = int(min(max(args.min_reps, np.ceil(args.min_seconds * 1e3 / est_ms)), args.max_reps))
+    cur = torch.cuda.current_stream()
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+    ids_rep = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    evs[0].record(cur)
+    for r in range(reps):
+        if args.overlap:
+            s_look.wait_stream(cur)
+            s_upd.wait_stream(cur)
+            n_ids = run_overlapped(args.warmup + r * K, K)
+            cur.wait_stream(s_upd)
+            cur.wait_stream(s_look)
+        else:
+            n_ids = 0
+            for i in range(K):
+                n_ids += step(args.warmup + r * K + i)
+        ids_rep.append(n_ids)
+        evs[r + 1].record(cur)
+    torch.cuda.synchronize()
+    wall_s = time.perf_counter() - t0
+    rep_ms = np.array([evs[r].elapsed_time(evs[r + 1]) for r in range(reps)])
+    med = int(np.argsort(rep_ms)[len(rep_ms) // 2])
+    ms_per_step = float(rep_ms[med]) / K
+    ids_per_s = ids_rep[med] / (float(rep_ms[med]) * 1e-3)
     cache_report = None
     if cache_rows is not None and any(cache_rows):
         cache_report = []
+        calls = args.warmup + K * (reps + 1)
         for t, c in enumerate(cache_rows):
             if c:
                 st = ctx.emb_cache_stats(t)
                 row_bytes = cfg.tables[t].dim * e_of[t] + 4
                 cache_report.append({"table": t, "cache_rows": c, "rows": cfg.tables[t].rows, **st,
                                      "hit_rate": round(1.0 - st["misses"] / max(st["requested"], 1), 4),
-                                     "host_link_bytes_per_step": round((st["misses"] + st["written_back"]) * row_bytes /
-                                                                       (args.warmup + args.steps))})
+                                     "host_link_bytes_per_step": round((st["misses"] + st["written_back"]) * row_bytes / calls)})
 
-    # per-kernel timing pass (HIP events on the launch stream, inside the library)
+    # ---- per-kernel timing pass: the same steps once more with every kernel stage bracketed by HIP events on the
+    # launch stream inside the library (the events themselves cost a little, so the stages add up to slightly more
+    # than a step of the region above)
     ctx.emb_set_profiling(True)
     ctx.emb_reset_stage_ms()
     N_t, U_t, Um_t = np.zeros(T), np.zeros(T), np.zeros(T)
     tile = int(binding.load_library().emb_tile_entries())   # segments crossing a tile edge are finished by the fix-up
     N_sum = 0
-    for i in range(args.steps):
+    prof_steps = max(K, nb)
+    for i in range(prof_steps):
         N_sum += step(args.warmup + i)
         keys, seg_off, _ = ctx.emb_read_dedup()
-        s, en = seg_off[:-1].astype(np.int64), seg_off[1:].astype(np.int64)
+        s_, en = seg_off[:-1].astype(np.int64), seg_off[1:].astype(np.int64)
         kt = (keys >> np.uint64(32)).astype(np.int64)
         U_t += np.bincount(kt, minlength=T)
-        Um_t += np.bincount(kt[s // tile != (en - 1) // tile], minlength=T)
-        N_t += np.bincount(kt, weights=(en - s), minlength=T)
+        Um_t += np.bincount(kt[s_ // tile != (en - 1) // tile], minlength=T)
+        N_t += np.bincount(kt, weights=(en - s_), minlength=T)
     stages = ctx.emb_read_stage_ms()
     ctx.emb_set_profiling(False)
-    N_avg, U_avg = N_sum / args.steps, float(U_t.sum()) / args.steps
-    ab = algorithmic_bytes([{"N": N_t[t] / args.steps, "bags": w.batch * int((slot_table == t).sum()),
-                             "U": U_t[t] / args.steps, "Um": Um_t[t] / args.steps, "D": cfg.tables[t].dim,
-                             "e": e_of[t]} for t in range(T)])
-    per_step_ms = {k: ms / args.steps for k, (ms, c) in stages.items() if c}
-    launches = {k: c / args.steps for k, (ms, c) in stages.items() if c}
-    dom = max((k for k in per_step_ms if k in ab), key=lambda k: per_step_ms[k])
+    N_avg, U_avg = N_sum / prof_steps, float(U_t.sum()) / prof_steps
+    occ, comp = algorithmic_bytes([{"N": N_t[t] / prof_steps, "bags": w.batch * int((slot_table == t).sum()),
+                                    "U": U_t[t] / prof_steps, "Um": Um_t[t] / prof_steps, "D": cfg.tables[t].dim,
+                                    "e": e_of[t]} for t in range(T)])
+    per_step_ms = {k: ms / prof_steps for k, (ms, c) in stages.items() if c}
+    launches = {k: c / prof_steps for k, (ms, c) in stages.items() if c}
+    dom = max((k for k in per_step_ms if k in occ), key=lambda k: per_step_ms[k])
+
+    def gbps(nbytes, ms):
+        return nbytes / (ms * 1e-3) / 1e9
+
     # launches of a stage that run once per table are taken together: bytes of all / time of all
-    achieved = ab[dom] / (per_step_ms[dom] * 1e-3) / 1e9
+    achieved = gbps(occ[dom], per_step_ms[dom])
+    achieved_c = gbps(comp[dom], per_step_ms[dom])
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                 "avg_launch_ms": round(per_step_ms[dom] / launches[dom], 4),
-                "algorithmic_bytes_per_launch": int(ab[dom] / launches[dom])}
-    # bytes per launch between L2 and the fabric, from the committed rocprofv3 --pmc summary (FETCH_SIZE and
-    # WRITE_SIZE runs of this same script, scaled by a plain copy kernel); null if no summary covers the workload
-    traffic_file = os.path.join(ROOT, "profiles", f"{w.name}_hbm_traffic.txt")
-    measured_step_bytes = None
-    if os.path.exists(traffic_file):
-        per_launch = ("gather_pool", "build_keys", "reduce_update")   # the other stages are listed per step
-        measured_step_bytes = 0
-        for line in open(traffic_file):
-            f = line.split()
-            if len(f) == 3 and f[0] == "traffic":
-                if f[1] == dom:
-                    roofline["traffic"] = int(f[2])
-                measured_step_bytes += int(f[2]) * (launches.get(f[1], 1) if f[1] in per_launch else 1)
+                "algorithmic_bytes_per_launch": int(occ[dom] / launches[dom]),
+                "bytes_model": "occurrence: every id occurrence reads its table row / its bag's gradient row; repeats that "
+                               "caches serve are counted, so this is delivered (effective) bandwidth and may exceed HBM's",
+                "achieved_compulsory": round(achieved_c, 1), "frac_compulsory": round(achieved_c / HBM_PEAK_GBS, 4),
+                "compulsory_bytes_per_launch": int(comp[dom] / launches[dom]),
+                "compulsory_model": "every distinct byte once (unique rows, each gradient row once): a lower bound of "
+                                    "the HBM traffic and of the HBM fraction"}
+    # bytes between L2 and the fabric from the committed rocprofv3 --pmc summary of this workload (FETCH_SIZE and
+    # WRITE_SIZE runs of this script, scaled by a plain copy of known size).  They are that earlier run's bytes, not
+    # this run's: used only if the summary was taken on the same ids / unique rows per step, else null.
+    prof = read_traffic_profile(os.path.join(ROOT, "profiles", f"{w.name}_hbm_traffic.txt"))
+    profile_step_bytes = None
+    if prof is not None and not args.overlap and cache_report is None:
+        traffic, meta = prof
+        same = (abs(meta.get("ids_per_step", -1) - N_avg) <= 0.01 * N_avg and
+                abs(meta.get("unique_rows_per_step", -1) - U_avg) <= 0.01 * U_avg)
+        if same:
+            per_launch = ("gather_pool", "build_keys", "reduce_update")   # the other stages are listed per step
+            roofline["traffic"] = traffic.get(dom)
+            profile_step_bytes = sum(v * (launches.get(k, 1) if k in per_launch else 1) for k, v in traffic.items())
 
     out = {
         "metric": "embedding IDs/sec (lookup+bwd+update), 1 GPU", "value": round(ids_per_s, 1), "unit": "IDs/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if all(x == 4 for x in e_of) else "bf16",
+        "dtype": "f64 sums and optimizer; " + ("f32" if all(x == 4 for x in e_of) else "bf16") + " table storage",
         "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "slots": cfg.num_slots,
                    "rows": [t.rows for t in cfg.tables], "dim": [t.dim for t in cfg.tables],
                    "ids_per_step": round(N_avg), "unique_rows_per_step": round(U_avg),
                    "distinct_batches": nb, "optimizer": "rowwise_adagrad" if cfg.opt else "sgd",
                    "schedule": "staleness-1 overlap, two streams" if args.overlap else "synchronous, one stream"},
-        "effective_GBps_step": round(ab["step"] / (ms_per_step * 1e-3) / 1e9, 1),
-        "effective_frac_of_hbm_peak": round(ab["step"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-        # counter-measured bytes of a whole step (all stages of the committed FETCH_SIZE / WRITE_SIZE summary) over
-        # this run's step time; the counters sit between L2 and the fabric (memory-side cache hits included)
-        "measured_GBps_step": (round(measured_step_bytes / (ms_per_step * 1e-3) / 1e9, 1)
-                               if measured_step_bytes and not args.overlap and cache_report is None else None),
-        "measured_frac_of_hbm_peak": (round(measured_step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
-                                      if measured_step_bytes and not args.overlap and cache_report is None else None),
+        "timing": {"protocol": f"median of {reps} back-to-back repetitions of {K} steps each (HIP events on the launch "
+                               f"stream), after {args.warmup} warm-up steps and one untimed repetition",
+                   "repetitions": reps, "timed_region_s": round(float(rep_ms.sum()) * 1e-3, 3), "wall_s": round(wall_s, 3),
+                   "rep_ms_min": round(float(rep_ms.min()), 4), "rep_ms_median": round(float(rep_ms[med]), 4),
+                   "rep_ms_max": round(float(rep_ms.max()), 4),
+                   "ms_per_step_mean": round(float(rep_ms.sum()) / (reps * K), 4)},
+        "effective_GBps_step": round(gbps(occ["step"], ms_per_step), 1),
+        "effective_frac_of_hbm_peak": round(gbps(occ["step"], ms_per_step) / HBM_PEAK_GBS, 4),
+        "compulsory_GBps_step": round(gbps(comp["step"], ms_per_step), 1),
+        "compulsory_frac_of_hbm_peak": round(gbps(comp["step"], ms_per_step) / HBM_PEAK_GBS, 4),
+        # the committed profile's L2<->fabric bytes of a whole step over this run's step time (null unless the profile
+        # was taken on the same workload); memory-side cache hits are inside these bytes, DRAM bytes are not measured
+        "profile_fabric_GBps_step": round(gbps(profile_step_bytes, ms_per_step), 1) if profile_step_bytes else None,
+        "profile_fabric_frac_of_hbm_peak": (round(gbps(profile_step_bytes, ms_per_step) / HBM_PEAK_GBS, 4)
+                                            if profile_step_bytes else None),
         "stage_ms_per_step": {k: round(v, 4) for k, v in per_step_ms.items()},
-        "stage_GBps": {k: round(ab[k] / (per_step_ms[k] * 1e-3) / 1e9, 1) for k in per_step_ms if k in ab},
+        "stage_GBps_occurrence": {k: round(gbps(occ[k], per_step_ms[k]), 1) for k in per_step_ms if k in occ},
+        "stage_GBps_compulsory": {k: round(gbps(comp[k], per_step_ms[k]), 1) for k in per_step_ms if k in comp},
         "setup_s": round(setup_s, 1),
         "roofline": roofline,
     }
@@ -473,15 +583,22 @@ def main() -> int:
         off = hb.offsets[: bs * S + 1]
         ids = hb.ids[: int(off[-1])]
         dp = grads[0][:bs].cpu().numpy()
-        orc = O.Oracle.from_config(cfg, dense=False)
+        table_gb = sum(t.rows * (t.dim + 1) * 4 for t in cfg.tables) / 1e9       # the oracle stores fp32
+        # whole (dense) tables when the host has the memory and their initialisation stays short; else the oracle's
+        # touched-rows-only mode, whose hash map costs time on every row access
+        dense = table_gb * 2.5 < host_mem_available_gb() and table_gb <= args.cpu_dense_gb
+        t0 = time.perf_counter()
+        orc = O.Oracle.from_config(cfg, dense=dense)
+        init_s = time.perf_counter() - t0
         t0 = time.perf_counter()
         orc.lookup_pool(ids, off)
         orc.backward_update(ids, off, dp)
         cpu_s = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": round(len(ids) / cpu_s, 1), "unit": "IDs/s", "cores": 1, "kind": "oracle",
+                               "cpu": cpu_model(), "tables": "dense" if dense else "sparse (touched rows in a hash map)",
                                "sample": f"{bs} of {hb.batch_size} samples of batch 0 ({len(ids)} IDs), one "
-                                         f"lookup+bwd+update step, sparse-table oracle, {cpu_s:.1f} s, "
-                                         f"{os.cpu_count()} cores visible"}
+                                         f"lookup+bwd+update step, {cpu_s:.1f} s on 1 of {os.cpu_count()} visible cores"
+                                         + (f" (+{init_s:.0f} s to initialise the {table_gb:.0f} GB tables, not counted)" if dense else "")}
         orc.close()
     ctx.close()
     print(json.dumps(out))
