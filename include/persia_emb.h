@@ -29,14 +29,23 @@
  *   - A batch is CSR over bags: bag index = b * num_slots + s for sample b and slot s;
  *     ids[offsets[bag] .. offsets[bag+1]) are the bag's 64-bit IDs.  offsets must be
  *     non-decreasing with offsets[0] = 0 and offsets[B*S] = num_ids; this is a caller
- *     contract and is not validated on the hot path.
+ *     contract, checked on the device only (see below), never on the host.
  *   - Pooled activations and their gradient are fp32, row-major [B, W] with
  *     W = sum over slots of the slot's table dim; slot s occupies columns
  *     [col(s), col(s) + dim) where col(s) is the sum of the dims of slots before it.
  *   - A context is not thread-safe; calls on one context must be issued from one thread
- *     (or externally serialised).  Two hot calls on different streams may overlap on the
- *     device only if the caller orders them as it needs (bounded-staleness training,
- *     section 5: a lookup may read rows an earlier update is still writing).
+ *     (or externally serialised).  An emb_lookup_pool and an emb_backward_update on
+ *     different streams may overlap on the device if the caller orders them as it needs
+ *     (bounded-staleness training, section 5: a lookup may read rows an earlier update is
+ *     still writing).  Two emb_backward_update calls (or emb_lookup_pool_indexed, which
+ *     uses the same buffers) must not overlap: the context has one workspace, and inside
+ *     a call the id sort and the tile-order sort share its histogram buffers, which is
+ *     safe only because a call's kernels run in order on one stream.  On a context with
+ *     cached tables (emb_create_cached) every hot call uses that workspace; the library
+ *     therefore makes a hot call that arrives on another stream wait for the previous one.
+ *   - offsets that do not tile [0, num_ids) are the caller's error, but not a fault: ids
+ *     are never read outside [0, num_ids), and emb_backward_update then leaves every row
+ *     untouched (emb_dedup_sizes / emb_read_dedup report EMB_EINVAL for that batch).
  */
 #ifndef PERSIA_EMB_H
 #define PERSIA_EMB_H

@@ -100,6 +100,8 @@ struct TileArgs {
   float* accs;
   uint32_t key_base;
   float lr, eps;
+  const uint32_t* bad_flag;  // see BackwardArgs
+  uint32_t call;
 };
 
 // n / S for any 32-bit n, with the constants the host prepared for S (round-up method of Granlund and
@@ -124,6 +126,7 @@ __global__ __launch_bounds__(kBlock) void k_tile_reduce_update(TileArgs a) {
   constexpr int GPB = kBlock / LG;   // tiles per workgroup
   constexpr int SC = 4;              // entries fetched together: SC gradient rows + the table rows of the runs they start
   static_assert(kTile % SC == 0, "sub-chunk geometry");
+  if (*a.bad_flag == a.call) return;  // inconsistent offsets: keys and bags cannot be trusted as addresses (uniform exit)
   __shared__ uint32_t s_key[GPB][kTile];
   __shared__ uint32_t s_bag[GPB][kTile];
   const int grp = threadIdx.x / LG, lane = threadIdx.x % LG;
@@ -229,6 +232,8 @@ struct FixupArgs {
   uint32_t key_base;
   uint64_t rows;
   float lr, eps;
+  const uint32_t* bad_flag;
+  uint32_t call;
 };
 
 // Segments that span at most kShortSpan tiles: one lane-group per listed segment (grid-stride), the
@@ -240,6 +245,7 @@ __global__ __launch_bounds__(kBlock) void k_fixup_short(FixupArgs a) {
   constexpr int LG = D / 4;
   constexpr int GPB = kBlock / LG;
   const int lane = threadIdx.x % LG;
+  if (*a.bad_flag == a.call) return;
   const uint32_t count = a.counters[1];
   T* w = reinterpret_cast<T*>(a.w);
   for (uint32_t e = blockIdx.x * GPB + threadIdx.x / LG; e < count; e += gridDim.x * GPB) {
@@ -307,6 +313,7 @@ __global__ __launch_bounds__(kBlock) void k_fixup_long(FixupArgs a) {
   constexpr int NG = kBlock / LG;
   __shared__ double s_part[NG][D];
   const int g = threadIdx.x / LG, lane = threadIdx.x % LG;
+  if (*a.bad_flag == a.call) return;
   const uint32_t count = a.counters[2];
   T* w = reinterpret_cast<T*>(a.w);
   for (uint32_t e = blockIdx.x; e < count; e += gridDim.x) {  // every branch below is uniform over the workgroup
@@ -490,6 +497,9 @@ hipError_t launch_tile_reduce_update(const TableView& t, const BackwardArgs& b, 
   a.key_base = t.key_base;
   a.lr = b.lr;
   a.eps = b.eps;
+  a.bad_flag = b.bad_flag;
+  a.call = b.call;
+  if (!a.bad_flag) return hipErrorInvalidValue;
   if (t.dtype == 1) {
     PEMB_DIM_SWITCH(bf16_t, t.dim, launch_tile_td, a, b.opt, stream)
   } else {
@@ -522,6 +532,9 @@ hipError_t launch_fixup(const TableView& t, const BackwardArgs& b, hipStream_t s
   a.rows = t.rows;
   a.lr = b.lr;
   a.eps = b.eps;
+  a.bad_flag = b.bad_flag;
+  a.call = b.call;
+  if (!a.bad_flag) return hipErrorInvalidValue;
   const uint32_t tiles = (b.n + kTile - 1) / kTile;
   if (t.dtype == 1) {
     PEMB_DIM_SWITCH(bf16_t, t.dim, launch_fixup_td, a, b.opt, tiles, stream)

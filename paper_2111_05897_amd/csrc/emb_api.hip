@@ -2,6 +2,7 @@
 // workspace, and the sequence of kernel launches of each hot call.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -38,6 +39,16 @@ struct EventRec {
 };
 
 thread_local std::string g_create_error;
+
+// Number of the dedup in progress, unique over all contexts of the process (the static workspace is shared): the
+// key builder stores it in counters[kBadFlag] when a batch's offsets are inconsistent.  Never 0 (fresh memory).
+std::atomic<uint32_t> g_call_seq{0};
+constexpr int kBadFlag = 4;
+uint32_t next_call() {
+  uint32_t c = ++g_call_seq;
+  if (c == 0) c = ++g_call_seq;
+  return c;
+}
 
 // Scratch memory of one emb_backward_update (and of the dedup a cached context runs in its lookups): either the
 // buffers a context allocated in emb_create for its max_ids, or the carved-up static array below.
@@ -88,11 +99,20 @@ struct emb_ctx {
   uint32_t* unique_slots = nullptr;   // unique keys with rows replaced by cache slots
   uint32_t lru_step = 0;              // one step per admission (every lookup and every update is a use)
   bool any_cached = false;
+  // calls on a context with cached tables share the cache's admission state: a hot call that arrives on another
+  // stream than the one before it first waits for that call (cache_done is recorded at the end of every hot call)
+  hipEvent_t cache_done = nullptr;
+  hipStream_t cache_stream = nullptr;
+  bool cache_busy = false;
   std::vector<void*> host_allocs;
   // last backward
   int sorted_buf = 0;
   uint64_t last_n = 0;
+  uint32_t last_call = 0;            // number of the last dedup (see g_call_seq)
   bool have_dedup = false;
+  // staging of emb_read_rows / emb_write_rows (allocated at the first use, kept)
+  uint64_t* io_rows = nullptr;
+  float *io_w = nullptr, *io_acc = nullptr;
   // bookkeeping
   std::vector<void*> allocs;
   uint64_t device_bytes = 0;
@@ -164,6 +184,8 @@ void free_all(emb_ctx* ctx) {
   ctx->recs.clear();
   for (auto& e : ctx->free_events) (void)hipEventDestroy(e);
   ctx->free_events.clear();
+  if (ctx->cache_done) (void)hipEventDestroy(ctx->cache_done);
+  ctx->cache_done = nullptr;
 }
 
 // Brackets one kernel stage with events when profiling is on.
@@ -440,6 +462,10 @@ static int emb_create_impl(const emb_config* cfg, const uint64_t* cache_rows, em
     CK(dev_alloc(ctx, &ctx->ws.keys[i], cap), "hipMalloc(sort keys)");
     CK(dev_alloc(ctx, &ctx->ws.bags[i], cap), "hipMalloc(sort payload)");
   }
+  for (int i = 0; i < 2; ++i) {  // entries a malformed batch leaves unwritten are then still keys and bags of the context
+    CK(hipMemset(ctx->ws.keys[i], 0, cap * sizeof(uint32_t)), "hipMemset(sort keys)");
+    CK(hipMemset(ctx->ws.bags[i], 0, cap * sizeof(uint32_t)), "hipMemset(sort payload)");
+  }
   CK(dev_alloc(ctx, &ctx->ws.hist, ((uint64_t)1 << kSortMaxBits) * kSortMaxBlocks), "hipMalloc(histograms)");
   CK(dev_alloc(ctx, &ctx->ws.total, (uint64_t)1 << kSortMaxBits), "hipMalloc(digit totals)");
   CK(dev_alloc(ctx, &ctx->ws.blk_heads, (cap + kUniqueTile - 1) / kUniqueTile + 1), "hipMalloc(block heads)");
@@ -449,6 +475,7 @@ static int emb_create_impl(const emb_config* cfg, const uint64_t* cache_rows, em
   CK(dev_alloc(ctx, &ctx->ws.multi_list, ntiles), "hipMalloc(multi-tile list)");
   CK(dev_alloc(ctx, &ctx->ws.long_list, ntiles), "hipMalloc(long segment list)");
   CK(dev_alloc(ctx, &ctx->ws.counters, 8), "hipMalloc(counters)");
+  CK(hipMemset(ctx->ws.counters, 0, 8 * sizeof(uint32_t)), "hipMemset(counters)");
   CK(dev_alloc(ctx, &ctx->ws.ranges, cfg->num_tables + 1), "hipMalloc(table ranges)");
   CK(dev_alloc(ctx, &ctx->ws.partials, 2 * ntiles * ctx->pstride), "hipMalloc(partials)");
   for (int i = 0; i < 2; ++i) {
@@ -457,6 +484,7 @@ static int emb_create_impl(const emb_config* cfg, const uint64_t* cache_rows, em
   }
 
   if (ctx->any_cached) {
+    CK(hipEventCreateWithFlags(&ctx->cache_done, hipEventDisableTiming), "hipEventCreate(cache order)");
     uint64_t max_c = 0;
     for (const LruView& v : ctx->lru) max_c = v.C > max_c ? v.C : max_c;
     const uint64_t big = max_c > cap ? max_c : cap;
@@ -498,6 +526,7 @@ static int run_dedup(emb_ctx* ctx, const Workspace& ws, const emb_batch* batch, 
   ctx->last_n = n;
   ctx->have_dedup = true;
   ctx->last_ws = ws;
+  ctx->last_call = next_call();
   ctx->sorted_buf = 0;
   if (n == 0) {  // leave an empty index form behind
     CKH(launch_unique(ws.keys[0], 0, ws.blk_heads, ws.blk_multi, ws.unique_keys, ws.seg_off,
@@ -507,8 +536,8 @@ static int run_dedup(emb_ctx* ctx, const Workspace& ws, const emb_batch* batch, 
   }
   {
     StageTimer tm(ctx, ST_BUILD_KEYS, stream);
-    CKH(launch_build_keys(ctx->slots, batch->ids, batch->offsets, batch->batch_size, ctx->S, ctx->mix, 0,
-                          ws.keys[0], ws.bags[0], stream),
+    CKH(launch_build_keys(ctx->slots, batch->ids, batch->offsets, n, batch->batch_size, ctx->S, ctx->mix, 0,
+                          ws.keys[0], ws.bags[0], ws.counters + kBadFlag, ctx->last_call, stream),
         "build_keys");
   }
   const SortPlan plan = make_sort_plan(n, ctx->key_bits, ctx->sort_max_bits);
@@ -555,6 +584,20 @@ static int admit_batch(emb_ctx* ctx, hipStream_t stream) {
   return EMB_OK;
 }
 
+// Order of the hot calls on a context whose tables sit behind the cache (see emb_ctx::cache_done).
+static int cache_enter(emb_ctx* ctx, hipStream_t stream) {
+  if (ctx->any_cached && ctx->cache_busy && stream != ctx->cache_stream)
+    CKH(hipStreamWaitEvent(stream, ctx->cache_done, 0), "hipStreamWaitEvent(cache order)");
+  return EMB_OK;
+}
+static int cache_leave(emb_ctx* ctx, hipStream_t stream) {
+  if (!ctx->any_cached) return EMB_OK;
+  CKH(hipEventRecord(ctx->cache_done, stream), "hipEventRecord(cache order)");
+  ctx->cache_stream = stream;
+  ctx->cache_busy = true;
+  return EMB_OK;
+}
+
 static int emb_lookup_pool_impl(emb_ctx* ctx, const emb_batch* batch, float* pooled, void* hip_stream) {
   int rc = check_batch(ctx, batch);
   if (rc) return rc;
@@ -562,6 +605,7 @@ static int emb_lookup_pool_impl(emb_ctx* ctx, const emb_batch* batch, float* poo
   if (!pooled) return fail(ctx, EMB_EINVAL, "null pooled output");
   hipStream_t stream = (hipStream_t)hip_stream;
   CKH(hipSetDevice(ctx->device), "hipSetDevice");
+  if ((rc = cache_enter(ctx, stream)) != EMB_OK) return rc;
   if (ctx->any_cached) {  // the rows must be in the cache before they are gathered
     if (!workspace_complete(ctx, ctx->ws)) return fail(ctx, EMB_ESTATE, "workspace is incomplete (a buffer is null)");
     if ((rc = run_dedup(ctx, ctx->ws, batch, stream)) != EMB_OK) return rc;
@@ -569,11 +613,11 @@ static int emb_lookup_pool_impl(emb_ctx* ctx, const emb_batch* batch, float* poo
   }
   for (const TableView& tv : ctx->tables) {
     StageTimer tm(ctx, ST_GATHER_POOL, stream);
-    CKH(launch_gather_pool(tv, ctx->slots, batch->ids, batch->offsets, batch->batch_size, ctx->S, ctx->width,
+    CKH(launch_gather_pool(tv, ctx->slots, batch->ids, batch->offsets, (uint32_t)batch->num_ids, batch->batch_size, ctx->S, ctx->width,
                            ctx->mix, ctx->zero_row, pooled, stream),
         "gather_pool");
   }
-  return EMB_OK;
+  return cache_leave(ctx, stream);
 }
 
 static int emb_lookup_pool_indexed_impl(emb_ctx* ctx, uint32_t batch_size, uint64_t num_unique, uint64_t num_ids,
@@ -629,7 +673,7 @@ static int emb_lookup_pool_indexed_impl(emb_ctx* ctx, uint32_t batch_size, uint6
   for (size_t t = 0; t < ctx->tables.size(); ++t) {
     StageTimer tm(ctx, ST_GATHER_POOL, stream);
     IndexedBags ix{ctx->bag_beg, ctx->bag_end, ws.bags[src], keys, (uint32_t)num_unique, (uint32_t)t};
-    CKH(launch_gather_pool(ctx->tables[t], ctx->slots, nullptr, nullptr, batch_size, ctx->S, ctx->width, ctx->mix,
+    CKH(launch_gather_pool(ctx->tables[t], ctx->slots, nullptr, nullptr, n, batch_size, ctx->S, ctx->width, ctx->mix,
                            ctx->zero_row, pooled, stream, &ix),
         "gather_pool(indexed)");
   }
@@ -643,8 +687,8 @@ static int emb_hash_rows_impl(emb_ctx* ctx, const emb_batch* batch, uint32_t* ro
   if (!rows_out) return fail(ctx, EMB_EINVAL, "null rows output");
   hipStream_t stream = (hipStream_t)hip_stream;
   CKH(hipSetDevice(ctx->device), "hipSetDevice");
-  CKH(launch_build_keys(ctx->slots, batch->ids, batch->offsets, batch->batch_size, ctx->S, ctx->mix, 1, rows_out,
-                        nullptr, stream),
+  CKH(launch_build_keys(ctx->slots, batch->ids, batch->offsets, (uint32_t)batch->num_ids, batch->batch_size, ctx->S,
+                        ctx->mix, 1, rows_out, nullptr, nullptr, 0, stream),
       "hash_rows");
   return EMB_OK;
 }
@@ -658,8 +702,9 @@ static int backward_update_with(emb_ctx* ctx, const Workspace& ws, const emb_bat
   hipStream_t stream = (hipStream_t)hip_stream;
   CKH(hipSetDevice(ctx->device), "hipSetDevice");
   const uint32_t n = (uint32_t)batch->num_ids;
+  if ((rc = cache_enter(ctx, stream)) != EMB_OK) return rc;
   if ((rc = run_dedup(ctx, ws, batch, stream)) != EMB_OK) return rc;
-  if (n == 0) return EMB_OK;  // nothing to update
+  if (n == 0) return cache_leave(ctx, stream);  // nothing to update
   const int src = ctx->sorted_buf;
   const bool multi_table = ctx->tables.size() > 1;
   if (multi_table)  // each table's stretch of the sorted list (found before any key is rewritten below)
@@ -704,6 +749,8 @@ static int backward_update_with(emb_ctx* ctx, const Workspace& ws, const emb_bat
   a.counters = ws.counters;
   a.multi_list = ws.multi_list;
   a.long_list = ws.long_list;
+  a.bad_flag = ws.counters + kBadFlag;
+  a.call = ctx->last_call;
   {
     StageTimer tm(ctx, ST_TILE_ORDER, stream);
     // shift that leaves 8 bits of the bag index (the tile keys use 7: 128 buckets of consecutive bags, sample-major)
@@ -726,7 +773,7 @@ static int backward_update_with(emb_ctx* ctx, const Workspace& ws, const emb_bat
     StageTimer tm(ctx, ST_FIXUP, stream);
     CKH(launch_fixup(ctx->tables[t], a, stream), "fixup");
   }
-  return EMB_OK;
+  return cache_leave(ctx, stream);
 }
 
 static int emb_backward_update_impl(emb_ctx* ctx, const emb_batch* batch, const float* d_pooled, void* hip_stream) {
@@ -795,8 +842,11 @@ static int emb_dedup_sizes_impl(emb_ctx* ctx, uint64_t* num_unique, uint64_t* nu
   if (!ctx->have_dedup) return fail(ctx, EMB_ESTATE, "no emb_backward_update has run on this context");
   CKH(hipSetDevice(ctx->device), "hipSetDevice");
   CKH(hipDeviceSynchronize(), "hipDeviceSynchronize");
-  uint32_t c[2] = {0, 0};
+  uint32_t c[kBadFlag + 1] = {0};
   CKH(hipMemcpy(c, ctx->last_ws.counters, sizeof(c), hipMemcpyDeviceToHost), "hipMemcpy(counters)");
+  if (c[kBadFlag] == ctx->last_call)
+    return fail(ctx, EMB_EINVAL, "the last batch's offsets do not tile [0, num_ids) (non-decreasing, offsets[0] = 0, "
+                                 "offsets[B * S] = num_ids): its update was skipped");
   if (num_unique) *num_unique = c[0];
   if (num_ids) *num_ids = ctx->last_n;
   return EMB_OK;
@@ -833,13 +883,19 @@ static int rows_io(emb_ctx* ctx, uint32_t table, const uint64_t* rows, uint64_t 
   for (uint64_t i = 0; i < n; ++i)
     if (rows[i] >= tv.rows) return fail(ctx, EMB_EINVAL, "row index out of range");
   CKH(hipSetDevice(ctx->device), "hipSetDevice");
-  const uint64_t chunk = 1u << 20;
-  uint64_t* d_rows = nullptr;
-  float *d_w = nullptr, *d_a = nullptr;
-  const uint64_t m = n < chunk ? n : chunk;
-  hipError_t e = hipMalloc((void**)&d_rows, m * sizeof(uint64_t));
-  if (e == hipSuccess) e = hipMalloc((void**)&d_w, m * tv.dim * sizeof(float));
-  if (e == hipSuccess) e = hipMalloc((void**)&d_a, m * sizeof(float));
+  const uint64_t chunk = 1u << 18;   // rows staged at a time (the staging buffers hold this many rows of the widest table)
+  hipError_t e = hipSuccess;
+  if (!ctx->io_rows) {
+    if ((e = dev_alloc(ctx, &ctx->io_rows, chunk)) == hipSuccess &&
+        (e = dev_alloc(ctx, &ctx->io_w, chunk * ctx->pstride)) == hipSuccess)
+      e = dev_alloc(ctx, &ctx->io_acc, chunk);
+    if (e != hipSuccess) {
+      ctx->io_rows = nullptr;  // whatever was allocated stays on the context's list and is freed with it
+      return fail_hip(ctx, "hipMalloc(row staging)", e);
+    }
+  }
+  uint64_t* d_rows = ctx->io_rows;
+  float *d_w = ctx->io_w, *d_a = ctx->io_acc;
   for (uint64_t i0 = 0; e == hipSuccess && i0 < n; i0 += chunk) {
     const uint64_t c = n - i0 < chunk ? n - i0 : chunk;
     e = hipMemcpy(d_rows, rows + i0, c * sizeof(uint64_t), hipMemcpyHostToDevice);
@@ -856,9 +912,6 @@ static int rows_io(emb_ctx* ctx, uint32_t table, const uint64_t* rows, uint64_t 
       if (e == hipSuccess && acc_out) e = hipMemcpy(acc_out + i0, d_a, c * sizeof(float), hipMemcpyDeviceToHost);
     }
   }
-  (void)hipFree(d_rows);
-  (void)hipFree(d_w);
-  (void)hipFree(d_a);
   if (e != hipSuccess) return fail_hip(ctx, write ? "emb_write_rows" : "emb_read_rows", e);
   return EMB_OK;
 }

@@ -23,6 +23,7 @@ struct GatherArgs {
   const uint32_t* slot_col;    // indexed by slot
   uint32_t n_slots_t, S, width;
   uint32_t n_local_bags;       // B * n_slots_t
+  uint32_t num_ids;            // offsets are clamped to [0, num_ids]: a malformed batch cannot read outside ids
   int mix;
   int stream_out;              // 1: the table serves every slot, so a launch writes whole rows of `pooled`
   float* pooled;
@@ -81,8 +82,10 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(sizeof(T
   const uint32_t b = lb / a.n_slots_t;
   const uint32_t slot = a.slot_list[lb - b * a.n_slots_t];
   const size_t bag = (size_t)b * a.S + slot;
-  const int beg = INDEXED ? (int)a.bag_beg[bag] : a.offsets[bag];
-  const int end = INDEXED ? (int)a.bag_end[bag] : a.offsets[bag + 1];
+  int beg = INDEXED ? (int)a.bag_beg[bag] : a.offsets[bag];
+  int end = INDEXED ? (int)a.bag_end[bag] : a.offsets[bag + 1];
+  beg = beg < 0 ? 0 : beg;
+  end = end > (int)a.num_ids ? (int)a.num_ids : end;  // beg >= end: an empty bag
   const uint64_t salt = a.slot_salt[slot];
   const T* __restrict__ base = reinterpret_cast<const T*>(a.w) + lane * VEC;
   const T* __restrict__ zero_row = reinterpret_cast<const T*>(a.zeros) + lane * VEC;
@@ -153,16 +156,27 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(sizeof(T
 }
 
 // 8 lanes per bag; lane j takes ids beg+j, beg+j+8, ...
+// Every bag also checks its stretch of the offsets: 0 <= beg <= end <= n, the first bag starts at 0 and the last ends
+// at n -- together: the bags tile [0, n) exactly, so every key and bag slot below n is written.  A violation is
+// recorded as bad_flag[0] = call (the number of this call) and the bag writes nothing outside [0, n); the kernels that
+// turn keys into addresses look at the flag first.
 __global__ __launch_bounds__(kBlock) void k_build_keys(SlotArrays sl, const uint64_t* __restrict__ ids,
                                                        const int32_t* __restrict__ offsets, uint32_t n_bags,
-                                                       uint32_t S, int mix, int bare_rows,
+                                                       uint32_t S, int mix, int bare_rows, uint32_t n,
                                                        uint32_t* __restrict__ keys_out,
-                                                       uint32_t* __restrict__ bags_out) {
+                                                       uint32_t* __restrict__ bags_out, uint32_t* __restrict__ bad_flag,
+                                                       uint32_t call) {
   const uint32_t bag = blockIdx.x * (kBlock / 8) + threadIdx.x / 8;
   const int lane = threadIdx.x % 8;
   if (bag >= n_bags) return;
   const uint32_t slot = bag % S;
-  const int beg = offsets[bag], end = offsets[bag + 1];
+  int beg = offsets[bag], end = offsets[bag + 1];
+  const bool bad = beg < 0 || end < beg || (uint32_t)end > n || (bag == 0 && beg != 0) || (bag == n_bags - 1 && (uint32_t)end != n);
+  if (bad) {
+    if (bad_flag && lane == 0) *bad_flag = call;  // every writer stores the same value
+    beg = beg < 0 ? 0 : beg;
+    end = (uint32_t)end > n ? (int)n : end;
+  }
   const uint64_t salt = sl.salt[slot], rows = sl.rows[slot], mask = sl.mask[slot];
   const uint32_t kb = bare_rows ? 0u : sl.key_base[slot];
   for (int i = beg + lane; i < end; i += 8) {
@@ -305,8 +319,8 @@ hipError_t launch_bag_bounds(const uint32_t* sorted_bags, uint32_t N, uint32_t* 
 }
 
 hipError_t launch_gather_pool(const TableView& t, const SlotArrays& sl, const uint64_t* ids, const int32_t* offsets,
-                              uint32_t B, uint32_t S, uint32_t width, int mix, const void* zeros, float* pooled,
-                              hipStream_t stream, const IndexedBags* ix) {
+                              uint32_t num_ids, uint32_t B, uint32_t S, uint32_t width, int mix, const void* zeros,
+                              float* pooled, hipStream_t stream, const IndexedBags* ix) {
   if (B == 0 || t.n_slots == 0) return hipSuccess;
   if (!zeros) return hipErrorInvalidValue;
   GatherArgs a;
@@ -324,6 +338,7 @@ hipError_t launch_gather_pool(const TableView& t, const SlotArrays& sl, const ui
   a.S = S;
   a.width = width;
   a.n_local_bags = B * t.n_slots;
+  a.num_ids = num_ids;
   a.mix = mix;
   a.stream_out = t.n_slots == S ? 1 : 0;
   a.pooled = pooled;
@@ -337,14 +352,14 @@ hipError_t launch_gather_pool(const TableView& t, const SlotArrays& sl, const ui
   return t.dtype == 1 ? dispatch_dim<bf16_t>(t.dim, a, stream) : dispatch_dim<float>(t.dim, a, stream);
 }
 
-hipError_t launch_build_keys(const SlotArrays& sl, const uint64_t* ids, const int32_t* offsets, uint32_t B,
-                             uint32_t S, int mix, int bare_rows, uint32_t* keys_out, uint32_t* bags_out,
-                             hipStream_t stream) {
+hipError_t launch_build_keys(const SlotArrays& sl, const uint64_t* ids, const int32_t* offsets, uint32_t num_ids,
+                             uint32_t B, uint32_t S, int mix, int bare_rows, uint32_t* keys_out, uint32_t* bags_out,
+                             uint32_t* bad_flag, uint32_t call, hipStream_t stream) {
   const uint32_t n_bags = B * S;
   if (n_bags == 0) return hipSuccess;
   const uint32_t grid = (n_bags + kBlock / 8 - 1) / (kBlock / 8);
   hipLaunchKernelGGL(k_build_keys, dim3(grid), dim3(kBlock), 0, stream, sl, ids, offsets, n_bags, S, mix, bare_rows,
-                     keys_out, bags_out);
+                     num_ids, keys_out, bags_out, bad_flag, call);
   return hipGetLastError();
 }
 

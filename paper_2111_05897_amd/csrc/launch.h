@@ -98,8 +98,8 @@ struct IndexedBags {
   uint32_t num_unique, table;
 };
 hipError_t launch_gather_pool(const TableView& t, const SlotArrays& sl, const uint64_t* ids, const int32_t* offsets,
-                              uint32_t B, uint32_t S, uint32_t width, int mix, const void* zeros, float* pooled,
-                              hipStream_t stream, const IndexedBags* ix = nullptr);
+                              uint32_t num_ids, uint32_t B, uint32_t S, uint32_t width, int mix, const void* zeros,
+                              float* pooled, hipStream_t stream, const IndexedBags* ix = nullptr);
 // Pieces of the forward from the index form: (bag, u) pairs of every entry of the bag lists; first / last position
 // of every bag in the pairs once sorted by bag (bag_beg / bag_end zeroed beforehand).
 hipError_t launch_zero_f32(float* p, uint64_t n, hipStream_t stream);
@@ -108,10 +108,12 @@ hipError_t launch_expand_index(const uint32_t* seg_off, const uint32_t* seg_bags
                                uint32_t* key_out, uint32_t* val_out, hipStream_t stream);
 hipError_t launch_bag_bounds(const uint32_t* sorted_bags, uint32_t N, uint32_t* bag_beg, uint32_t* bag_end,
                              hipStream_t stream);
-// keys_out[i] = key_base(slot) + row (or the bare row when bare_rows != 0); bags_out may be null.
-hipError_t launch_build_keys(const SlotArrays& sl, const uint64_t* ids, const int32_t* offsets, uint32_t B,
-                             uint32_t S, int mix, int bare_rows, uint32_t* keys_out, uint32_t* bags_out,
-                             hipStream_t stream);
+// keys_out[i] = key_base(slot) + row (or the bare row when bare_rows != 0); bags_out may be null.  bad_flag
+// (optional, device): receives `call` if the offsets do not tile [0, num_ids) bag by bag; nothing is written outside
+// [0, num_ids) either way.
+hipError_t launch_build_keys(const SlotArrays& sl, const uint64_t* ids, const int32_t* offsets, uint32_t num_ids,
+                             uint32_t B, uint32_t S, int mix, int bare_rows, uint32_t* keys_out, uint32_t* bags_out,
+                             uint32_t* bad_flag, uint32_t call, hipStream_t stream);
 
 // ---- sort.hip ----
 struct SortPlan {
@@ -152,6 +154,8 @@ struct BackwardArgs {
   const uint32_t* unique_keys;
   const uint32_t* seg_off;
   const uint32_t* counters;  // [0] = U, [1] = number of multi-tile segments, [2] = of those, the long ones
+  const uint32_t* bad_flag;  // device word: equal to `call` if the batch's offsets were inconsistent -- then the kernels
+  uint32_t call;             // that turn keys and bags into addresses do nothing
   const uint32_t* multi_list;
   const uint32_t* long_list; // multi-tile segments spanning more than 16 tiles (filled by launch_classify_multi)
 };

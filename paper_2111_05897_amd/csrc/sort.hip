@@ -311,7 +311,8 @@ __global__ __launch_bounds__(kBlock) void k_unique_count(const uint32_t* __restr
 
 // Single block of 1024 threads: exclusive scans of blk_heads[nb] and blk_multi[nb] in place;
 // counters[0] = U, counters[1] = number of multi-tile runs, counters[2] = 0; seg_off[U] = n.
-// Thread t owns the entries [t*per, (t+1)*per): serial sums, one scan over the 1024 sums, serial write-back.
+// The arrays are walked in chunks of 4096 entries, four consecutive entries per thread (one 16-byte access, so a
+// wave reads whole cache lines); per chunk one block-wide scan of the threads' sums, carried into the next chunk.
 constexpr int kScanThreads = 1024;
 
 __global__ __launch_bounds__(kScanThreads) void k_unique_scan(uint32_t* __restrict__ blk_heads,
@@ -321,52 +322,76 @@ __global__ __launch_bounds__(kScanThreads) void k_unique_scan(uint32_t* __restri
   constexpr int NW = kScanThreads / kWave;
   __shared__ uint32_t s_h[NW], s_m[NW];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-  const uint32_t per = (nb + kScanThreads - 1) / kScanThreads;
-  const uint32_t b0 = threadIdx.x * per;
-  uint32_t sum_h = 0, sum_m = 0;
-  for (uint32_t j = 0; j < per; ++j)
-    if (b0 + j < nb) {
-      sum_h += blk_heads[b0 + j];
-      sum_m += blk_multi[b0 + j];
-    }
-  uint32_t inc_h = sum_h, inc_m = sum_m;  // inclusive scans inside the wave
+  uint32_t carry_h = 0, carry_m = 0;
+  for (uint32_t base = 0; base < nb; base += 4 * kScanThreads) {  // the loop bounds are the same for every thread
+    const uint32_t i0 = base + 4 * threadIdx.x;
+    uint32_t h[4] = {0, 0, 0, 0}, m[4] = {0, 0, 0, 0};
+    if (i0 + 4 <= nb) {
+      const uint4 a = *reinterpret_cast<const uint4*>(blk_heads + i0), c = *reinterpret_cast<const uint4*>(blk_multi + i0);
+      h[0] = a.x; h[1] = a.y; h[2] = a.z; h[3] = a.w;
+      m[0] = c.x; m[1] = c.y; m[2] = c.z; m[3] = c.w;
+    } else {
 #pragma unroll
-  for (int off = 1; off < kWave; off <<= 1) {
-    const uint32_t th = __shfl_up(inc_h, off), tm = __shfl_up(inc_m, off);
-    if (lane >= off) {
-      inc_h += th;
-      inc_m += tm;
+      for (int j = 0; j < 4; ++j)
+        if (i0 + j < nb) {
+          h[j] = blk_heads[i0 + j];
+          m[j] = blk_multi[i0 + j];
+        }
     }
-  }
-  if (lane == kWave - 1) {
-    s_h[wave] = inc_h;
-    s_m[wave] = inc_m;
-  }
-  __syncthreads();
-  uint32_t run_h = inc_h - sum_h, run_m = inc_m - sum_m, tot_h = 0, tot_m = 0;
+    const uint32_t sum_h = h[0] + h[1] + h[2] + h[3], sum_m = m[0] + m[1] + m[2] + m[3];
+    uint32_t inc_h = sum_h, inc_m = sum_m;  // inclusive scans inside the wave
 #pragma unroll
-  for (int w = 0; w < NW; ++w) {
-    const uint32_t xh = s_h[w], xm = s_m[w];
-    if (w < wave) {
-      run_h += xh;
-      run_m += xm;
+    for (int off = 1; off < kWave; off <<= 1) {
+      const uint32_t th = __shfl_up(inc_h, off), tm = __shfl_up(inc_m, off);
+      if (lane >= off) {
+        inc_h += th;
+        inc_m += tm;
+      }
     }
-    tot_h += xh;
-    tot_m += xm;
+    if (lane == kWave - 1) {
+      s_h[wave] = inc_h;
+      s_m[wave] = inc_m;
+    }
+    __syncthreads();
+    uint32_t run_h = carry_h + inc_h - sum_h, run_m = carry_m + inc_m - sum_m, tot_h = 0, tot_m = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const uint32_t xh = s_h[w], xm = s_m[w];
+      if (w < wave) {
+        run_h += xh;
+        run_m += xm;
+      }
+      tot_h += xh;
+      tot_m += xm;
+    }
+    __syncthreads();  // s_h / s_m are rewritten by the next chunk
+    carry_h += tot_h;
+    carry_m += tot_m;
+    uint32_t oh[4], om[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      oh[j] = run_h;
+      om[j] = run_m;
+      run_h += h[j];
+      run_m += m[j];
+    }
+    if (i0 + 4 <= nb) {
+      *reinterpret_cast<uint4*>(blk_heads + i0) = make_uint4(oh[0], oh[1], oh[2], oh[3]);
+      *reinterpret_cast<uint4*>(blk_multi + i0) = make_uint4(om[0], om[1], om[2], om[3]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (i0 + j < nb) {
+          blk_heads[i0 + j] = oh[j];
+          blk_multi[i0 + j] = om[j];
+        }
+    }
   }
-  for (uint32_t j = 0; j < per; ++j)
-    if (b0 + j < nb) {
-      const uint32_t vh = blk_heads[b0 + j], vm = blk_multi[b0 + j];
-      blk_heads[b0 + j] = run_h;
-      blk_multi[b0 + j] = run_m;
-      run_h += vh;
-      run_m += vm;
-    }
   if (threadIdx.x == 0) {
-    counters[0] = tot_h;
-    counters[1] = tot_m;
+    counters[0] = carry_h;
+    counters[1] = carry_m;
     counters[2] = 0;
-    seg_off[tot_h] = n;
+    seg_off[carry_h] = n;
   }
 }
 

@@ -222,3 +222,39 @@ def test_cached_table_is_transparent_at_full_size(B):
     np.testing.assert_array_equal(ga, wa)
     ctx.close()
     ref.close()
+
+
+def test_cached_context_orders_calls_that_arrive_on_different_streams(B):
+    """A context with cached tables has one admission state; the library makes a hot call that arrives on another
+    stream wait for the one before it, so a two-stream caller without events of its own gets what one stream gives."""
+    import torch
+    rows, S, bsz, steps, cache = 1 << 13, 4, 128, 6, 2048
+    a = _args([(rows, 64, 0)], [0] * S, 1)
+    max_ids = bsz * S * 4
+    one = B.EmbContext(max_batch=bsz, max_ids=max_ids, cache_rows=[cache], **a)
+    two = B.EmbContext(max_batch=bsz, max_ids=max_ids, cache_rows=[cache], **a)
+    s_a, s_b = torch.cuda.Stream(), torch.cuda.Stream()      # default priority, both
+    rng = np.random.default_rng(2)
+    batches = [W.random_batch(900 + t, bsz, S, 4, 3000) for t in range(steps)]
+    dbs = [B.DeviceBatch(b.batch_size, b.ids, b.offsets) for b in batches]
+    grads = [torch.from_numpy(rng.standard_normal((bsz, S * 64)).astype(np.float32)).cuda() for _ in range(steps)]
+    p_one = [torch.empty((bsz, S * 64), device="cuda") for _ in range(steps)]
+    p_two = [torch.empty((bsz, S * 64), device="cuda") for _ in range(steps)]
+    torch.cuda.synchronize()
+    for t in range(steps):
+        one.emb_lookup_pool(dbs[t], p_one[t])
+        one.emb_backward_update(dbs[t], grads[t])
+    for t in range(steps):                                    # lookups on one stream, updates on the other, no events
+        two.emb_lookup_pool(dbs[t], p_two[t], stream=s_a)
+        two.emb_backward_update(dbs[t], grads[t], stream=s_b)
+    torch.cuda.synchronize()
+    for t in range(steps):
+        assert torch.equal(p_one[t], p_two[t]), f"lookup {t}"
+    allrows = np.arange(rows, dtype=np.uint64)
+    w1, a1 = one.emb_read_rows(0, allrows)
+    w2, a2 = two.emb_read_rows(0, allrows)
+    np.testing.assert_array_equal(w1, w2)
+    np.testing.assert_array_equal(a1, a2)
+    assert one.emb_cache_stats(0) == two.emb_cache_stats(0)
+    one.close()
+    two.close()

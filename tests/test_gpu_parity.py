@@ -387,3 +387,52 @@ class TestConfig4FullSizeOverlapOnBf16Table:
         st.pop("ctx").close()
         st.pop("orc").close()
         st.clear()
+
+
+def test_inconsistent_offsets_are_an_error_not_a_fault(B):
+    """offsets that do not tile [0, num_ids) -- the caller's mistake -- must neither read nor write outside the batch:
+    the lookup treats what lies outside [0, num_ids) as absent, the update leaves every row untouched and the index
+    form reports EMB_EINVAL; the next well-formed call works as usual.  (The device buffers of this test are large
+    enough for the true batch, so the stated num_ids only ever understates them.)"""
+    import torch
+    cfg = _cfg([(4096, 64, W.F32)], [0, 0, 0], opt=W.OPT_ROWWISE_ADAGRAD, lr=0.05, init_seed=11)
+    good = W.random_batch(5, 64, 3, 9, 5000, allow_empty=False)
+    n = good.num_ids
+    ctx = B.EmbContext.from_config(cfg, max_batch=64, max_ids=n)
+    orc = O.Oracle.from_config(cfg, dense=True)
+    allrows = np.arange(4096, dtype=np.uint64)
+    w0, a0 = ctx.emb_read_rows(0, allrows)
+    dp = torch.from_numpy(np.random.default_rng(1).standard_normal((64, 3 * 64)).astype(np.float32)).cuda()
+
+    def device_batch(offsets, num_ids):
+        db = B.DeviceBatch(64, good.ids, good.offsets)          # buffers of the true batch
+        db.offsets = torch.from_numpy(np.ascontiguousarray(offsets, dtype=np.int32)).cuda()
+        db.c = B.emb_batch(64, 0, num_ids, db.ids.data_ptr(), db.offsets.data_ptr())
+        db.num_ids = num_ids
+        return db
+
+    swapped = good.offsets.copy()
+    swapped[[40, 41]] = swapped[[41, 40]]                       # a bag with beg > end, its neighbours overlap
+    negative = good.offsets.copy()
+    negative[7] = -3
+    cases = {"offsets end above num_ids": device_batch(good.offsets, n - 5),
+             "offsets end below num_ids": device_batch(np.minimum(good.offsets, n - 7), n),
+             "offsets not monotone": device_batch(swapped, n),
+             "a negative offset": device_batch(negative, n)}
+    for name, db in cases.items():
+        pooled = ctx.emb_lookup_pool(db)
+        torch.cuda.synchronize()
+        assert torch.isfinite(pooled).all(), name
+        ctx.emb_backward_update(db, dp)
+        with pytest.raises(B.EmbError) as ei:
+            ctx.emb_read_dedup()
+        assert ei.value.code == B.EMB_EINVAL, name
+        w1, a1 = ctx.emb_read_rows(0, allrows)
+        np.testing.assert_array_equal(w1, w0, err_msg=name)
+        np.testing.assert_array_equal(a1, a0, err_msg=name)
+    # and a well-formed call afterwards is the ordinary one
+    db = B.DeviceBatch(64, good.ids, good.offsets)
+    ctx.emb_backward_update(db, dp)
+    util.compare_dedup(ctx.emb_read_dedup(), orc.backward_update(good.ids, good.offsets, dp.cpu().numpy()))
+    util.compare_rows(ctx, orc, cfg, orc.dedup(good.ids, good.offsets)[0])
+    ctx.close()
