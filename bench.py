@@ -573,6 +573,22 @@ def main() -> int:
     }
     if cache_report is not None:
         out["config"]["tables_in_host_memory"] = cache_report
+        # what the host link of this machine delivers to bulk copies (the copy engines, 256 MiB of pinned memory each way):
+        # the reference beside the row traffic of the cache, whose rows move as 16-byte accesses of a kernel
+        hbuf = torch.empty(1 << 26, dtype=torch.float32, pin_memory=True)
+        dbuf = torch.empty(1 << 26, dtype=torch.float32, device="cuda")
+        link = {}
+        for name, (dst, src) in {"host_to_device": (dbuf, hbuf), "device_to_host": (hbuf, dbuf)}.items():
+            dst.copy_(src, non_blocking=True)
+            torch.cuda.synchronize()
+            c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            c0.record()
+            for _ in range(4):
+                dst.copy_(src, non_blocking=True)
+            c1.record()
+            torch.cuda.synchronize()
+            link[name + "_GBps"] = round(4 * hbuf.numel() * 4 / (c0.elapsed_time(c1) * 1e-3) / 1e9, 1)
+        out["host_link_bulk_copy"] = link
 
     if not args.no_cpu_baseline:
         from oracle import oracle as O   # the checker, timed as a baseline only

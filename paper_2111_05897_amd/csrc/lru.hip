@@ -206,42 +206,88 @@ __global__ __launch_bounds__(kPlanThreads) void k_lru_plan(const uint32_t* __res
   (void)v;
 }
 
-// One wave per replaced slot: write the old row back to the host table, bring the new row in.
-template <typename T>
+// A group of G lanes (16 bytes each: G = row bytes / 16) per replaced slot, kSwapRows slots per group at a time: write the
+// old row back to the host table, bring the new row in.  The host link is a long pipe of small requests (a row is
+// one or a few 64-byte reads), so what matters is how many rows are in flight: 64 / G groups per wave, kSwapRows rows
+// per group, and all loads of a round (cache rows and host rows) issued before the first store.
+constexpr int kSwapRows = 4;
+template <typename T, int G>
 __global__ __launch_bounds__(kBlock) void k_lru_swap(LruView v, uint32_t step, const uint32_t* __restrict__ plan,
                                                      const uint32_t* __restrict__ miss_list,
                                                      const uint32_t* __restrict__ victims, uint32_t* __restrict__ evicted) {
-  const int lane = threadIdx.x & (kWave - 1);
-  const uint32_t wave = (blockIdx.x * kBlock + threadIdx.x) >> 6, nwaves = (gridDim.x * kBlock) >> 6;
-  const uint32_t M = plan[PL_MISSES];
   constexpr int VEC = 16 / (int)sizeof(T);
-  const uint32_t chunks = v.dim / VEC;  // 16-byte pieces per row (at most 32)
+  const int lane = threadIdx.x % G;
+  const uint32_t gid = (blockIdx.x * kBlock + threadIdx.x) / G, ngroups = (gridDim.x * kBlock) / G;
+  const uint32_t M = plan[PL_MISSES];
   T* cw = reinterpret_cast<T*>(v.cache_w);
   T* bw = reinterpret_cast<T*>(v.back_w);
-  for (uint32_t i = wave; i < M; i += nwaves) {
-    const uint32_t slot = victims[i], row = miss_list[i];
-    const uint32_t old = v.slot_row[slot];
-    if (old != kEmptySlot) {
-      if ((uint32_t)lane < chunks)
-        *reinterpret_cast<uint4*>(bw + (size_t)old * v.dim + lane * VEC) =
-            *reinterpret_cast<const uint4*>(cw + (size_t)slot * v.dim + lane * VEC);
+  constexpr int R = kSwapRows;
+  for (uint32_t i0 = gid; i0 < M; i0 += R * ngroups) {
+    uint32_t slot[R], row[R], old[R];
+    bool on[R], had[R];
+    uint4 from_cache[R], from_host[R];
+    float acc_cache[R], acc_host[R];
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+      const uint32_t idx = i0 + k * ngroups;
+      on[k] = idx < M;
+      acc_cache[k] = acc_host[k] = 0.f;
+      slot[k] = on[k] ? victims[idx] : 0u;
+      row[k] = on[k] ? miss_list[idx] : 0u;
+      old[k] = on[k] ? v.slot_row[slot[k]] : kEmptySlot;
+      had[k] = old[k] != kEmptySlot;
+    }
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+      from_cache[k] = had[k] ? *reinterpret_cast<const uint4*>(cw + (size_t)slot[k] * v.dim + lane * VEC) : make_uint4(0, 0, 0, 0);
+      from_host[k] = on[k] ? *reinterpret_cast<const uint4*>(bw + (size_t)row[k] * v.dim + lane * VEC) : make_uint4(0, 0, 0, 0);
       if (lane == 0) {
-        v.back_acc[old] = v.cache_acc[slot];
-        v.where[old] = -1;
-        atomicAdd(evicted, 1u);
+        if (had[k]) acc_cache[k] = v.cache_acc[slot[k]];
+        if (on[k]) acc_host[k] = v.back_acc[row[k]];
       }
     }
-    // the write-back above reads the slot before the fill below overwrites it: same lanes, program order
-    if ((uint32_t)lane < chunks)
-      *reinterpret_cast<uint4*>(cw + (size_t)slot * v.dim + lane * VEC) =
-          *reinterpret_cast<const uint4*>(bw + (size_t)row * v.dim + lane * VEC);
-    if (lane == 0) {
-      v.cache_acc[slot] = v.back_acc[row];
-      v.slot_row[slot] = row;
-      v.stamp[slot] = step;
-      v.where[row] = (int32_t)slot;
+    // every load above precedes the stores below in program order, so a slot is read before it is refilled
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+      if (had[k]) {
+        *reinterpret_cast<uint4*>(bw + (size_t)old[k] * v.dim + lane * VEC) = from_cache[k];
+        if (lane == 0) {
+          v.back_acc[old[k]] = acc_cache[k];
+          v.where[old[k]] = -1;
+          atomicAdd(evicted, 1u);
+        }
+      }
+      if (on[k]) {
+        *reinterpret_cast<uint4*>(cw + (size_t)slot[k] * v.dim + lane * VEC) = from_host[k];
+        if (lane == 0) {
+          v.cache_acc[slot[k]] = acc_host[k];
+          v.slot_row[slot[k]] = row[k];
+          v.stamp[slot[k]] = step;
+          v.where[row[k]] = (int32_t)slot[k];
+        }
+      }
     }
   }
+}
+
+template <typename T>
+hipError_t launch_swap_t(const LruView& v, uint32_t step, const uint32_t* plan, const uint32_t* miss_list,
+                         const uint32_t* victims, uint32_t* evicted, uint32_t max_unique, hipStream_t stream) {
+  const uint32_t G = v.dim * (uint32_t)sizeof(T) / 16u;   // 1 .. 32
+  const uint64_t groups = ((uint64_t)max_unique + kSwapRows - 1) / kSwapRows;
+  uint64_t blocks = (groups * G + kBlock - 1) / kBlock;
+  blocks = blocks < 1 ? 1 : (blocks > 4096 ? 4096 : blocks);
+#define PEMB_SWAP(GG)                                                                                                  \
+  case GG:                                                                                                             \
+    hipLaunchKernelGGL((k_lru_swap<T, GG>), dim3((uint32_t)blocks), dim3(kBlock), 0, stream, v, step, plan, miss_list,  \
+                       victims, evicted);                                                                              \
+    break;
+  switch (G) {
+    PEMB_SWAP(1) PEMB_SWAP(2) PEMB_SWAP(4) PEMB_SWAP(8) PEMB_SWAP(16) PEMB_SWAP(32)
+    default: return hipErrorInvalidValue;
+  }
+#undef PEMB_SWAP
+  return hipGetLastError();
 }
 
 __global__ void k_lru_fold_stats(uint64_t* __restrict__ stats, uint32_t* __restrict__ evicted,
@@ -365,13 +411,9 @@ hipError_t launch_lru_admit(const LruView& v, const LruScratch& s, const uint32_
   e = compact(ep, v.C, s.blk_counts, s.plan + PL_SCRATCH + 2, s.victims, s.plan + PL_OLDER, s.plan + PL_TAKE, stream);
   if (e != hipSuccess) return e;
   // 4. write back + refill
-  const uint32_t swap_blocks = blocks_for((uint64_t)max_unique * kWave, kBlock, 4096);
-  if (v.dtype == 1)
-    hipLaunchKernelGGL(k_lru_swap<bf16_t>, dim3(swap_blocks), dim3(kBlock), 0, stream, v, step, (const uint32_t*)s.plan,
-                       (const uint32_t*)s.miss_list, (const uint32_t*)s.victims, s.evicted);
-  else
-    hipLaunchKernelGGL(k_lru_swap<float>, dim3(swap_blocks), dim3(kBlock), 0, stream, v, step, (const uint32_t*)s.plan,
-                       (const uint32_t*)s.miss_list, (const uint32_t*)s.victims, s.evicted);
+  e = v.dtype == 1 ? launch_swap_t<bf16_t>(v, step, s.plan, s.miss_list, s.victims, s.evicted, max_unique, stream)
+                   : launch_swap_t<float>(v, step, s.plan, s.miss_list, s.victims, s.evicted, max_unique, stream);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(k_lru_fold_stats, dim3(1), dim3(64), 0, stream, s.stats, s.evicted, (const uint32_t*)(s.plan + PL_SCRATCH));
   return hipGetLastError();
 }
