@@ -150,6 +150,44 @@ def test_loop_tracks_the_oracle(B, tau):
     loop.close()
 
 
+@pytest.mark.parametrize("tau,opt", [(0, 1), (2, 0), (3, 1)])
+def test_embedding_side_of_the_loop_follows_the_oracle_element_by_element(B, tau, opt):
+    """The loop equals the serial order of its entry points bit for bit (test above).  Here that serial order runs
+    with the embedding oracle beside it, fed at every training step with the GPU network's own gradient of the
+    pooled activations (stage isolation: the bf16 noise of the dense step never enters the comparison): every
+    lookup of the loop -- stale by tau updates -- and the rows and accumulators at the end must match the oracle
+    element by element on the fp32 bar."""
+    import torch
+    from tests import util
+    batches = _host_batches()
+    emb, mlp = _contexts(B, opt)
+    orc = Oracle(**_emb_args(opt))
+    cfg = W.EmbConfig(tables=[W.TableDesc(ROWS, DIM, 0)], slots=[W.SlotDesc(0, W.default_salt(s)) for s in range(SLOTS)])
+    pending = []
+
+    def train(item):
+        b, db, dense, labels, pooled = item
+        d_pooled, _ = mlp.mlp_step(pooled, dense, labels)
+        emb.emb_backward_update(db, d_pooled)
+        orc.backward_update(b.ids, b.offsets, d_pooled.cpu().numpy())
+
+    for b, dense, labels in batches:
+        db = B.DeviceBatch(b.batch_size, b.ids, b.offsets)
+        pooled = emb.emb_lookup_pool(db)
+        torch.cuda.synchronize()
+        util.compare_pooled(pooled.cpu().numpy(), orc.lookup_pool(b.ids, b.offsets), cfg)
+        pending.append((b, db, torch.from_numpy(dense).cuda(), torch.from_numpy(labels).cuda(), pooled))
+        if len(pending) > tau:
+            train(pending.pop(0))
+    while pending:
+        train(pending.pop(0))
+    gw, ga = emb.emb_read_rows(0, np.arange(ROWS))
+    ow, oa = orc.read_rows(0, np.arange(ROWS))
+    util.assert_close(gw, ow, rtol=1e-5, atol=1e-6, err_msg="rows")
+    util.assert_close(ga, oa, rtol=1e-5, atol=1e-6, err_msg="accumulators")
+    assert (ow != Oracle(**_emb_args(opt)).read_rows(0, np.arange(ROWS))[0]).any()
+
+
 def test_loop_validation(B):
     import torch
     emb, mlp = _contexts(B, 0)
