@@ -74,7 +74,7 @@ def read_traffic_profile(path):
     traffic, meta = {}, {}
     for line in open(path):
         f = line.split()
-        if len(f) == 3 and f[0] == "traffic":
+        if len(f) == 3 and f[0] == "traffic_per_step":
             traffic[f[1]] = int(f[2])
         elif len(f) == 3 and f[0] == "workload":
             meta[f[1]] = int(f[2])
@@ -328,7 +328,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 1 GiB device-to-device copies (reference for rocprofv3 byte counters)")
-    ap.add_argument("--cpu-samples", type=int, default=0, help="samples of batch 0 the oracle is timed on (0 = all)")
+    ap.add_argument("--cpu-samples", type=int, default=0, help="samples of batch 0 the oracle is timed on (0 = all, or as many as hold about 30 M ids)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives); use --gpus 1", file=sys.stderr)
@@ -534,10 +534,9 @@ def main() -> int:
         traffic, meta = prof
         same = (abs(meta.get("ids_per_step", -1) - N_avg) <= 0.01 * N_avg and
                 abs(meta.get("unique_rows_per_step", -1) - U_avg) <= 0.01 * U_avg)
-        if same:
-            per_launch = ("gather_pool", "build_keys", "reduce_update")   # the other stages are listed per step
-            roofline["traffic"] = traffic.get(dom)
-            profile_step_bytes = sum(v * (launches.get(k, 1) if k in per_launch else 1) for k, v in traffic.items())
+        if same and dom in traffic:
+            roofline["traffic"] = int(traffic[dom] / launches[dom])     # per launch, like `achieved`
+            profile_step_bytes = sum(traffic.values())
 
     out = {
         "metric": "embedding IDs/sec (lookup+bwd+update), 1 GPU", "value": round(ids_per_s, 1), "unit": "IDs/s",
@@ -594,7 +593,8 @@ def main() -> int:
         from oracle import oracle as O   # the checker, timed as a baseline only
         hb = host_batches[0]
         S = cfg.num_slots
-        bs = args.cpu_samples if args.cpu_samples else hb.batch_size
+        # a bounded sample: whole batch 0 unless it holds more than ~30 M ids (then as many leading samples as hold that many)
+        bs = args.cpu_samples if args.cpu_samples else max(1, min(hb.batch_size, int(3.0e7 * hb.batch_size / max(hb.num_ids, 1))))
         bs = min(bs, hb.batch_size)
         off = hb.offsets[: bs * S + 1]
         ids = hb.ids[: int(off[-1])]
