@@ -124,7 +124,11 @@ template <typename T, int D, int OPT>
 __global__ __launch_bounds__(kBlock) void k_tile_reduce_update(TileArgs a) {
   constexpr int LG = D / 4;          // lanes per tile
   constexpr int GPB = kBlock / LG;   // tiles per workgroup
-  constexpr int SC = 4;              // entries fetched together: SC gradient rows + the table rows of the runs they start
+  // entries fetched together: SC gradient rows + the table rows of the runs they start.  Four keep more requests in
+  // flight per wave, two leave registers for 7 instead of 5 waves per SIMD; measured (reduce + update, ms): fp32 D = 64
+  // (config 2) 0.717 with four against 0.725 with two, bf16 D = 64 (config 4) 1.034 against 0.965, the five bf16 tables
+  // of config 3 8.36 against 7.64.
+  constexpr int SC = sizeof(T) == 4 ? 4 : 2;
   static_assert(kTile % SC == 0, "sub-chunk geometry");
   if (*a.bad_flag == a.call) return;  // inconsistent offsets: keys and bags cannot be trusted as addresses (uniform exit)
   __shared__ uint32_t s_key[GPB][kTile];
