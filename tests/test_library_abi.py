@@ -13,7 +13,7 @@ HEADER = os.path.join(ROOT, "include", "persia_emb.h")
 def declared_functions():
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(emb_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b((?:emb|mlp|hyb)_[a-z_]+)\s*\(", text)))
 
 
 def test_header_declares_the_boundary_calls():
@@ -36,6 +36,67 @@ def test_library_loads_and_exports_every_declared_symbol():
     # error path that needs no GPU: null arguments are rejected, with a message
     assert lib.emb_create(None, None) == binding.EMB_EINVAL
     assert b"null" in lib.emb_last_error(None)
+
+
+def _config(b, tables, slots, **kw):
+    t = (b.emb_table_desc * len(tables))(*[b.emb_table_desc(*x) for x in tables])
+    s = (b.emb_slot_desc * len(slots))(*[b.emb_slot_desc(x[0], x[2] if len(x) > 2 else 0, x[1]) for x in slots])
+    f = dict(hash=1, opt=1, lr=0.05, eps=1e-8, acc_init=0.1, init_lo=-0.01, init_hi=0.01, device=0, init_seed=1,
+             max_ids=64, max_batch=8, reserved=0)
+    f.update(kw)
+    cfg = b.emb_config(len(tables), len(slots), t, s, f["hash"], f["opt"], f["lr"], f["eps"], f["acc_init"], f["init_lo"],
+                       f["init_hi"], f["device"], f["init_seed"], f["max_ids"], f["max_batch"], f["reserved"])
+    cfg._keep = (t, s)
+    return cfg
+
+
+def test_argument_validation_happens_on_the_host_before_any_device_call():
+    """Every malformed configuration is turned away with EMB_EINVAL and a message by checks that run before the
+    library touches a device (so they can be exercised here, without a GPU); null contexts likewise."""
+    from paper_2111_05897_amd import binding as b
+    lib = b.load_library()
+    h = C.c_void_p()
+    bad = {
+        "dim 12": _config(b, [(100, 12, 0)], [(0, 1)]),
+        "unknown dtype": _config(b, [(100, 8, 7)], [(0, 1)]),
+        "table with 0 rows": _config(b, [(0, 8, 0)], [(0, 1)]),
+        "too many rows": _config(b, [(1 << 30, 8, 0), (1 << 30, 8, 0)], [(0, 1), (1, 2)]),
+        "slot names a missing table": _config(b, [(100, 8, 0)], [(3, 1)]),
+        "slot.reserved": _config(b, [(100, 8, 0)], [(0, 1, 9)]),
+        "config.reserved": _config(b, [(100, 8, 0)], [(0, 1)], reserved=1),
+        "unknown hash": _config(b, [(100, 8, 0)], [(0, 1)], hash=5),
+        "unknown optimizer": _config(b, [(100, 8, 0)], [(0, 1)], opt=2),
+        "negative eps": _config(b, [(100, 8, 0)], [(0, 1)], eps=-1.0),
+        "lr not finite": _config(b, [(100, 8, 0)], [(0, 1)], lr=float("nan")),
+        "init range reversed": _config(b, [(100, 8, 0)], [(0, 1)], init_lo=1.0, init_hi=-1.0),
+        "max_batch 0": _config(b, [(100, 8, 0)], [(0, 1)], max_batch=0),
+        "max_ids too large": _config(b, [(100, 8, 0)], [(0, 1)], max_ids=1 << 31),
+        "bags overflow": _config(b, [(100, 8, 0)], [(0, 1)] * 4096, max_batch=1 << 20),
+    }
+    for name, cfg in bad.items():
+        assert lib.emb_create(C.byref(cfg), C.byref(h)) == b.EMB_EINVAL, name
+        assert lib.emb_last_error(None), name
+        assert not h.value, name
+    small_cache = (C.c_uint64 * 1)(10)            # fewer slots than one batch may need
+    cfg = _config(b, [(1000, 8, 0)], [(0, 1)])
+    assert lib.emb_create_cached(C.byref(cfg), small_cache, C.byref(h)) == b.EMB_EINVAL
+    assert b"cache_rows" in lib.emb_last_error(None)
+    # null contexts
+    batch = b.emb_batch(1, 0, 0, None, None)
+    assert lib.emb_lookup_pool(None, C.byref(batch), None, None) == b.EMB_EINVAL
+    assert lib.emb_backward_update(None, C.byref(batch), None, None) == b.EMB_EINVAL
+    assert lib.emb_backward_update_static(None, C.byref(batch), None, None) == b.EMB_EINVAL
+    assert lib.emb_hash_rows(None, C.byref(batch), None, None) == b.EMB_EINVAL
+    assert lib.emb_dedup_sizes(None, None, None) == b.EMB_EINVAL
+    assert lib.emb_read_rows(None, 0, None, 0, None, None) == b.EMB_EINVAL
+    assert lib.emb_destroy(None) == b.EMB_OK
+    assert lib.emb_static_max_ids() == 1 << 18
+    # the value codec's arguments (pointers are only looked at, never followed, before the checks)
+    fake = C.c_void_p(0x1000)
+    assert lib.emb_codec_compress(fake, 4, 6, 1024.0, fake, fake, None) == b.EMB_EINVAL          # block_len % 4
+    assert lib.emb_codec_compress(fake, 4, 8, 1.0e6, fake, fake, None) == b.EMB_EINVAL           # kappa beyond fp16
+    assert lib.emb_codec_decompress(None, fake, 4, 8, 1024.0, fake, None) == b.EMB_EINVAL        # null buffer
+    assert lib.emb_codec_compress(None, 0, 8, 1024.0, None, None, None) == b.EMB_OK              # nothing to do
 
 
 def test_binding_struct_layouts():
