@@ -570,6 +570,36 @@ def main() -> int:
         "setup_s": round(setup_s, 1),
         "roofline": roofline,
     }
+    if cache_report is None and not args.overlap:
+        # What this machine delivers to the barest kernel with the same access pattern (emb_probe_random_rows): as many
+        # uniformly random whole-row reads as the step has ids, over the benchmark's own table (no key is frequent,
+        # so this is the forward without its cache hits) and over its gradient buffer (row = one bag's gradient).
+        sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+        p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+        def probe_ms(ptr, rows, row_bytes, n):
+            binding.emb_probe_random_rows(ptr, rows, row_bytes, n, sink)
+            torch.cuda.synchronize()
+            p0.record()
+            for _ in range(5):
+                binding.emb_probe_random_rows(ptr, rows, row_bytes, n, sink)
+            p1.record()
+            torch.cuda.synchronize()
+            return p0.elapsed_time(p1) / 5
+
+        bare = []
+        for t in range(T):
+            n_t, D_t = int(N_t[t] / prof_steps), cfg.tables[t].dim
+            if n_t == 0:
+                continue
+            w_ptr, _ = ctx.emb_table_ptr(t)
+            ms_w = probe_ms(w_ptr, cfg.tables[t].rows, D_t * e_of[t], n_t)
+            g_rows = grads[0].numel() // D_t
+            ms_g = probe_ms(grads[0].data_ptr(), g_rows, D_t * 4, n_t)
+            bare.append({"table": t, "reads": n_t,
+                         "table_rows": {"row_bytes": D_t * e_of[t], "ms": round(ms_w, 4), "GBps": round(gbps(n_t * D_t * e_of[t], ms_w), 1)},
+                         "gradient_rows": {"row_bytes": D_t * 4, "ms": round(ms_g, 4), "GBps": round(gbps(n_t * D_t * 4, ms_g), 1)}})
+        out["bare_random_row_reads"] = bare
     if cache_report is not None:
         out["config"]["tables_in_host_memory"] = cache_report
         # what the host link of this machine delivers to bulk copies (the copy engines, 256 MiB of pinned memory each way):

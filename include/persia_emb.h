@@ -310,6 +310,16 @@ int emb_cache_stats(emb_ctx* ctx, uint32_t table, uint64_t* stats);
 int emb_cache_where(emb_ctx* ctx, uint32_t table, int32_t* where_host);
 int emb_cache_flush(emb_ctx* ctx, void* hip_stream);
 
+/* Measurement aid (no part of the paper's path): the barest kernel with the path's access pattern.  Reads
+ * n_reads rows of row_bytes (a power of two, 16 .. 512) at pseudo-random positions of the array base[rows * row_bytes]
+ * (device), 16 bytes per lane, eight rows in flight per lane group, and discards them; hot_of_8 of every 8 reads fall
+ * into the first hot_rows rows, the others anywhere (hot_of_8 = 0: all anywhere).  sink16: 16 bytes of device memory
+ * that receive one value depending on the rows read.  Enqueue-only; the caller times it.  bench.py runs it on the
+ * benchmark's own table and gradient buffer, so that the gather and the segmented reduction are set against what
+ * this box delivers to random row reads rather than against a datasheet. */
+int emb_probe_random_rows(const void* base, uint64_t rows, uint32_t row_bytes, uint64_t n_reads, uint64_t hot_rows,
+                          uint32_t hot_of_8, void* sink16, void* hip_stream);
+
 /* Shapes and limits a context was created with (any pointer may be NULL). */
 int emb_describe(emb_ctx* ctx, uint32_t* num_slots, uint32_t* pooled_width, uint32_t* max_batch, uint64_t* max_ids,
                  int32_t* device);

@@ -84,6 +84,8 @@ def load_library() -> C.CDLL:
     L.emb_backward_update_static.restype = C.c_int
     L.emb_static_max_ids.argtypes = []
     L.emb_static_max_ids.restype = u64
+    L.emb_probe_random_rows.argtypes = [vp, u64, u32, u64, u64, u32, vp, vp]
+    L.emb_probe_random_rows.restype = C.c_int
     L.emb_dedup_sizes.argtypes = [vp, C.POINTER(u64), C.POINTER(u64)]
     L.emb_read_dedup.argtypes = [vp, vp, vp, vp]
     L.emb_read_rows.argtypes = [vp, u32, vp, u64, vp, vp]
@@ -316,6 +318,16 @@ class EmbContext:
 
     def emb_device_bytes(self) -> int:
         return int(self.L.emb_device_bytes(self.h))
+
+
+def emb_probe_random_rows(base_ptr: int, rows: int, row_bytes: int, n_reads: int, sink: torch.Tensor, hot_rows: int = 0,
+                          hot_of_8: int = 0, stream=None) -> None:
+    """Enqueues the bare random-row read probe on the array at device address base_ptr (rows * row_bytes bytes)."""
+    L = load_library()
+    assert sink.is_cuda and sink.numel() * sink.element_size() >= 16
+    rc = L.emb_probe_random_rows(base_ptr, rows, row_bytes, n_reads, hot_rows, hot_of_8, sink.data_ptr(), _stream_ptr(stream))
+    if rc:
+        raise EmbError(rc, "emb_probe_random_rows: bad arguments")
 
 
 def emb_codec_compress(v: torch.Tensor, block_len: int, kappa: float = 2.0 ** 15, stream=None):

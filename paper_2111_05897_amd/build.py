@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpersia_emb.so")
-SOURCES = ["table.hip", "forward.hip", "sort.hip", "backward.hip", "codec.hip", "gemm.hip", "mlp.hip", "lru.hip", "emb_api.hip", "hybrid.hip"]
+SOURCES = ["table.hip", "forward.hip", "sort.hip", "backward.hip", "codec.hip", "gemm.hip", "mlp.hip", "lru.hip", "emb_api.hip", "hybrid.hip", "probe.hip"]
 # packed-fp32 instructions are switched off for all device code (some of their forms have given wrong results)
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wextra",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
