@@ -91,7 +91,8 @@ struct TileArgs {
   uint32_t S, width;
   uint32_t s_mul, s_shift;  // bag / S as a multiply-high and shifts (div_by_S below)
   const uint32_t* slot_col;
-  int uniform;
+  int uniform;            // 1: gradient of payload g at g * D (one table: the payload is the bag index)
+  int position;           // 1: the payload is the gradient's position in d_pooled in units of 4 floats
   double* partials;
   uint32_t pstride;
   const uint32_t* range;
@@ -115,6 +116,7 @@ __device__ __forceinline__ uint32_t div_by_S(const TileArgs& a, uint32_t n) {
 template <int D>
 __device__ __forceinline__ const float* grad_ptr(const TileArgs& a, uint32_t bag, int lane) {
   if (a.uniform) return a.d_pooled + (size_t)bag * D + lane * 4;
+  if (a.position) return a.d_pooled + (size_t)bag * 4 + lane * 4;
   const uint32_t b = div_by_S(a, bag);
   const uint32_t s = bag - b * a.S;
   return a.d_pooled + (size_t)b * a.width + a.slot_col[s] + lane * 4;
@@ -492,6 +494,7 @@ hipError_t launch_tile_reduce_update(const TableView& t, const BackwardArgs& b, 
   a.width = b.width;
   a.slot_col = b.slot_col;
   a.uniform = b.uniform;
+  a.position = b.payload_is_position;
   a.partials = b.partials;
   a.pstride = b.pstride;
   a.range = b.range;

@@ -2,6 +2,7 @@
 // workspace, and the sequence of kernel launches of each hot call.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <cstdio>
@@ -83,6 +84,8 @@ struct emb_ctx {
   int key_bits = 1;
   int sort_max_bits = 8;  // 9-bit digits save a pass at 26 key bits but scatter in shorter runs: measured slower (scatter 0.260 vs 0.225 ms)
   int uniform = 0;
+  uint32_t payload_width = 0;        // != 0: the sort's payload is the gradient's position in d_pooled / 4, not the bag
+  std::vector<uint32_t> slot_col_host;
   uint32_t pstride = 0;
   std::vector<TableView> tables;
   std::vector<uint32_t> key_base_host;
@@ -435,6 +438,9 @@ static int emb_create_impl(const emb_config* cfg, const uint64_t* cache_rows, em
     col += tv.dim;
   }
   ctx->width = col;
+  ctx->slot_col_host = s_col;
+  // several tables: the payload carries the gradient's position (in units of 4 floats) if that fits 32 bits
+  if (cfg->num_tables > 1 && (uint64_t)cfg->max_batch * col / 4 < (1ull << 32)) ctx->payload_width = col;
   {
     uint64_t *p_salt = nullptr, *p_rows = nullptr, *p_mask = nullptr;
     uint32_t *p_kb = nullptr, *p_col = nullptr;
@@ -537,7 +543,7 @@ static int run_dedup(emb_ctx* ctx, const Workspace& ws, const emb_batch* batch, 
   {
     StageTimer tm(ctx, ST_BUILD_KEYS, stream);
     CKH(launch_build_keys(ctx->slots, batch->ids, batch->offsets, n, batch->batch_size, ctx->S, ctx->mix, 0,
-                          ws.keys[0], ws.bags[0], ws.counters + kBadFlag, ctx->last_call, stream),
+                          ws.keys[0], ws.bags[0], ws.counters + kBadFlag, ctx->last_call, ctx->payload_width, stream),
         "build_keys");
   }
   const SortPlan plan = make_sort_plan(n, ctx->key_bits, ctx->sort_max_bits);
@@ -688,7 +694,7 @@ static int emb_hash_rows_impl(emb_ctx* ctx, const emb_batch* batch, uint32_t* ro
   hipStream_t stream = (hipStream_t)hip_stream;
   CKH(hipSetDevice(ctx->device), "hipSetDevice");
   CKH(launch_build_keys(ctx->slots, batch->ids, batch->offsets, (uint32_t)batch->num_ids, batch->batch_size, ctx->S,
-                        ctx->mix, 1, rows_out, nullptr, nullptr, 0, stream),
+                        ctx->mix, 1, rows_out, nullptr, nullptr, 0, 0, stream),
       "hash_rows");
   return EMB_OK;
 }
@@ -737,6 +743,7 @@ static int backward_update_with(emb_ctx* ctx, const Workspace& ws, const emb_bat
   a.width = ctx->width;
   a.slot_col = ctx->slots.col;
   a.uniform = ctx->uniform;
+  a.payload_is_position = ctx->payload_width != 0;
   a.partials = ws.partials;
   a.pstride = ctx->pstride;
   a.range = nullptr;
@@ -753,8 +760,11 @@ static int backward_update_with(emb_ctx* ctx, const Workspace& ws, const emb_bat
   a.call = ctx->last_call;
   {
     StageTimer tm(ctx, ST_TILE_ORDER, stream);
-    // shift that leaves 8 bits of the bag index (the tile keys use 7: 128 buckets of consecutive bags, sample-major)
-    int shift = bit_length((uint64_t)batch->batch_size * ctx->S - 1) - 8;
+    // shift that leaves 8 bits of the payload (the tile keys use 7: 128 buckets of consecutive bags, sample-major;
+    // gradient positions are sample-major too)
+    const uint64_t payload_range = ctx->payload_width ? (uint64_t)batch->batch_size * ctx->payload_width / 4
+                                                      : (uint64_t)batch->batch_size * ctx->S;
+    int shift = bit_length(payload_range - 1) - 8;
     if (shift < 0) shift = 0;
     CKH(launch_tile_order(a.keys, a.bags, n, shift, ctx->key_base_dev, (uint32_t)ctx->tables.size(), ws.tile_key,
                           ws.tile_val, ws.hist, ws.total, &a.tile_perm, stream),
@@ -867,9 +877,19 @@ static int emb_read_dedup_impl(emb_ctx* ctx, uint64_t* keys, uint32_t* seg_off, 
     }
   }
   if (seg_off) CKH(hipMemcpy(seg_off, ctx->last_ws.seg_off, (U + 1) * sizeof(uint32_t), hipMemcpyDeviceToHost), "hipMemcpy(seg_off)");
-  if (seg_bags && N)
+  if (seg_bags && N) {
     CKH(hipMemcpy(seg_bags, ctx->last_ws.bags[ctx->sorted_buf], N * sizeof(uint32_t), hipMemcpyDeviceToHost),
         "hipMemcpy(seg_bags)");
+    if (ctx->payload_width) {  // gradient positions back to bag indices: sample = p / (W / 4), slot = the one whose columns hold the rest
+      const uint32_t w4 = ctx->payload_width / 4;
+      const std::vector<uint32_t>& col = ctx->slot_col_host;
+      for (uint64_t i = 0; i < N; ++i) {
+        const uint32_t b = seg_bags[i] / w4, c = (seg_bags[i] % w4) * 4;
+        const uint32_t slot = (uint32_t)(std::upper_bound(col.begin(), col.end(), c) - col.begin()) - 1;
+        seg_bags[i] = b * ctx->S + slot;
+      }
+    }
+  }
   return EMB_OK;
 }
 

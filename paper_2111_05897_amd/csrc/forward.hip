@@ -160,12 +160,16 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(sizeof(T
 // at n -- together: the bags tile [0, n) exactly, so every key and bag slot below n is written.  A violation is
 // recorded as bad_flag[0] = call (the number of this call) and the bag writes nothing outside [0, n); the kernels that
 // turn keys into addresses look at the flag first.
+// The payload stored beside a key is the bag index, or -- payload_width != 0, contexts with several tables -- the
+// position of the bag's gradient in d_pooled in units of 4 floats, (sample * payload_width + col(slot)) / 4: the
+// segmented reduction then forms the gradient's address with one multiply instead of a division by S and a load of
+// col(slot) in front of every gradient load.
 __global__ __launch_bounds__(kBlock) void k_build_keys(SlotArrays sl, const uint64_t* __restrict__ ids,
                                                        const int32_t* __restrict__ offsets, uint32_t n_bags,
                                                        uint32_t S, int mix, int bare_rows, uint32_t n,
                                                        uint32_t* __restrict__ keys_out,
                                                        uint32_t* __restrict__ bags_out, uint32_t* __restrict__ bad_flag,
-                                                       uint32_t call) {
+                                                       uint32_t call, uint32_t payload_width) {
   const uint32_t bag = blockIdx.x * (kBlock / 8) + threadIdx.x / 8;
   const int lane = threadIdx.x % 8;
   if (bag >= n_bags) return;
@@ -179,9 +183,10 @@ __global__ __launch_bounds__(kBlock) void k_build_keys(SlotArrays sl, const uint
   }
   const uint64_t salt = sl.salt[slot], rows = sl.rows[slot], mask = sl.mask[slot];
   const uint32_t kb = bare_rows ? 0u : sl.key_base[slot];
+  const uint32_t payload = payload_width ? (uint32_t)(((uint64_t)(bag / S) * payload_width + sl.col[slot]) >> 2) : bag;
   for (int i = beg + lane; i < end; i += 8) {
     keys_out[i] = kb + hash_row(ids[i], salt, rows, mask, mix);
-    if (bags_out) bags_out[i] = bag;
+    if (bags_out) bags_out[i] = payload;
   }
 }
 
@@ -354,12 +359,12 @@ hipError_t launch_gather_pool(const TableView& t, const SlotArrays& sl, const ui
 
 hipError_t launch_build_keys(const SlotArrays& sl, const uint64_t* ids, const int32_t* offsets, uint32_t num_ids,
                              uint32_t B, uint32_t S, int mix, int bare_rows, uint32_t* keys_out, uint32_t* bags_out,
-                             uint32_t* bad_flag, uint32_t call, hipStream_t stream) {
+                             uint32_t* bad_flag, uint32_t call, uint32_t payload_width, hipStream_t stream) {
   const uint32_t n_bags = B * S;
   if (n_bags == 0) return hipSuccess;
   const uint32_t grid = (n_bags + kBlock / 8 - 1) / (kBlock / 8);
   hipLaunchKernelGGL(k_build_keys, dim3(grid), dim3(kBlock), 0, stream, sl, ids, offsets, n_bags, S, mix, bare_rows,
-                     num_ids, keys_out, bags_out, bad_flag, call);
+                     num_ids, keys_out, bags_out, bad_flag, call, payload_width);
   return hipGetLastError();
 }
 

@@ -110,10 +110,11 @@ hipError_t launch_bag_bounds(const uint32_t* sorted_bags, uint32_t N, uint32_t* 
                              hipStream_t stream);
 // keys_out[i] = key_base(slot) + row (or the bare row when bare_rows != 0); bags_out may be null.  bad_flag
 // (optional, device): receives `call` if the offsets do not tile [0, num_ids) bag by bag; nothing is written outside
-// [0, num_ids) either way.
+// [0, num_ids) either way.  payload_width != 0: bags_out receives (sample * payload_width + col(slot)) / 4, the
+// position of the bag's gradient in d_pooled in units of 4 floats, instead of the bag index.
 hipError_t launch_build_keys(const SlotArrays& sl, const uint64_t* ids, const int32_t* offsets, uint32_t num_ids,
                              uint32_t B, uint32_t S, int mix, int bare_rows, uint32_t* keys_out, uint32_t* bags_out,
-                             uint32_t* bad_flag, uint32_t call, hipStream_t stream);
+                             uint32_t* bad_flag, uint32_t call, uint32_t payload_width, hipStream_t stream);
 
 // ---- sort.hip ----
 struct SortPlan {
@@ -138,7 +139,8 @@ hipError_t launch_unique(const uint32_t* keys, uint32_t n, uint32_t* blk_heads, 
 // ---- backward.hip ----
 struct BackwardArgs {
   const uint32_t* keys;      // sorted, [n]
-  const uint32_t* bags;      // sorted with the keys, [n]
+  const uint32_t* bags;      // sorted with the keys, [n]: bag indices, or gradient positions (payload_is_position)
+  int payload_is_position;   // the payload is (sample * width + col(slot)) / 4 (launch_build_keys with payload_width)
   uint32_t n;
   const float* d_pooled;     // [B, width]
   uint32_t S, width;
