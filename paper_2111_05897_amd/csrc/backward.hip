@@ -126,11 +126,13 @@ template <typename T, int D, int OPT>
 __global__ __launch_bounds__(kBlock) void k_tile_reduce_update(TileArgs a) {
   constexpr int LG = D / 4;          // lanes per tile
   constexpr int GPB = kBlock / LG;   // tiles per workgroup
-  // entries fetched together: SC gradient rows + the table rows of the runs they start.  Four keep more requests in
-  // flight per wave, two leave registers for 7 instead of 5 waves per SIMD; measured (reduce + update, ms): fp32 D = 64
-  // (config 2) 0.717 with four against 0.725 with two, bf16 D = 64 (config 4) 1.034 against 0.965, the five bf16 tables
-  // of config 3 8.36 against 7.64.
-  constexpr int SC = sizeof(T) == 4 ? 4 : 2;
+  // entries fetched together: SC gradient rows + the table rows of the runs they start.  More keep more requests in
+  // flight per wave, fewer leave registers for more waves per SIMD.  Measured (reduce + update, ms): fp32 D = 64
+  // (config 2) 0.717 with four against 0.725 with two; bf16 D = 64 (config 4) 1.034 with four, 0.965 with two, 1.012
+  // with one; the bf16 tables of config 3 per launch (us) with 1 / 2 / 4 / 8 entries: D = 128: 2537 / 2586 / 2747 / -,
+  // D = 64: 1494 / 1536 / 1633 / -, D = 32: - / 969 / 978 / -, D = 16: - / 799 / 776 / -, D = 8 (whose LDS tiles allow
+  // two waves per SIMD whatever the register count): - / 877 / 820 / 828.
+  constexpr int SC = sizeof(T) == 4 ? 4 : (D <= 16 ? 4 : D == 128 ? 1 : 2);
   static_assert(kTile % SC == 0, "sub-chunk geometry");
   if (*a.bad_flag == a.call) return;  // inconsistent offsets: keys and bags cannot be trusted as addresses (uniform exit)
   __shared__ uint32_t s_key[GPB][kTile];
