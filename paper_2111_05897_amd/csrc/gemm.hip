@@ -32,7 +32,7 @@ constexpr int kRowBytes = BK * 2;                   // a staged row: chunks of 1
 constexpr int kStageBytes = (BM + BN) * kRowBytes;  // one LDS stage: A tile then Bt tile
 constexpr size_t kGemmLdsBytes = (size_t)kStages * kStageBytes;
 constexpr uint32_t kXcds = 8;
-constexpr uint32_t kGroupM = 8;     // m-tiles per raster group
+constexpr uint32_t kBlockM = 8, kBlockN = 4;  // tiles the 32 CUs of an XCD work on together
 
 struct GemmArgs {
   const bf16_t* A;   // [M, K], row stride lda
@@ -54,19 +54,36 @@ template <int EPI>
 __global__ __launch_bounds__(kGemmThreads, 2) void k_gemm_nt(GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
   const uint32_t tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-  const uint32_t total = tiles_m * tiles_n;
-  // XCD-aware numbering: workgroup b runs on XCD b % 8; give each XCD a contiguous stretch of the tile order
-  const uint32_t per_xcd = (gridDim.x + kXcds - 1) / kXcds;
-  const uint32_t lid = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
-  if (lid >= total) return;
-  // grouped raster: kGroupM m-tiles at a time, n fastest inside a group column
-  const uint32_t group_sz = kGroupM * tiles_n;
-  const uint32_t gidx = lid / group_sz;
-  const uint32_t first_m = gidx * kGroupM;
-  const uint32_t rows_in_group = (tiles_m - first_m < kGroupM) ? tiles_m - first_m : kGroupM;
-  const uint32_t in_group = lid - gidx * group_sz;
-  const uint32_t tile_m = first_m + in_group % rows_in_group;
-  const uint32_t tile_n = in_group / rows_in_group;
+  // XCD-aware numbering.  Workgroup b runs on XCD b % 8, and an XCD starts its workgroups in the order of b / 8, 32 at
+  // a time (one per CU): those 32 take a block of kBlockM x kBlockN tiles, so that 8 + 4 operand strips serve 32 tiles
+  // out of that XCD's L2.  The blocks are numbered along n first, and at any time the 8 XCDs hold 8 consecutive
+  // blocks: XCDs that work on the same m-tiles at the same time fetch the same strips of A, and all but the first
+  // find them in the memory-side cache instead of HBM (likewise the strips of Bt for XCDs on the same n-tiles).
+  // A product with fewer than 8 such blocks (the ones cut along K) instead gives every XCD a contiguous stretch of a
+  // raster that runs down kBlockM m-tiles at a time.
+  const uint32_t nchunks = (tiles_n + kBlockN - 1) / kBlockN;
+  const uint32_t nblocks = ((tiles_m + kBlockM - 1) / kBlockM) * nchunks;
+  uint32_t tile_m, tile_n;
+  if (nblocks >= kXcds) {
+    const uint32_t local = blockIdx.x / kXcds;                     // order of this workgroup on its XCD
+    const uint32_t blk = (local / (kBlockM * kBlockN)) * kXcds + blockIdx.x % kXcds;
+    const uint32_t within = local % (kBlockM * kBlockN);
+    if (blk >= nblocks) return;
+    tile_m = (blk / nchunks) * kBlockM + within % kBlockM;
+    tile_n = (blk % nchunks) * kBlockN + within / kBlockM;
+    if (tile_m >= tiles_m || tile_n >= tiles_n) return;
+  } else {
+    const uint32_t per_xcd = gridDim.x / kXcds;
+    const uint32_t lid = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+    if (lid >= tiles_m * tiles_n) return;
+    const uint32_t group_sz = kBlockM * tiles_n;
+    const uint32_t gidx = lid / group_sz;
+    const uint32_t first_m = gidx * kBlockM;
+    const uint32_t rows_in_group = (tiles_m - first_m < kBlockM) ? tiles_m - first_m : kBlockM;
+    const uint32_t in_group = lid - gidx * group_sz;
+    tile_m = first_m + in_group % rows_in_group;
+    tile_n = in_group / rows_in_group;
+  }
   const uint32_t m0 = tile_m * BM, n0 = tile_n * BN;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -116,25 +133,37 @@ __global__ __launch_bounds__(kGemmThreads, 2) void k_gemm_nt(GemmArgs g) {
     srcB[j] = reinterpret_cast<const char*>(g.Bt + (size_t)(n0 + r) * g.ldb + (size_t)kt0 * kKUnit + chunk_of(rt) * 8);
   }
   char* lds_bytes = reinterpret_cast<char*>(lds);
-  auto request = [&](uint32_t tile, int stage) {  // tile: index of the 32-wide K tile inside this split
+  // one wave instruction of a tile's requests: numbers 0 .. LA-1 are A's, LA .. LA+LB-1 are Bt's
+  auto request_one = [&](uint32_t tile, int stage, int j) {  // tile: index of the BK-wide K tile inside this split
     char* dst = lds_bytes + stage * kStageBytes;
-#pragma unroll
-    for (int j = 0; j < LA; ++j)
+    if (j < LA)
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(srcA[j] + (size_t)tile * kRowBytes),
                                        (__attribute__((address_space(3))) void*)(dst + (j * kWaves + uwave) * 1024), 16, 0, 0);
+    else
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(srcB[j - LA] + (size_t)tile * kRowBytes),
+                                       (__attribute__((address_space(3))) void*)(dst + BM * kRowBytes + ((j - LA) * kWaves + uwave) * 1024), 16, 0, 0);
+  };
+  auto request = [&](uint32_t tile, int stage) {
 #pragma unroll
-    for (int j = 0; j < LB; ++j)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(srcB[j] + (size_t)tile * kRowBytes),
-                                       (__attribute__((address_space(3))) void*)(dst + BM * kRowBytes + (j * kWaves + uwave) * 1024), 16, 0, 0);
+    for (int j = 0; j < LA + LB; ++j) request_one(tile, stage, j);
   };
   // fragment rows are base + lane % 32 with base a multiple of 32, so swz(row) depends on the lane only
   const uint32_t swz = (uint32_t)(((lane & 31) >> SWZ_SHIFT) & (CPR - 1));
   static_assert((kStages - 2) * (LA + LB) <= 15, "the wait below encodes its count in four bits");
-  auto compute = [&](int stage) {
+  // The products of one staged tile, with the requests for the next tile (into next_stage) issued between them: a
+  // k-step's share of the requests goes out in front of that k-step's fragment reads.  Issued in one burst after the
+  // barrier, the 64 wave instructions of a tile (512 cache lines) queue up in front of the L1 and hold the waves at
+  // the issue of their later requests, so that the products start late (measured: 1.07 -> 1.11 PFLOP/s).
+  constexpr int KSTEPS = BK / 16;
+  constexpr int kPerStep = (LA + LB) / KSTEPS;
+  static_assert((LA + LB) % KSTEPS == 0, "requests per k-step");
+  auto compute = [&](int stage, uint32_t next_tile, int next_stage) {
     const char* As = lds_bytes + stage * kStageBytes;
     const char* Bs = As + BM * kRowBytes;
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
+    for (int kk = 0; kk < KSTEPS; ++kk) {
+#pragma unroll
+      for (int j = 0; j < kPerStep; ++j) request_one(next_tile, next_stage, kk * kPerStep + j);
       const uint32_t pos = ((uint32_t)(kk * 2 + (lane >> 5)) ^ swz) * 16;
       bf16x8 af[WM], bfr[WN];
 #pragma unroll
@@ -148,14 +177,15 @@ __global__ __launch_bounds__(kGemmThreads, 2) void k_gemm_nt(GemmArgs g) {
 #pragma unroll
         for (int j = 0; j < WN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
-  // K tiles of 32 inside this split
+  // K tiles of BK inside this split
   const uint32_t nk = min(g.K / kKUnit - kt0, g.k_tiles_per_split) * (kKUnit / BK);
   // Requests run kStages - 1 tiles ahead.  Near the end the last tile is requested again (into a stage nobody
   // reads any more), so that every iteration issues the same number of loads and "all but the newest
-  // (kStages - 1) * (LA + LB) loads have landed" always means "tile i has landed".
+  // (kStages - 2) * (LA + LB) loads have landed" always means "tile i has landed".
 #pragma unroll
   for (int t = 0; t < kStages - 1; ++t) request(min((uint32_t)t, nk - 1), t);
   for (uint32_t i = 0; i < nk; ++i) {
@@ -166,9 +196,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void k_gemm_nt(GemmArgs g) {
     // A bare barrier: __syncthreads() would add a fence that waits for every outstanding request.
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    request(min(i + kStages - 1, nk - 1), (i + kStages - 1) % kStages);
-    compute(i % kStages);
-    __builtin_amdgcn_sched_barrier(0);
+    compute(i % kStages, min(i + kStages - 1, nk - 1), (i + kStages - 1) % kStages);
   }
   __syncthreads();  // the epilogue reuses the stages
   __builtin_amdgcn_s_waitcnt(0x0F70);  // the surplus requests of the last iterations must not land on the epilogue's patch
@@ -304,8 +332,10 @@ hipError_t launch_epi(const GemmArgs& g, hipStream_t stream) {
   const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_nt<EPI>),
                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmLdsBytes);
   if (attr != hipSuccess) return attr;
-  const uint32_t tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
-  const uint32_t grid = (tiles + kXcds - 1) / kXcds * kXcds;
+  const uint32_t tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+  const uint32_t nblocks = ((tiles_m + kBlockM - 1) / kBlockM) * ((tiles_n + kBlockN - 1) / kBlockN);
+  const uint32_t grid = nblocks >= kXcds ? (nblocks + kXcds - 1) / kXcds * kXcds * kBlockM * kBlockN  // whole blocks on every XCD
+                                         : (tiles_m * tiles_n + kXcds - 1) / kXcds * kXcds;
   const uint32_t splits = (g.K / kKUnit + g.k_tiles_per_split - 1) / g.k_tiles_per_split;
   hipLaunchKernelGGL(k_gemm_nt<EPI>, dim3(grid, splits), dim3(kGemmThreads), kGemmLdsBytes, stream, g);
   return hipGetLastError();
