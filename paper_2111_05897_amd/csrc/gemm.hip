@@ -6,9 +6,11 @@
 // each, i.e. 4x2 MFMA tiles of v_mfma_f32_32x32x16_bf16 (lane l feeds row/column l%32 with the 8
 // consecutive k values starting at 8*(l/32)).  K is walked in steps of 64 through two LDS stages that
 // global_load_lds_dwordx4 fills directly (no staging registers, whole 128-byte lines per row), one tile
-// ahead of the products; rows are unpadded and XOR-swizzled against bank conflicts.  Workgroups are numbered so that
-// the ones running together on an XCD cover a compact block of tiles and share their A and Bt strips in
-// that XCD's L2.
+// ahead of the products; rows are unpadded and XOR-swizzled against bank conflicts.  The loop over K is rotated: its
+// one barrier per tile sits in front of the tile's last k-step, whose products cover what follows the barrier (the
+// requests for the tile after next and the first fragment reads of the next tile).  Workgroups are numbered so that
+// the ones running together on an XCD cover a compact block of tiles and share their A and Bt strips in that XCD's
+// L2, and XCDs that run at the same time share strips through the memory-side cache.
 #include "device_utils.h"
 #include "launch.h"
 
@@ -149,54 +151,67 @@ __global__ __launch_bounds__(kGemmThreads, 2) void k_gemm_nt(GemmArgs g) {
   };
   // fragment rows are base + lane % 32 with base a multiple of 32, so swz(row) depends on the lane only
   const uint32_t swz = (uint32_t)(((lane & 31) >> SWZ_SHIFT) & (CPR - 1));
-  static_assert((kStages - 2) * (LA + LB) <= 15, "the wait below encodes its count in four bits");
-  // The products of one staged tile, with the requests for the next tile (into next_stage) issued between them: a
-  // k-step's share of the requests goes out in front of that k-step's fragment reads.  Issued in one burst after the
-  // barrier, the 64 wave instructions of a tile (512 cache lines) queue up in front of the L1 and hold the waves at
-  // the issue of their later requests, so that the products start late (measured: 1.07 -> 1.11 PFLOP/s).
+  static_assert(LA + LB <= 15, "the wait in the K loop encodes its count in four bits");
+  // The K loop is rotated so that its one barrier per tile has work behind it.  Fragments are read one k-step ahead of
+  // the products (two register sets).  When the products of the last-but-one k-step of tile i have been issued, the
+  // stage of tile i has been read for the last time (the reads of its last k-step went out in front of those
+  // products), and the wave waits for its part of tile i + 1 and meets the others at the barrier.  Behind the barrier:
+  // the requests for tile i + 2 into the stage just vacated, the fragment reads of the first k-step of tile i + 1,
+  // and the products of the last k-step of tile i, which cover the latency of those reads.  (With the barrier at the
+  // top of a tile, all eight waves stand behind it with empty hands until the first fragments arrive from the LDS.)
   constexpr int KSTEPS = BK / 16;
-  constexpr int kPerStep = (LA + LB) / KSTEPS;
-  static_assert((LA + LB) % KSTEPS == 0, "requests per k-step");
-  auto compute = [&](int stage, uint32_t next_tile, int next_stage) {
+  static_assert(KSTEPS == 4 && kStages == 2, "the rotation below is written out for four k-steps and two stages");
+  bf16x8 af[2][WM], bfr[2][WN];
+  auto read_frags = [&](int stage, int kk, int set) {
     const char* As = lds_bytes + stage * kStageBytes;
     const char* Bs = As + BM * kRowBytes;
+    const uint32_t pos = ((uint32_t)(kk * 2 + (lane >> 5)) ^ swz) * 16;
 #pragma unroll
-    for (int kk = 0; kk < KSTEPS; ++kk) {
+    for (int i = 0; i < WM; ++i)
+      af[set][i] = *reinterpret_cast<const bf16x8*>(As + (wm * 32 * WM + i * 32 + (lane & 31)) * kRowBytes + pos);
 #pragma unroll
-      for (int j = 0; j < kPerStep; ++j) request_one(next_tile, next_stage, kk * kPerStep + j);
-      const uint32_t pos = ((uint32_t)(kk * 2 + (lane >> 5)) ^ swz) * 16;
-      bf16x8 af[WM], bfr[WN];
+    for (int j = 0; j < WN; ++j)
+      bfr[set][j] = *reinterpret_cast<const bf16x8*>(Bs + (wn * 32 * WN + j * 32 + (lane & 31)) * kRowBytes + pos);
+  };
+  // products of one k-step from register set `set`; behind the first of them (whose operands are then the only LDS
+  // reads outstanding, so that the wait in front of it is exact) goes `between`, the next k-step's fragment reads
+  auto products = [&](int set, auto between) {
 #pragma unroll
-      for (int i = 0; i < WM; ++i)
-        af[i] = *reinterpret_cast<const bf16x8*>(As + (wm * 32 * WM + i * 32 + (lane & 31)) * kRowBytes + pos);
+    for (int i = 0; i < WM; ++i)
 #pragma unroll
-      for (int j = 0; j < WN; ++j)
-        bfr[j] = *reinterpret_cast<const bf16x8*>(Bs + (wn * 32 * WN + j * 32 + (lane & 31)) * kRowBytes + pos);
-#pragma unroll
-      for (int i = 0; i < WM; ++i)
-#pragma unroll
-        for (int j = 0; j < WN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
+      for (int j = 0; j < WN; ++j) {
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][i], bfr[set][j], acc[i][j], 0, 0, 0);
+        if (i == 0 && j == 0) {
+          __builtin_amdgcn_sched_barrier(0);
+          between();
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    __builtin_amdgcn_sched_barrier(0);
   };
 
   // K tiles of BK inside this split
   const uint32_t nk = min(g.K / kKUnit - kt0, g.k_tiles_per_split) * (kKUnit / BK);
-  // Requests run kStages - 1 tiles ahead.  Near the end the last tile is requested again (into a stage nobody
-  // reads any more), so that every iteration issues the same number of loads and "all but the newest
-  // (kStages - 2) * (LA + LB) loads have landed" always means "tile i has landed".
-#pragma unroll
-  for (int t = 0; t < kStages - 1; ++t) request(min((uint32_t)t, nk - 1), t);
+  // Tile 0 is awaited up front.  Past the end the last tile is requested (and its first fragments read) again, into a
+  // stage nobody multiplies from any more, so that every iteration is the same.
+  request(0, 0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_sched_barrier(0);
+  request(min(1u, nk - 1), 1);
+  read_frags(0, 0, 0);
   for (uint32_t i = 0; i < nk; ++i) {
-    // this wave's part of tile i has landed (all but its newest (kStages - 2) * (LA + LB) requests are done) ...
-    __builtin_amdgcn_s_waitcnt(0x0F70 | ((kStages - 2) * (LA + LB)));  // vmcnt only
-    // ... and so has everybody else's; also, everybody has finished reading the stage that is requested next
-    // (its fragments were consumed by the products above, which the wave issued before arriving here).
-    // A bare barrier: __syncthreads() would add a fence that waits for every outstanding request.
+    const int stage = (int)(i % kStages);
+    products(0, [&] { read_frags(stage, 1, 1); });
+    products(1, [&] { read_frags(stage, 2, 0); });
+    products(0, [&] { read_frags(stage, 3, 1); });
+    // this wave's part of tile i + 1 has landed and its reads of tile i are complete; the barrier makes both true of
+    // everybody.  A bare barrier: __syncthreads() would add a fence of its own.
+    __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) and lgkmcnt(0)
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    compute(i % kStages, min(i + kStages - 1, nk - 1), (i + kStages - 1) % kStages);
+    request(min(i + 2, nk - 1), stage);
+    products(1, [&] { read_frags(stage ^ 1, 0, 0); });
   }
   __syncthreads();  // the epilogue reuses the stages
   __builtin_amdgcn_s_waitcnt(0x0F70);  // the surplus requests of the last iterations must not land on the epilogue's patch
