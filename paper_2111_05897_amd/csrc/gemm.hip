@@ -160,6 +160,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void k_gemm_nt(GemmArgs g) {
   // and the products of the last k-step of tile i, which cover the latency of those reads.  (With the barrier at the
   // top of a tile, all eight waves stand behind it with empty hands until the first fragments arrive from the LDS.)
   constexpr int KSTEPS = BK / 16;
+  static_assert(LA + LB <= WM * WN, "one request behind every product of a k-step");
   static_assert(KSTEPS == 4 && kStages == 2, "the rotation below is written out for four k-steps and two stages");
   bf16x8 af[2][WM], bfr[2][WN];
   auto read_frags = [&](int stage, int kk, int set) {
@@ -181,13 +182,10 @@ __global__ __launch_bounds__(kGemmThreads, 2) void k_gemm_nt(GemmArgs g) {
 #pragma unroll
       for (int j = 0; j < WN; ++j) {
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][i], bfr[set][j], acc[i][j], 0, 0, 0);
-        if (i == 0 && j == 0) {
-          __builtin_amdgcn_sched_barrier(0);
-          between();
-          __builtin_amdgcn_sched_barrier(0);
-        }
+        __builtin_amdgcn_sched_barrier(0);
+        between(i * WN + j);
+        __builtin_amdgcn_sched_barrier(0);
       }
-    __builtin_amdgcn_sched_barrier(0);
   };
 
   // K tiles of BK inside this split
@@ -202,16 +200,19 @@ __global__ __launch_bounds__(kGemmThreads, 2) void k_gemm_nt(GemmArgs g) {
   read_frags(0, 0, 0);
   for (uint32_t i = 0; i < nk; ++i) {
     const int stage = (int)(i % kStages);
-    products(0, [&] { read_frags(stage, 1, 1); });
-    products(1, [&] { read_frags(stage, 2, 0); });
-    products(0, [&] { read_frags(stage, 3, 1); });
+    products(0, [&](int m) { if (m == 0) read_frags(stage, 1, 1); });
+    products(1, [&](int m) { if (m == 0) read_frags(stage, 2, 0); });
+    products(0, [&](int m) { if (m == 0) read_frags(stage, 3, 1); });
     // this wave's part of tile i + 1 has landed and its reads of tile i are complete; the barrier makes both true of
     // everybody.  A bare barrier: __syncthreads() would add a fence of its own.
     __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) and lgkmcnt(0)
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    request(min(i + 2, nk - 1), stage);
-    products(1, [&] { read_frags(stage ^ 1, 0, 0); });
+    const uint32_t refill = min(i + 2, nk - 1);
+    products(1, [&](int m) {  // the next tile's first fragments early, the requests one behind each product
+      if (m == 0) read_frags(stage ^ 1, 0, 0);
+      if (m < LA + LB) request_one(refill, stage, m);
+    });
   }
   __syncthreads();  // the epilogue reuses the stages
   __builtin_amdgcn_s_waitcnt(0x0F70);  // the surplus requests of the last iterations must not land on the epilogue's patch
