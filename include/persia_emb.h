@@ -92,7 +92,9 @@ typedef struct {
  * init:  element d of row r of table t starts at lo + (hi-lo) * k / 2^24, k = the top 24 bits of
  *        mix64(mix64(init_seed + (t+1)*0x9E3779B97F4A7C15) + r*dim + d), evaluated as
  *        float(k - 2^23) * ((hi-lo) * 2^-24) + (hi+lo)/2 with separate fp32 multiply and add.
- * max_batch / max_ids bound batch_size and num_ids of every later call (workspace sizing). */
+ * max_batch / max_ids bound batch_size and num_ids of every later call (workspace sizing): max_ids < 2^31,
+ * max_batch * num_slots < 2^31 and, with more than one table, max_batch * pooled width < 2^34 floats (the sorted index form
+ * carries the position of a bag's gradient in d_pooled in 32 bits). */
 typedef struct {
   uint32_t num_tables;
   uint32_t num_slots;

@@ -88,11 +88,8 @@ struct TileArgs {
   const uint32_t* bags;
   uint32_t n;
   const float* d_pooled;
-  uint32_t S, width;
-  uint32_t s_mul, s_shift;  // bag / S as a multiply-high and shifts (div_by_S below)
-  const uint32_t* slot_col;
-  int uniform;            // 1: gradient of payload g at g * D (one table: the payload is the bag index)
-  int position;           // 1: the payload is the gradient's position in d_pooled in units of 4 floats
+  int position;           // 1: the payload is the gradient's position in d_pooled in units of 4 floats (several
+                          // tables); 0: it is the bag index, and the gradient of bag g is at g * D (one table)
   double* partials;
   uint32_t pstride;
   const uint32_t* range;
@@ -105,21 +102,9 @@ struct TileArgs {
   uint32_t call;
 };
 
-// n / S for any 32-bit n, with the constants the host prepared for S (round-up method of Granlund and
-// Montgomery: S = 1 is s_mul = 0, s_shift = 0, where the formula below gives n itself).  The division instruction
-// sequence the compiler emits for a run-time divisor is about twenty instructions, paid per entry.
-__device__ __forceinline__ uint32_t div_by_S(const TileArgs& a, uint32_t n) {
-  const uint32_t t = __umulhi(a.s_mul, n);
-  return (t + ((n - t) >> (a.s_shift ? 1 : 0))) >> (a.s_shift ? a.s_shift - 1 : 0);
-}
-
 template <int D>
-__device__ __forceinline__ const float* grad_ptr(const TileArgs& a, uint32_t bag, int lane) {
-  if (a.uniform) return a.d_pooled + (size_t)bag * D + lane * 4;
-  if (a.position) return a.d_pooled + (size_t)bag * 4 + lane * 4;
-  const uint32_t b = div_by_S(a, bag);
-  const uint32_t s = bag - b * a.S;
-  return a.d_pooled + (size_t)b * a.width + a.slot_col[s] + lane * 4;
+__device__ __forceinline__ const float* grad_ptr(const TileArgs& a, uint32_t payload, int lane) {
+  return a.d_pooled + (size_t)payload * (a.position ? 4 : D) + lane * 4;
 }
 
 template <typename T, int D, int OPT>
@@ -486,16 +471,6 @@ hipError_t launch_tile_reduce_update(const TableView& t, const BackwardArgs& b, 
   a.bags = b.bags;
   a.n = b.n;
   a.d_pooled = b.d_pooled;
-  a.S = b.S;
-  {  // l = ceil(log2 S), m = floor(2^32 (2^l - S) / S) + 1
-    uint32_t l = 0;
-    while ((1ull << l) < b.S) ++l;
-    a.s_shift = l;
-    a.s_mul = l ? (uint32_t)((((1ull << l) - b.S) << 32) / b.S + 1) : 0u;
-  }
-  a.width = b.width;
-  a.slot_col = b.slot_col;
-  a.uniform = b.uniform;
   a.position = b.payload_is_position;
   a.partials = b.partials;
   a.pstride = b.pstride;

@@ -83,7 +83,6 @@ struct emb_ctx {
   float lr = 0, eps = 0;
   int key_bits = 1;
   int sort_max_bits = 8;  // 9-bit digits save a pass at 26 key bits but scatter in shorter runs: measured slower (scatter 0.260 vs 0.225 ms)
-  int uniform = 0;
   uint32_t payload_width = 0;        // != 0: the sort's payload is the gradient's position in d_pooled / 4, not the bag
   std::vector<uint32_t> slot_col_host;
   uint32_t pstride = 0;
@@ -299,10 +298,15 @@ static int emb_create_impl(const emb_config* cfg, const uint64_t* cache_rows, em
       if (cache_rows[t] < need) return fail(nullptr, EMB_EINVAL, "cache_rows must be at least min(rows, max_ids)");
     }
   }
+  uint64_t pooled_width = 0;
   for (uint32_t s = 0; s < cfg->num_slots; ++s) {
     if (cfg->slots[s].table >= cfg->num_tables) return fail(nullptr, EMB_EINVAL, "slot refers to a missing table");
     if (cfg->slots[s].reserved != 0) return fail(nullptr, EMB_EINVAL, "slot.reserved must be 0");
+    pooled_width += cfg->tables[cfg->slots[s].table].dim;
   }
+  // with several tables the sort carries the position of a bag's gradient in d_pooled, in units of 4 floats, in 32 bits
+  if (cfg->num_tables > 1 && (uint64_t)cfg->max_batch * pooled_width / 4 >= (1ull << 32))
+    return fail(nullptr, EMB_EINVAL, "max_batch * pooled width must be < 2^34 floats when there are several tables");
   int ndev = 0;
   hipError_t e = hipGetDeviceCount(&ndev);
   if (e != hipSuccess) return fail_hip(nullptr, "hipGetDeviceCount", e);
@@ -337,7 +341,6 @@ static int emb_create_impl(const emb_config* cfg, const uint64_t* cache_rows, em
   ctx->eps = cfg->eps;
   ctx->key_bits = bit_length(total_rows - 1);
   if (ctx->key_bits < 1) ctx->key_bits = 1;
-  ctx->uniform = cfg->num_tables == 1;
   ctx->pstride = max_dim;
 
 #define CK(call, what)                                         \
@@ -439,8 +442,7 @@ static int emb_create_impl(const emb_config* cfg, const uint64_t* cache_rows, em
   }
   ctx->width = col;
   ctx->slot_col_host = s_col;
-  // several tables: the payload carries the gradient's position (in units of 4 floats) if that fits 32 bits
-  if (cfg->num_tables > 1 && (uint64_t)cfg->max_batch * col / 4 < (1ull << 32)) ctx->payload_width = col;
+  if (cfg->num_tables > 1) ctx->payload_width = col;  // several tables: the payload carries the gradient's position
   {
     uint64_t *p_salt = nullptr, *p_rows = nullptr, *p_mask = nullptr;
     uint32_t *p_kb = nullptr, *p_col = nullptr;
@@ -739,10 +741,6 @@ static int backward_update_with(emb_ctx* ctx, const Workspace& ws, const emb_bat
   a.bags = ws.bags[src];
   a.n = n;
   a.d_pooled = d_pooled;
-  a.S = ctx->S;
-  a.width = ctx->width;
-  a.slot_col = ctx->slots.col;
-  a.uniform = ctx->uniform;
   a.payload_is_position = ctx->payload_width != 0;
   a.partials = ws.partials;
   a.pstride = ctx->pstride;

@@ -139,13 +139,12 @@ hipError_t launch_unique(const uint32_t* keys, uint32_t n, uint32_t* blk_heads, 
 // ---- backward.hip ----
 struct BackwardArgs {
   const uint32_t* keys;      // sorted, [n]
-  const uint32_t* bags;      // sorted with the keys, [n]: bag indices, or gradient positions (payload_is_position)
-  int payload_is_position;   // the payload is (sample * width + col(slot)) / 4 (launch_build_keys with payload_width)
+  const uint32_t* bags;      // sorted with the keys, [n]: the payload launch_build_keys wrote
+  int payload_is_position;   // 1: the payload is (sample * width + col(slot)) / 4, the gradient's position in d_pooled in
+                             // units of 4 floats (several tables); 0: it is the bag index and every slot has this
+                             // table's dim, so the gradient of bag g starts at g * dim (one table)
   uint32_t n;
   const float* d_pooled;     // [B, width]
-  uint32_t S, width;
-  const uint32_t* slot_col;  // device [S]
-  int uniform;               // every slot has this table's dim: gradient of a bag starts at bag*dim
   double* partials;          // [2 * ntiles, pstride] fp64 partial sums of segments that cross tile edges
   uint32_t pstride;
   const uint32_t* range;     // device [2]: occurrences [range[0], range[1]) belong to this table; null = all

@@ -72,6 +72,7 @@ def test_argument_validation_happens_on_the_host_before_any_device_call():
         "max_batch 0": _config(b, [(100, 8, 0)], [(0, 1)], max_batch=0),
         "max_ids too large": _config(b, [(100, 8, 0)], [(0, 1)], max_ids=1 << 31),
         "bags overflow": _config(b, [(100, 8, 0)], [(0, 1)] * 4096, max_batch=1 << 20),
+        "gradient positions overflow": _config(b, [(100, 128, 0), (100, 128, 0)], [(0, 1), (1, 2)] * 500, max_batch=1 << 20),
     }
     for name, cfg in bad.items():
         assert lib.emb_create(C.byref(cfg), C.byref(h)) == b.EMB_EINVAL, name
