@@ -73,20 +73,49 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(sizeof(T
   constexpr int GPB = kBlock / LANES;       // bags per workgroup
   constexpr int CH = LANES > 8 ? LANES : 8; // ids the group fetches and hashes per round, one or more per lane
   constexpr int IPL = CH / LANES;           // ids per lane per round
-  constexpr int RIF = 8;                    // row loads in flight per lane
+  constexpr int RIF = 8;                    // row loads in flight per lane (four: 0.418 -> 0.438 ms at config 2)
   static_assert(LANES >= 1 && LANES <= 64 && (LANES & (LANES - 1)) == 0, "row must map onto a power-of-two lane group");
   static_assert(CH % RIF == 0 && CH % LANES == 0, "round geometry");
   const uint32_t lb = blockIdx.x * GPB + threadIdx.x / LANES;
   const int lane = threadIdx.x % LANES;
+  // What belongs to a bag -- its stretch of the ids, its slot's salt, where its pooled vector goes -- is fetched by one
+  // thread per bag and handed to the bag's lanes through LDS: fetched by every lane, these five loads were a third of
+  // the vector-memory instructions a wave issues for a bag of 8 rows.  (One lane per bag: nothing to share.)
+  constexpr bool kStage = LANES >= 4;
+  __shared__ int s_beg[kStage ? GPB : 1], s_end[kStage ? GPB : 1];
+  __shared__ uint64_t s_salt[kStage ? GPB : 1], s_out[kStage ? GPB : 1];
+  int beg = 0, end = 0;
+  uint64_t salt = 0, out_at = 0;
+  auto fetch_bag = [&](uint32_t l) {  // bag number l of this launch
+    if (l >= a.n_local_bags) return;  // beg = end: nothing to read
+    const uint32_t b = l / a.n_slots_t;
+    const uint32_t slot = a.slot_list[l - b * a.n_slots_t];
+    const size_t bag = (size_t)b * a.S + slot;
+    beg = INDEXED ? (int)a.bag_beg[bag] : a.offsets[bag];
+    end = INDEXED ? (int)a.bag_end[bag] : a.offsets[bag + 1];
+    beg = beg < 0 ? 0 : beg;
+    end = end > (int)a.num_ids ? (int)a.num_ids : end;  // beg >= end: an empty bag
+    salt = a.slot_salt[slot];
+    out_at = (uint64_t)b * a.width + a.slot_col[slot];
+  };
+  if constexpr (kStage) {
+    if (threadIdx.x < GPB) {
+      fetch_bag(blockIdx.x * GPB + threadIdx.x);
+      s_beg[threadIdx.x] = beg;
+      s_end[threadIdx.x] = end;
+      s_salt[threadIdx.x] = salt;
+      s_out[threadIdx.x] = out_at;
+    }
+    __syncthreads();
+    const int g = threadIdx.x / LANES;
+    beg = s_beg[g];
+    end = s_end[g];
+    salt = s_salt[g];
+    out_at = s_out[g];
+  } else {
+    fetch_bag(lb);
+  }
   if (lb >= a.n_local_bags) return;         // whole groups leave together
-  const uint32_t b = lb / a.n_slots_t;
-  const uint32_t slot = a.slot_list[lb - b * a.n_slots_t];
-  const size_t bag = (size_t)b * a.S + slot;
-  int beg = INDEXED ? (int)a.bag_beg[bag] : a.offsets[bag];
-  int end = INDEXED ? (int)a.bag_end[bag] : a.offsets[bag + 1];
-  beg = beg < 0 ? 0 : beg;
-  end = end > (int)a.num_ids ? (int)a.num_ids : end;  // beg >= end: an empty bag
-  const uint64_t salt = a.slot_salt[slot];
   const T* __restrict__ base = reinterpret_cast<const T*>(a.w) + lane * VEC;
   const T* __restrict__ zero_row = reinterpret_cast<const T*>(a.zeros) + lane * VEC;
   const uint64_t* __restrict__ ids = a.ids;
@@ -128,7 +157,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(sizeof(T
       if (j0 < cnt) {  // same for all lanes of the group
         // Every one of the RIF loads is issued, without a branch: past the bag's end it reads a row of zeros (one
         // cached line).  Straight-line code keeps all RIF requests in flight and the widening to fp64 behind them;
-        // with a branch per row the compiler widens inside the branch and waits for every load in turn.
+        // with a branch per row -- or one scalar branch around the second half of the loads, for waves none of whose
+        // bags reaches it -- the compiler widens between the loads and waits for them in turn.
         Raw16<T> r[RIF];
 #pragma unroll
         for (int jj = 0; jj < RIF; ++jj) {
@@ -142,7 +172,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(sizeof(T
     }
   }
 
-  float* out = a.pooled + (size_t)b * a.width + a.slot_col[slot] + lane * VEC;
+  float* out = a.pooled + out_at + lane * VEC;
 #pragma unroll
   for (int e = 0; e < VEC; e += 4)
     if (a.stream_out) {  // this launch writes whole pooled rows: streamed, nothing re-reads them here
