@@ -444,7 +444,8 @@ def main() -> int:
     e1.record()
     torch.cuda.synchronize()
     est_ms = max(e0.elapsed_time(e1), 1e-3)
-    reps = int(min(max(args.min_reps, np.ceil(args.min_seconds * 1e3 / est_ms)), args.max_reps))
+    # (+1: the sizing repetition is often a little slower than the settled ones, and the region must not end short)
+    reps = int(min(max(args.min_reps, np.ceil(args.min_seconds * 1e3 / est_ms) + 1), args.max_reps))
     cur = torch.cuda.current_stream()
     evs = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
     ids_rep = []
